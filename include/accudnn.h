@@ -1,0 +1,212 @@
+/*
+ * accudnn.h - C ABI of the MI355X-native training-step library.
+ *
+ * One context trains one network on one GPU under a device-memory budget, the
+ * problem the paper states in Sec. 3 ("given a certain UDNN and hardware
+ * configuration ... memory budget"): the layer list is unfolded into 2N steps
+ * (Sec. 4.1), feature maps are the swap targets, and the runtime knows four
+ * operations: allocate, release, offload, prefetch (Sec. 4.1, Sec. 6).
+ *
+ * Conventions
+ *  - Every function returns ACC_OK (0) or a negative acc_status; nothing throws
+ *    or aborts.  acc_last_error() gives the text of the last failure of a context.
+ *  - "host" pointers are ordinary or pinned host memory, "device" pointers are
+ *    HIP device memory.  The caller owns every buffer it passes in and keeps the
+ *    pool, the host arena and the streams alive until acc_destroy().
+ *  - The library calls no hipMalloc: all device data (weights, gradients, feature
+ *    maps, workspace, the input batch) lives inside the caller's pool, so the
+ *    budget is a hard cap by construction (Sec. 6: one buffer pool of the size of
+ *    the budget, sub-allocated at run time).
+ *  - Activations are NHWC fp32 on the device, filters O-H-W-I; the host-side
+ *    weight interface uses the framework-neutral OIHW order and converts.
+ *  - One context per thread; calls on one context must not overlap.
+ */
+#ifndef ACCUDNN_H
+#define ACCUDNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ACC_OK = 0,
+  ACC_EINVAL = -1,       /* malformed argument or unsupported network topology        */
+  ACC_EUNTRAINABLE = -2, /* budget below the layer-wise peak: k > k_max (Algorithm 2) */
+  ACC_EPOOL = -3,        /* pool smaller than budget / static data do not fit         */
+  ACC_EHOSTMEM = -4,     /* pinned host arena too small for the swapped maps          */
+  ACC_EHIP = -5,         /* a HIP call failed; text in acc_last_error()               */
+  ACC_ESTATE = -6        /* call out of order (e.g. train_step before plan_swaps)     */
+} acc_status;
+
+/* layer kinds of a network record */
+enum { ACC_CONV = 0, ACC_BN = 1, ACC_RELU = 2, ACC_ADD = 3, ACC_MAXPOOL = 4, ACC_GAP = 5,
+       ACC_FC = 6, ACC_SOFTMAX_CE = 7 };
+enum { ACC_F32 = 0, ACC_BF16 = 1 };
+/* planner modes: keep everything / swap every feature map (the "naive" strategy of
+ * Sec. 4.1) / performance-model-guided choice (the "dynamic" strategy, Sec. 4.1, 4.4, 5.1) */
+enum { ACC_PLAN_NONE = 0, ACC_PLAN_NAIVE_ALL = 1, ACC_PLAN_DYNAMIC = 2 };
+enum { ACC_LOC_HOST = 0, ACC_LOC_DEVICE = 1 };
+
+/* One layer, in execution order.  in0/in1: index of the producing layer, -1 = the
+ * network input.  conv: cin,cout,r,s,stride,pad (no bias).  bn: cin channels,
+ * parameters [gamma|beta], eps 1e-5, minibatch statistics.  maxpool: r,s,stride,pad.
+ * fc: cin,cout, parameters [W cout x cin | b cout].  softmax_ce: in0 = logits. */
+typedef struct {
+  int32_t kind, in0, in1, cin, cout, r, s, stride, pad;
+} acc_layer;
+
+/* Device pool, pinned host arena and the three streams of Sec. 6 (compute,
+ * swap-out, swap-in; hipStream_t passed as void*).  With a NULL acc_resources the
+ * context is planning-only: everything but calibrate / train_step / weights works. */
+typedef struct {
+  void* pool;        /* device */
+  size_t pool_bytes;
+  void* host;        /* pinned host */
+  size_t host_bytes;
+  void* s_compute;
+  void* s_out;
+  void* s_in;
+} acc_resources;
+
+typedef struct {
+  int32_t n_steps;          /* 2N (+1 for the weight update)                              */
+  int32_t n_maps;           /* feature maps that live from forward into backward          */
+  int32_t n_swapped;        /* of those, how many are offloaded and prefetched            */
+  int32_t n_instr;          /* length of the instruction list the executor runs           */
+  uint64_t bytes_swapped;   /* per direction, per step                                    */
+  uint64_t bytes_maps;      /* retention set at this minibatch                            */
+  uint64_t static_bytes;    /* weights, gradients, saved statistics, scratch              */
+  uint64_t peak_bytes;      /* predicted pool high-water mark, static part included       */
+  uint64_t layer_peak_bytes;/* M_peak(k): high-water mark with every map swapped          */
+  uint64_t noswap_peak_bytes;/* high-water mark with no map swapped                       */
+  uint64_t host_bytes;      /* pinned host bytes the plan uses                            */
+  double t_compute;         /* Eq. 2: sum of per-step compute times, seconds              */
+  double t_iter;            /* predicted iteration time with stalls, seconds              */
+  double t_stall;           /* predicted total stall, seconds                             */
+  double plan_ms;           /* wall time spent planning                                   */
+} acc_plan_summary;
+
+typedef struct {
+  int32_t kind;             /* internal step kind (see acc_step_kind_name)                */
+  int32_t layer;            /* layer record this step belongs to                          */
+  int32_t backward;         /* 0 forward, 1 backward, 2 update                            */
+  int32_t reserved;
+  double flops;             /* at the planned minibatch (Eq. 1: linear in k)              */
+  double t_compute;         /* cost-model time, seconds                                   */
+  double t_ready;           /* Algorithm 1: data on the GPU and memory allocated          */
+  double t_start, t_end;    /* simulated execution on the compute stream                  */
+} acc_step_info;
+
+typedef struct {
+  int32_t kind;             /* 0 activation, 1 gradient, 2 workspace, 3 input staging     */
+  int32_t producer_step, last_fwd_step, first_bwd_step, last_step;
+  int32_t is_map;           /* lives from forward into backward (swappable)               */
+  int32_t swapped;
+  int32_t reserved;
+  uint64_t bytes;           /* at the planned minibatch                                   */
+  uint64_t offset;          /* pool offset of the (first) allocation                      */
+  uint64_t offset2;         /* pool offset after prefetch, if swapped                     */
+  uint64_t host_offset;     /* slot in the pinned arena, if swapped                       */
+} acc_tensor_info;
+
+typedef struct {
+  double step_ms;           /* last train_step: events on the compute stream              */
+  double host_issue_ms;     /* last train_step: host time to issue all work               */
+  uint64_t peak_pool_bytes; /* high-water mark actually touched (static part included)    */
+  uint64_t bytes_out, bytes_in; /* offloaded / prefetched in the last step                */
+  double d2h_ms, h2d_ms;    /* summed copy durations (only when profiling is enabled)     */
+  uint64_t steps_run;
+} acc_stats;
+
+typedef struct acc_ctx acc_ctx;
+
+/* ---- context ---------------------------------------------------------------------- */
+/* Builds the fused step list and the tensor table (static information of Sec. 4.2).
+ * With resources: places weights / gradients / statistics at the bottom of the pool. */
+int acc_create(const acc_layer* layers, int n_layers, int in_c, int in_h, int in_w, int dtype,
+               const acc_resources* res, acc_ctx** out);
+void acc_destroy(acc_ctx* ctx);
+const char* acc_last_error(const acc_ctx* ctx);   /* ctx may be NULL: last create error */
+const char* acc_step_kind_name(int kind);
+
+/* fp32 master weights of one layer, host side, OIHW / [gamma|beta] / [W|b]; n = element
+ * count and must match.  Blocking.  get_grads returns d(loss)/d(weights) of the last step. */
+int acc_set_weights(acc_ctx* ctx, int layer, const float* host_w, size_t n);
+int acc_get_weights(acc_ctx* ctx, int layer, float* host_w, size_t n);
+int acc_get_grads(acc_ctx* ctx, int layer, float* host_g, size_t n);
+/* forward output of a layer that the last plan keeps (a retained map), NCHW, host.
+ * Valid after train_step only for maps that were not swapped; parity/debug hook. */
+int acc_param_count(const acc_ctx* ctx, int layer, size_t* n);
+
+/* ---- cost model (dynamic information, Sec. 4.2; Eq. 2 and Eq. 5) ------------------- */
+/* Times every step's kernels at each minibatch in ks[] with events on the compute
+ * stream, and D2H / H2D copies of a few sizes on the side streams.  Needs resources. */
+int acc_calibrate(acc_ctx* ctx, const int* ks, int nk);
+/* Synthetic cost model for planning without a GPU: step time = launch_s + flops /
+ * flops_per_s + bytes / bytes_per_s (flops for conv/fc steps, touched bytes for the
+ * rest); copies run at d2h / h2d bytes per second plus copy_latency_s each. */
+int acc_set_cost_model(acc_ctx* ctx, double flops_per_s, double bytes_per_s, double launch_s,
+                       double d2h_bytes_per_s, double h2d_bytes_per_s, double copy_latency_s);
+/* Overrides the cost of single steps (seconds, at the minibatch given to the next
+ * plan_swaps); n must equal the step count.  Used to test Algorithm 1 on hand-built cases. */
+int acc_set_step_times(acc_ctx* ctx, const double* seconds, int n);
+
+/* ---- planning (Algorithm 1, Eq. 4-6, body of Algorithm 2) ------------------------- */
+int acc_plan_swaps(acc_ctx* ctx, int minibatch, size_t budget_bytes, int mode,
+                   acc_plan_summary* out);
+/* Plans with an explicit swap decision per map (maps in producer order; 1 = swap). */
+int acc_plan_explicit(acc_ctx* ctx, int minibatch, size_t budget_bytes, const uint8_t* swap,
+                      int n_maps, acc_plan_summary* out);
+int acc_get_step_count(const acc_ctx* ctx);
+int acc_get_tensor_count(const acc_ctx* ctx);
+int acc_get_step_info(const acc_ctx* ctx, int step, acc_step_info* out);
+int acc_get_tensor_info(const acc_ctx* ctx, int tensor, acc_tensor_info* out);
+/* tensors a step reads / writes (ids into the tensor table); returns the count or <0 */
+int acc_get_step_io(const acc_ctx* ctx, int step, int32_t* reads, int max_reads, int32_t* writes,
+                    int max_writes);
+
+/* ---- execution --------------------------------------------------------------------- */
+/* One forward / backward / SGD step at the planned minibatch.  images: fp32 NCHW,
+ * pinned host (ACC_LOC_HOST) or device (ACC_LOC_DEVICE); labels: int32, host.  Blocks
+ * until the step is done; *loss_out is the mean cross-entropy at the pre-update weights. */
+int acc_train_step(acc_ctx* ctx, const float* images, int images_loc, const int32_t* labels,
+                   float lr, float* loss_out);
+int acc_get_stats(acc_ctx* ctx, acc_stats* out);
+/* profiling = 1 records timing events around every kernel group and copy (slower) */
+int acc_set_profiling(acc_ctx* ctx, int on);
+/* per-step kernel time of the last profiled train_step, milliseconds; n = step count */
+int acc_get_step_times_ms(acc_ctx* ctx, double* ms, int n);
+
+/* ---- single operations on caller-owned device buffers (parity and roofline) ------- */
+/* All pointers device, fp32; x / y / dy / dx NHWC, w / dw O-H-W-I; stream is a
+ * hipStream_t.  workspace may be NULL when workspace_bytes is 0; query the need with
+ * acc_op_conv_workspace().  accumulate != 0 adds into dx instead of overwriting. */
+size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, int r, int s, int stride,
+                             int pad);
+int acc_op_conv_fwd(const float* x, const float* w, float* y, int n, int h, int wd, int cin,
+                    int cout, int r, int s, int stride, int pad, void* stream);
+int acc_op_conv_dgrad(const float* dy, const float* w, float* dx, int n, int h, int wd, int cin,
+                      int cout, int r, int s, int stride, int pad, int accumulate,
+                      void* workspace, size_t workspace_bytes, void* stream);
+int acc_op_conv_wgrad(const float* x, const float* dy, float* dw, int n, int h, int wd, int cin,
+                      int cout, int r, int s, int stride, int pad, void* workspace,
+                      size_t workspace_bytes, void* stream);
+/* y = relu?(gamma*(x-mean)*istd + beta (+ res)); saves mean / istd (c floats each).
+ * workspace: acc_op_bn_workspace(c) bytes. */
+size_t acc_op_bn_workspace(int c);
+int acc_op_bn_fwd(const float* x, const float* gamma, const float* beta, const float* res,
+                  float* y, float* mean, float* istd, int rows, int c, int relu, float eps,
+                  void* workspace, void* stream);
+/* dy is masked by (y > 0) when y != NULL (fused ReLU); when g_out != NULL the masked
+ * gradient is also written there (it may alias dy). */
+int acc_op_bn_bwd(const float* x, const float* dy, const float* y, const float* gamma,
+                  const float* mean, const float* istd, float* dx, float* dgamma, float* dbeta,
+                  float* g_out, int rows, int c, void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACCUDNN_H */

@@ -1,0 +1,305 @@
+// Batch normalisation with minibatch statistics over an NHWC tensor viewed as
+// rows x c, fused with ReLU and with the residual add of a bottleneck block.
+//
+// The work is bandwidth bound, so every kernel reads whole float4 channel groups of
+// consecutive rows (a wave covers 1 KiB of contiguous memory per load).  Reductions
+// over rows run in two fixed-order stages (per-slab partials in double, then one
+// thread per channel adds the slabs in order): no atomics, results do not depend on
+// timing or addresses.
+//
+// workspace layout (bn_workspace_bytes): double part[2][MAX_SLABS][c] | float coef[4][c]
+#include "kernels.h"
+
+namespace acc {
+namespace {
+
+constexpr int MAX_SLABS = 256;  // row slabs of the reduction grid (upper bound)
+constexpr int THREADS = 256;
+constexpr int FIN_CH = 16;      // channels per workgroup of the finishing kernels
+constexpr int FIN_LANES = THREADS / FIN_CH;
+
+struct ReduceShape {
+  int tpr;        // threads across one row (each owns 4 channels)
+  int rpi;        // rows per iteration of a block
+  int col_slices; // grid.y: slices of 1024 channels
+};
+
+__host__ __device__ inline ReduceShape reduce_shape(int c) {
+  ReduceShape s;
+  const int cg = c / 4;
+  s.tpr = cg < THREADS ? cg : THREADS;
+  // tpr need not divide 256: the leftover threads idle
+  s.rpi = THREADS / s.tpr;
+  s.col_slices = (cg + THREADS - 1) / THREADS;
+  return s;
+}
+
+// Sums over the rows of one slab, per channel, of up to two quantities.
+// MODE 0: (x, x*x).   MODE 1: (g, g*xhat) with g = dy * [y > 0] (y optional).
+template <int MODE>
+__global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restrict__ x,
+                                                            const float* __restrict__ dy,
+                                                            const float* __restrict__ y,
+                                                            const float* __restrict__ mean,
+                                                            const float* __restrict__ istd,
+                                                            double* __restrict__ part, long rows,
+                                                            int c, int tpr, int rpi, int slabs) {
+  __shared__ double red[2][THREADS][4];
+  const int tid = threadIdx.x;
+  const int lane_r = tid / tpr;            // which row of the iteration
+  const int lane_c = tid - lane_r * tpr;   // which channel group
+  const int cg = blockIdx.y * THREADS + lane_c;
+  const bool active = lane_r < rpi && cg * 4 < c;
+  const long rows_per_slab = (rows + slabs - 1) / slabs;
+  const long r_lo = (long)blockIdx.x * rows_per_slab;
+  const long r_hi = r_lo + rows_per_slab < rows ? r_lo + rows_per_slab : rows;
+
+  double s0[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0};
+  if (active) {
+    float mu[4] = {0, 0, 0, 0}, is[4] = {0, 0, 0, 0};
+    if (MODE == 1) {
+      const float4 m4 = *reinterpret_cast<const float4*>(mean + cg * 4);
+      const float4 i4 = *reinterpret_cast<const float4*>(istd + cg * 4);
+      mu[0] = m4.x; mu[1] = m4.y; mu[2] = m4.z; mu[3] = m4.w;
+      is[0] = i4.x; is[1] = i4.y; is[2] = i4.z; is[3] = i4.w;
+    }
+#pragma unroll 4
+    for (long r = r_lo + lane_r; r < r_hi; r += rpi) {
+      const size_t off = (size_t)r * c + (size_t)cg * 4;
+      const float4 xv = *reinterpret_cast<const float4*>(x + off);
+      const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
+      if (MODE == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const double d = (double)xs[j];
+          s0[j] += d;
+          s1[j] += d * d;
+        }
+      } else {
+        const float4 gv = *reinterpret_cast<const float4*>(dy + off);
+        float gs[4] = {gv.x, gv.y, gv.z, gv.w};
+        if (y) {
+          const float4 yv = *reinterpret_cast<const float4*>(y + off);
+          const float ys[4] = {yv.x, yv.y, yv.z, yv.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) gs[j] = ys[j] > 0.f ? gs[j] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const double gd = (double)gs[j];
+          s0[j] += gd;
+          s1[j] += gd * (double)((xs[j] - mu[j]) * is[j]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    red[0][tid][j] = s0[j];
+    red[1][tid][j] = s1[j];
+  }
+  __syncthreads();
+  // the first row of threads adds the other rows in order
+  if (lane_r == 0 && cg * 4 < c) {
+    for (int rr = 1; rr < rpi; ++rr) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        s0[j] += red[0][rr * tpr + lane_c][j];
+        s1[j] += red[1][rr * tpr + lane_c][j];
+      }
+    }
+    double* p0 = part + ((size_t)0 * MAX_SLABS + blockIdx.x) * c + (size_t)cg * 4;
+    double* p1 = part + ((size_t)1 * MAX_SLABS + blockIdx.x) * c + (size_t)cg * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      p0[j] = s0[j];
+      p1[j] = s1[j];
+    }
+  }
+}
+
+// Adds the slab partials of FIN_CH channels per workgroup in a fixed order: lane s of a
+// channel adds slabs s, s+FIN_LANES, ...; the channel's first lane then adds the lanes.
+__device__ __forceinline__ void sum_partials(const double* __restrict__ part, int c, int slabs, int ch,
+                                             int s, double (*sh)[FIN_LANES][FIN_CH], double* out0,
+                                             double* out1) {
+  double a0 = 0.0, a1 = 0.0;
+  if (ch < c)
+    for (int k = s; k < slabs; k += FIN_LANES) {
+      a0 += part[((size_t)0 * MAX_SLABS + k) * c + ch];
+      a1 += part[((size_t)1 * MAX_SLABS + k) * c + ch];
+    }
+  const int cl = threadIdx.x % FIN_CH;
+  sh[0][s][cl] = a0;
+  sh[1][s][cl] = a1;
+  __syncthreads();
+  if (s == 0) {
+    for (int k = 1; k < FIN_LANES; ++k) {
+      a0 += sh[0][k][cl];
+      a1 += sh[1][k][cl];
+    }
+  }
+  *out0 = a0;
+  *out1 = a1;
+}
+
+// forward:  mean, istd; coef[0] = scale = gamma*istd, coef[1] = shift = beta - mean*scale
+__global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
+    const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ beta,
+    float* __restrict__ mean, float* __restrict__ istd, float* __restrict__ coef, long rows, int c,
+    float eps, int slabs) {
+  __shared__ double sh[2][FIN_LANES][FIN_CH];
+  const int ch = blockIdx.x * FIN_CH + threadIdx.x % FIN_CH, s = threadIdx.x / FIN_CH;
+  double sum, ss;
+  sum_partials(part, c, slabs, ch, s, sh, &sum, &ss);
+  if (s != 0 || ch >= c) return;
+  const double m = (double)rows;
+  const double mu = sum / m;
+  double var = ss / m - mu * mu;
+  if (var < 0.0) var = 0.0;
+  const double is = 1.0 / sqrt(var + (double)eps);
+  mean[ch] = (float)mu;
+  istd[ch] = (float)is;
+  const double scale = (double)gamma[ch] * is;
+  coef[ch] = (float)scale;
+  coef[c + ch] = (float)((double)beta[ch] - mu * scale);
+}
+
+// backward: dbeta, dgamma; coef[0] = a = gamma*istd, coef[1] = dbeta/m, coef[2] = dgamma/m
+__global__ __launch_bounds__(THREADS) void bn_bwd_finish_kernel(
+    const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ istd,
+    float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef, long rows, int c,
+    int slabs) {
+  __shared__ double sh[2][FIN_LANES][FIN_CH];
+  const int ch = blockIdx.x * FIN_CH + threadIdx.x % FIN_CH, s = threadIdx.x / FIN_CH;
+  double db, dg;
+  sum_partials(part, c, slabs, ch, s, sh, &db, &dg);
+  if (s != 0 || ch >= c) return;
+  dbeta[ch] = (float)db;
+  dgamma[ch] = (float)dg;
+  const double m = (double)rows;
+  coef[ch] = gamma[ch] * istd[ch];
+  coef[c + ch] = (float)(db / m);
+  coef[2 * c + ch] = (float)(dg / m);
+}
+
+// y = relu?(x*scale + shift (+ res)), float4 per thread, grid-stride
+__global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restrict__ x,
+                                                           const float* __restrict__ res,
+                                                           const float* __restrict__ coef,
+                                                           float* __restrict__ y, size_t n4, int c,
+                                                           int relu) {
+  const int cg = c >> 2;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < n4; i += (size_t)gridDim.x * THREADS) {
+    const int g = (int)(i % cg);
+    const float4 xv = reinterpret_cast<const float4*>(x)[i];
+    const float4 sc = reinterpret_cast<const float4*>(coef)[g];
+    const float4 sh = reinterpret_cast<const float4*>(coef + c)[g];
+    float4 o;
+    o.x = fmaf(xv.x, sc.x, sh.x);
+    o.y = fmaf(xv.y, sc.y, sh.y);
+    o.z = fmaf(xv.z, sc.z, sh.z);
+    o.w = fmaf(xv.w, sc.w, sh.w);
+    if (res) {
+      const float4 rv = reinterpret_cast<const float4*>(res)[i];
+      o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
+    }
+    if (relu) {
+      o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f);
+    }
+    reinterpret_cast<float4*>(y)[i] = o;
+  }
+}
+
+// dx = a*(g - dbeta/m - xhat*dgamma/m), g = dy*[y>0]; optionally stores g (may alias dy)
+__global__ __launch_bounds__(THREADS) void bn_bwd_apply_kernel(
+    const float* __restrict__ x, const float* dy, const float* __restrict__ y,
+    const float* __restrict__ mean, const float* __restrict__ istd, const float* __restrict__ coef,
+    float* __restrict__ dx, float* g_out, size_t n4, int c) {
+  const int cg = c >> 2;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < n4; i += (size_t)gridDim.x * THREADS) {
+    const int g = (int)(i % cg);
+    const float4 xv = reinterpret_cast<const float4*>(x)[i];
+    float4 gv = reinterpret_cast<const float4*>(dy)[i];
+    if (y) {
+      const float4 yv = reinterpret_cast<const float4*>(y)[i];
+      gv.x = yv.x > 0.f ? gv.x : 0.f;
+      gv.y = yv.y > 0.f ? gv.y : 0.f;
+      gv.z = yv.z > 0.f ? gv.z : 0.f;
+      gv.w = yv.w > 0.f ? gv.w : 0.f;
+    }
+    const float4 mu = reinterpret_cast<const float4*>(mean)[g];
+    const float4 is = reinterpret_cast<const float4*>(istd)[g];
+    const float4 a = reinterpret_cast<const float4*>(coef)[g];
+    const float4 c1 = reinterpret_cast<const float4*>(coef + c)[g];
+    const float4 c2 = reinterpret_cast<const float4*>(coef + 2 * c)[g];
+    float4 o;
+    o.x = a.x * (gv.x - c1.x - (xv.x - mu.x) * is.x * c2.x);
+    o.y = a.y * (gv.y - c1.y - (xv.y - mu.y) * is.y * c2.y);
+    o.z = a.z * (gv.z - c1.z - (xv.z - mu.z) * is.z * c2.z);
+    o.w = a.w * (gv.w - c1.w - (xv.w - mu.w) * is.w * c2.w);
+    reinterpret_cast<float4*>(dx)[i] = o;
+    if (g_out) reinterpret_cast<float4*>(g_out)[i] = gv;
+  }
+}
+
+// slab count: a function of the shape only, at least 8 rows per thread and slab
+inline int slab_count(long rows, int rpi) {
+  long s = (rows + (long)rpi * 8 - 1) / ((long)rpi * 8);
+  if (s < 1) s = 1;
+  if (s > MAX_SLABS) s = MAX_SLABS;
+  return (int)s;
+}
+
+inline unsigned apply_grid(size_t n4) {
+  const size_t blocks = (n4 + THREADS - 1) / THREADS;
+  const size_t cap = 256 * 16;   // 16 workgroups per CU keep every XCD busy
+  return (unsigned)(blocks < cap ? (blocks ? blocks : 1) : cap);
+}
+
+}  // namespace
+
+size_t bn_workspace_bytes(int c) {
+  return (size_t)2 * MAX_SLABS * c * sizeof(double) + (size_t)4 * c * sizeof(float);
+}
+
+hipError_t bn_forward(const float* x, const float* gamma, const float* beta, const float* res,
+                      float* y, float* mean, float* istd, long rows, int c, int relu, float eps,
+                      void* workspace, hipStream_t st) {
+  if (!x || !gamma || !beta || !y || !mean || !istd || !workspace) return hipErrorInvalidValue;
+  if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  double* part = static_cast<double*>(workspace);
+  float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
+  const ReduceShape rs = reduce_shape(c);
+  const int slabs = slab_count(rows, rs.rpi);
+  hipLaunchKernelGGL(bn_reduce_kernel<0>, dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, nullptr,
+                     nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
+  hipLaunchKernelGGL(bn_fwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
+                     gamma, beta, mean, istd, coef, rows, c, eps, slabs);
+  const size_t n4 = (size_t)rows * c / 4;
+  hipLaunchKernelGGL(bn_apply_kernel, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, res, coef, y, n4, c,
+                     relu);
+  return hipGetLastError();
+}
+
+hipError_t bn_backward(const float* x, const float* dy, const float* y, const float* gamma,
+                       const float* mean, const float* istd, float* dx, float* dgamma, float* dbeta,
+                       float* g_out, long rows, int c, void* workspace, hipStream_t st) {
+  if (!x || !dy || !gamma || !mean || !istd || !dx || !dgamma || !dbeta || !workspace)
+    return hipErrorInvalidValue;
+  if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  double* part = static_cast<double*>(workspace);
+  float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
+  const ReduceShape rs = reduce_shape(c);
+  const int slabs = slab_count(rows, rs.rpi);
+  hipLaunchKernelGGL(bn_reduce_kernel<1>, dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
+                     istd, part, rows, c, rs.tpr, rs.rpi, slabs);
+  hipLaunchKernelGGL(bn_bwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
+                     gamma, istd, dgamma, dbeta, coef, rows, c, slabs);
+  const size_t n4 = (size_t)rows * c / 4;
+  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, dy, y, mean, istd,
+                     coef, dx, g_out, n4, c);
+  return hipGetLastError();
+}
+
+}  // namespace acc

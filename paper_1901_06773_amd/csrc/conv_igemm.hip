@@ -1,0 +1,284 @@
+// Implicit-GEMM convolution on the fp32 matrix cores of gfx950
+// (v_mfma_f32_32x32x2_f32), used for the forward pass and, with a flipped /
+// transposed filter or a scattering epilogue, for the data gradient.
+//
+//   out[m][n] (+)= sum_k A[m][k] * W[n][k],   m = (img,p,q), k = (r,t,c), c fastest
+//
+// A is never materialised: each K-chunk of 32 lies inside one filter tap, so a tile
+// row is 128 contiguous bytes of the NHWC input (or zeros in the padding).  A
+// workgroup of 4 waves (2 x 2) owns a BM x BN tile; each wave a (BM/2) x (BN/2)
+// sub-tile made of 32x32 MFMA blocks.  Operand tiles are staged through LDS as
+// [row][k] with a 36-float pitch, so that one ds_read_b128 per lane feeds four
+// consecutive MFMAs: lanes 0-31 hold k = 8g..8g+3, lanes 32-63 hold k = 8g+4..8g+7
+// of their row (the pairing of k inside one MFMA is free, A and W use the same one).
+// The next chunk's global loads are in flight while the current chunk is multiplied.
+#include "kernels.h"
+
+namespace acc {
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 32;
+constexpr int LD = BK + 4;
+
+__device__ __forceinline__ v16f mfma32x32x2(float a, float b, v16f c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+#else
+  return c;  // the host pass never runs this
+#endif
+}
+
+struct RowPos {  // decoded GEMM row
+  int pix;       // img * h * wd (pixel index of the image origin)
+  int iy0, ix0;  // p*stride - pad, q*stride - pad
+  int ok;
+};
+
+__device__ __forceinline__ RowPos decode_row(const ConvGeom& g, int m, int M) {
+  RowPos rp;
+  rp.ok = m < M;
+  const int mm = rp.ok ? m : 0;
+  const int pq = g.p * g.q;
+  const int img = mm / pq;
+  const int rem = mm - img * pq;
+  const int p = rem / g.q;
+  const int q = rem - p * g.q;
+  rp.pix = img * g.h * g.wd;
+  rp.iy0 = p * g.stride - g.pad;
+  rp.ix0 = q * g.stride - g.pad;
+  return rp;
+}
+
+__device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
+  if (g.out_stride == 1 && g.out_h == g.p && g.out_w == g.q) return (size_t)m * g.n_out;
+  const int pq = g.p * g.q;
+  const int img = m / pq;
+  const int rem = m - img * pq;
+  const int p = rem / g.q;
+  const int q = rem - p * g.q;
+  return ((size_t)(img * g.out_h + p * g.out_stride) * g.out_w + q * g.out_stride) * g.n_out;
+}
+
+// FAST: c % 32 == 0, NHWC input.  Otherwise every element is decoded on its own
+// (any c, K tail, NCHW input); used for the 3-channel stem and for tiny layers.
+template <int BM, int BN, bool FAST>
+__global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n,
+                                                     int n_tiles) {
+  __shared__ __attribute__((aligned(16))) float As[BM * LD];
+  __shared__ __attribute__((aligned(16))) float Bs[BN * LD];
+
+  // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give
+  // each XCD a contiguous range of tiles (neighbouring tiles share operand rows in its L2).
+  const int per_xcd = gridDim.x >> 3;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= n_tiles) return;
+  const int tile_m = tile / n_tiles_n, tile_n = tile - tile_m * n_tiles_n;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
+  const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+
+  v16f acc[FM][FN];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  const int n_chunks = (K + BK - 1) / BK;
+
+  // K loop shared by both loaders: the next chunk is fetched into registers while the
+  // current one, already in LDS, is multiplied.
+  auto main_loop = [&](auto& load_chunk, auto& store_chunk) {
+    load_chunk(0);
+    store_chunk();
+    __syncthreads();
+    for (int kc = 0; kc < n_chunks; ++kc) {
+      const bool more = kc + 1 < n_chunks;
+      if (more) load_chunk(kc + 1);
+#pragma unroll
+      for (int g8 = 0; g8 < 4; ++g8) {
+        float4 af[FM], bf[FN];
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+          af[a] = *reinterpret_cast<const float4*>(
+              &As[(wm0 + 32 * a + (lane & 31)) * LD + g8 * 8 + (lane >> 5) * 4]);
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+          bf[b] = *reinterpret_cast<const float4*>(
+              &Bs[(wn0 + 32 * b + (lane & 31)) * LD + g8 * 8 + (lane >> 5) * 4]);
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+          for (int b = 0; b < FN; ++b) {
+            acc[a][b] = mfma32x32x2(af[a].x, bf[b].x, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[a].y, bf[b].y, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[a].z, bf[b].z, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[a].w, bf[b].w, acc[a][b]);
+          }
+      }
+      __syncthreads();
+      if (more) {
+        store_chunk();
+        __syncthreads();
+      }
+    }
+  };
+
+  if constexpr (FAST) {
+    constexpr int AI = BM / 32, BI = BN / 32;
+    const int col4 = tid & 7, row0 = tid >> 3;
+    RowPos rp[AI];
+#pragma unroll
+    for (int i = 0; i < AI; ++i) rp[i] = decode_row(g, m0 + row0 + 32 * i, M);
+    const float* wrow[BI];
+    bool wok[BI];
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int n = n0 + row0 + 32 * i;
+      wok[i] = n < g.n_out;
+      wrow[i] = g.w + (size_t)(wok[i] ? n : 0) * K + col4 * 4;
+    }
+    float4 ra[AI], rb[BI];
+    int kr = 0, kt = 0, c0 = 0;  // tap and channel offset of the chunk being loaded
+
+    auto load_chunk = [&](int kc) {
+#pragma unroll
+      for (int i = 0; i < AI; ++i) {
+        const int iy = rp[i].iy0 + kr, ix = rp[i].ix0 + kt;
+        const bool ok = rp[i].ok && (unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd;
+        ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok)
+          ra[i] = *reinterpret_cast<const float4*>(
+              g.in + ((size_t)(rp[i].pix + iy * g.wd + ix) * g.c + c0 + col4 * 4));
+      }
+#pragma unroll
+      for (int i = 0; i < BI; ++i) {
+        rb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (wok[i]) rb[i] = *reinterpret_cast<const float4*>(wrow[i] + (size_t)kc * BK);
+      }
+      c0 += BK;
+      if (c0 == g.c) {
+        c0 = 0;
+        if (++kt == g.s) { kt = 0; ++kr; }
+      }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+      for (int i = 0; i < AI; ++i)
+        *reinterpret_cast<float4*>(&As[(row0 + 32 * i) * LD + col4 * 4]) = ra[i];
+#pragma unroll
+      for (int i = 0; i < BI; ++i)
+        *reinterpret_cast<float4*>(&Bs[(row0 + 32 * i) * LD + col4 * 4]) = rb[i];
+    };
+
+    main_loop(load_chunk, store_chunk);
+  } else {
+    // one element per load: thread -> k column tid%32, rows tid/32 + 8*i
+    constexpr int AI = BM / 8, BI = BN / 8;
+    const int kcol = tid & 31, row0 = tid >> 5;
+    RowPos rp[AI];
+#pragma unroll
+    for (int i = 0; i < AI; ++i) rp[i] = decode_row(g, m0 + row0 + 8 * i, M);
+    float ra[AI], rb[BI];
+    auto load_chunk = [&](int kc) {
+      const int k = kc * BK + kcol;
+      const bool kok = k < K;
+      const int kk = kok ? k : 0;
+      const int tap = kk / g.c, c = kk - tap * g.c;
+      const int kr = tap / g.s, kt = tap - kr * g.s;
+#pragma unroll
+      for (int i = 0; i < AI; ++i) {
+        const int iy = rp[i].iy0 + kr, ix = rp[i].ix0 + kt;
+        const bool ok = kok && rp[i].ok && (unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd;
+        float v = 0.f;
+        if (ok) {
+          const int img = rp[i].pix / (g.h * g.wd);
+          const size_t off = g.in_nchw ? ((size_t)(img * g.c + c) * g.h + iy) * g.wd + ix
+                                       : (size_t)(rp[i].pix + iy * g.wd + ix) * g.c + c;
+          v = g.in[off];
+        }
+        ra[i] = v;
+      }
+#pragma unroll
+      for (int i = 0; i < BI; ++i) {
+        const int n = n0 + row0 + 8 * i;
+        rb[i] = (kok && n < g.n_out) ? g.w[(size_t)n * K + k] : 0.f;
+      }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+      for (int i = 0; i < AI; ++i) As[(row0 + 8 * i) * LD + kcol] = ra[i];
+#pragma unroll
+      for (int i = 0; i < BI; ++i) Bs[(row0 + 8 * i) * LD + kcol] = rb[i];
+    };
+    main_loop(load_chunk, store_chunk);
+  }
+
+  // epilogue: accumulator register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4,
+  // column lane%32 of its 32x32 block
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int m = m0 + wm0 + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (m >= M) continue;
+      const size_t ro = out_row_offset(g, m);
+#pragma unroll
+      for (int b = 0; b < FN; ++b) {
+        const int n = n0 + wn0 + 32 * b + (lane & 31);
+        if (n >= g.n_out) continue;
+        float val = acc[a][b][v];
+        if (g.accumulate) val += g.out[ro + n];
+        g.out[ro + n] = val;
+      }
+    }
+}
+
+template <int BM, int BN, bool FAST>
+hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st) {
+  const int tm = (M + BM - 1) / BM, tn = (g.n_out + BN - 1) / BN;
+  const long tiles = (long)tm * tn;
+  if (tiles <= 0 || tiles > (1L << 30)) return hipErrorInvalidValue;
+  const int grid = (int)((tiles + 7) / 8 * 8);
+  hipLaunchKernelGGL((igemm_kernel<BM, BN, FAST>), dim3(grid), dim3(256), 0, st, g, M, K, tn,
+                     (int)tiles);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t conv_igemm(const ConvGeom& g, hipStream_t st) {
+  if (!g.in || !g.w || !g.out) return hipErrorInvalidValue;
+  if (g.n_img <= 0 || g.h <= 0 || g.wd <= 0 || g.c <= 0 || g.p <= 0 || g.q <= 0 || g.n_out <= 0 ||
+      g.r <= 0 || g.s <= 0 || g.stride <= 0 || g.pad < 0 || g.out_stride <= 0)
+    return hipErrorInvalidValue;
+  // every gathered coordinate p*stride+r-pad is range-checked in the kernel; the output
+  // pixel (p*out_stride, q*out_stride) must exist
+  if ((g.p - 1) * g.out_stride >= g.out_h || (g.q - 1) * g.out_stride >= g.out_w)
+    return hipErrorInvalidValue;
+  const long M = (long)g.n_img * g.p * g.q;
+  const long K = (long)g.r * g.s * g.c;
+  if (M >= (1L << 31) || K >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31))
+    return hipErrorInvalidValue;
+  const bool fast = (g.c % BK == 0) && !g.in_nchw;
+  if (!fast) return launch<64, 64, false>(g, (int)M, (int)K, st);
+  // tile choice depends on the GEMM shape only (never on addresses or on the swap plan)
+  auto cost = [&](int bm, int bn, double eff) {
+    const double tiles = (double)((M + bm - 1) / bm) * ((g.n_out + bn - 1) / bn);
+    const double rounds = __builtin_ceil(tiles / 512.0);
+    return rounds * bm * bn / eff;
+  };
+  const double c128 = g.n_out > 64 ? cost(128, 128, 1.0) : 1e300;
+  const double c12864 = cost(128, 64, 0.92);
+  const double c64 = cost(64, 64, 0.80);
+  if (c128 <= c12864 && c128 <= c64) return launch<128, 128, true>(g, (int)M, (int)K, st);
+  if (c12864 <= c64) return launch<128, 64, true>(g, (int)M, (int)K, st);
+  return launch<64, 64, true>(g, (int)M, (int)K, st);
+}
+
+}  // namespace acc

@@ -1,0 +1,704 @@
+// Context, runtime memory manager and executor behind the C ABI (include/accudnn.h).
+//
+// The runtime of Sec. 6 of the paper: one buffer pool of the size of the budget, pinned
+// host backing store, and three streams (compute, swap-out, swap-in).  The four operations
+// allocate / release / offload / prefetch are resolved at plan time into pool offsets and
+// event waits (plan.h); train_step() only walks the instruction list, so the host never
+// blocks inside an iteration and the GPU-side order is the same on every run.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/accudnn.h"
+#include "graph.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace acc;
+
+namespace {
+thread_local std::string g_create_error;
+inline size_t al256(size_t b) { return (b + 255) & ~(size_t)255; }
+double now_ms() {
+  return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+}  // namespace
+
+struct acc_ctx {
+  Graph g;
+  CostModel cm;
+  Plan plan;
+  bool have_res = false;
+  acc_resources res{};
+  std::string err;
+  hipStream_t s_c = nullptr, s_o = nullptr, s_i = nullptr;
+  // static part of the pool
+  float* d_params = nullptr;
+  float* d_grads = nullptr;
+  float* d_stats = nullptr;
+  float* d_loss = nullptr;
+  char* dyn = nullptr;
+  size_t dyn_cap = 0;
+  // events of the current plan
+  std::vector<hipEvent_t> ev_step, ev_d2h, ev_h2d;
+  std::vector<hipEvent_t> prof_a, prof_b, prof_copy_a, prof_copy_b;
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+  bool profiling = false;
+  bool calibrating = false;     // input batch is synthesised on the device
+  std::vector<double> step_ms;
+  std::vector<size_t> cur_off;  // per tensor, while executing
+  acc_stats stats{};
+  float* h_loss = nullptr;      // pinned scalar
+
+  int fail(int code, const std::string& what) { err = what; return code; }
+  int hipfail(hipError_t e, const char* what) {
+    err = std::string(what) + ": " + hipGetErrorString(e);
+    return ACC_EHIP;
+  }
+  void drop_events() {
+    for (auto* v : {&ev_step, &ev_d2h, &ev_h2d, &prof_a, &prof_b, &prof_copy_a, &prof_copy_b}) {
+      for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
+      v->clear();
+    }
+  }
+};
+
+#define HIPCHK(ctx, expr)                                  \
+  do {                                                     \
+    hipError_t e_ = (expr);                                \
+    if (e_ != hipSuccess) return (ctx)->hipfail(e_, #expr); \
+  } while (0)
+
+// ------------------------------------------------------------------ weight layout helpers
+namespace {
+
+// host OIHW <-> device O-H-W-I
+void oihw_to_ohwi(const float* src, float* dst, int o, int i, int r, int s) {
+  for (int a = 0; a < o; ++a)
+    for (int b = 0; b < i; ++b)
+      for (int y = 0; y < r; ++y)
+        for (int x = 0; x < s; ++x)
+          dst[(((size_t)a * r + y) * s + x) * i + b] = src[(((size_t)a * i + b) * r + y) * s + x];
+}
+void ohwi_to_oihw(const float* src, float* dst, int o, int i, int r, int s) {
+  for (int a = 0; a < o; ++a)
+    for (int b = 0; b < i; ++b)
+      for (int y = 0; y < r; ++y)
+        for (int x = 0; x < s; ++x)
+          dst[(((size_t)a * i + b) * r + y) * s + x] = src[(((size_t)a * r + y) * s + x) * i + b];
+}
+
+int param_io(acc_ctx* c, int layer, float* host, size_t n, bool to_device, bool grads) {
+  if (!c) return ACC_EINVAL;
+  if (!c->have_res) return c->fail(ACC_ESTATE, "context has no device resources");
+  if (layer < 0 || layer >= (int)c->g.layers.size() || !host) return c->fail(ACC_EINVAL, "bad layer or pointer");
+  const ParamSlot& ps = c->g.params[layer];
+  if (ps.count == 0 || n != ps.count) return c->fail(ACC_EINVAL, "element count does not match the layer");
+  const acc_layer& l = c->g.layers[layer];
+  float* dev = (grads ? c->d_grads : c->d_params) + ps.offset;
+  std::vector<float> tmp(n);
+  if (to_device) {
+    if (l.kind == ACC_CONV) oihw_to_ohwi(host, tmp.data(), l.cout, l.cin, l.r, l.s);
+    else std::memcpy(tmp.data(), host, n * sizeof(float));
+    HIPCHK(c, hipMemcpyAsync(dev, tmp.data(), n * sizeof(float), hipMemcpyHostToDevice, c->s_c));
+    HIPCHK(c, hipStreamSynchronize(c->s_c));
+  } else {
+    HIPCHK(c, hipMemcpyAsync(tmp.data(), dev, n * sizeof(float), hipMemcpyDeviceToHost, c->s_c));
+    HIPCHK(c, hipStreamSynchronize(c->s_c));
+    if (l.kind == ACC_CONV) ohwi_to_oihw(tmp.data(), host, l.cout, l.cin, l.r, l.s);
+    else std::memcpy(host, tmp.data(), n * sizeof(float));
+  }
+  return ACC_OK;
+}
+
+}  // namespace
+
+// --------------------------------------------------------------------------- lifecycle
+extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int in_h, int in_w, int dtype,
+                          const acc_resources* res, acc_ctx** out) {
+  if (!out) { g_create_error = "out is null"; return ACC_EINVAL; }
+  *out = nullptr;
+  if (dtype != ACC_F32) { g_create_error = "only fp32 is implemented"; return ACC_EINVAL; }
+  acc_ctx* c = new (std::nothrow) acc_ctx();
+  if (!c) { g_create_error = "out of host memory"; return ACC_EHOSTMEM; }
+  std::string err;
+  if (!c->g.build(layers, n_layers, in_c, in_h, in_w, &err)) {
+    g_create_error = err;
+    delete c;
+    return ACC_EINVAL;
+  }
+  if (res) {
+    if (!res->pool || !res->host || !res->s_compute || !res->s_out || !res->s_in ||
+        ((uintptr_t)res->pool & 255) || ((uintptr_t)res->host & 255)) {
+      g_create_error = "resources: null or not 256-byte aligned";
+      delete c;
+      return ACC_EINVAL;
+    }
+    if (res->s_compute == res->s_out || res->s_compute == res->s_in || res->s_out == res->s_in) {
+      g_create_error = "resources: the three streams must differ";
+      delete c;
+      return ACC_EINVAL;
+    }
+    const size_t stat = c->g.static_bytes();
+    if (res->pool_bytes < stat + 256) {
+      g_create_error = "pool smaller than parameters + gradients";
+      delete c;
+      return ACC_EPOOL;
+    }
+    c->res = *res;
+    c->have_res = true;
+    c->s_c = (hipStream_t)res->s_compute;
+    c->s_o = (hipStream_t)res->s_out;
+    c->s_i = (hipStream_t)res->s_in;
+    char* p = (char*)res->pool;
+    const size_t pb = al256(c->g.param_elems * sizeof(float));
+    c->d_params = (float*)p; p += pb;
+    c->d_grads = (float*)p; p += pb;
+    c->d_stats = (float*)p; p += al256(c->g.stat_elems * sizeof(float));
+    c->d_loss = (float*)p; p += 256;
+    c->dyn = p;
+    c->dyn_cap = (res->pool_bytes - stat) & ~(size_t)255;
+    hipError_t e = fill_zero(c->d_params, (pb * 2) / sizeof(float), c->s_c);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->s_c);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_loss, 256, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreate(&c->ev_begin);
+    if (e == hipSuccess) e = hipEventCreate(&c->ev_end);
+    if (e != hipSuccess) {
+      g_create_error = std::string("device setup: ") + hipGetErrorString(e);
+      delete c;
+      return ACC_EHIP;
+    }
+  }
+  *out = c;
+  return ACC_OK;
+}
+
+extern "C" void acc_destroy(acc_ctx* c) {
+  if (!c) return;
+  if (c->have_res) {
+    (void)hipStreamSynchronize(c->s_c);
+    (void)hipStreamSynchronize(c->s_o);
+    (void)hipStreamSynchronize(c->s_i);
+    c->drop_events();
+    if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
+    if (c->ev_end) (void)hipEventDestroy(c->ev_end);
+    if (c->h_loss) (void)hipHostFree(c->h_loss);
+  }
+  delete c;
+}
+
+extern "C" const char* acc_last_error(const acc_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+extern "C" const char* acc_step_kind_name(int kind) { return step_kind_name(kind); }
+
+extern "C" int acc_set_weights(acc_ctx* c, int layer, const float* w, size_t n) {
+  return param_io(c, layer, const_cast<float*>(w), n, true, false);
+}
+extern "C" int acc_get_weights(acc_ctx* c, int layer, float* w, size_t n) { return param_io(c, layer, w, n, false, false); }
+extern "C" int acc_get_grads(acc_ctx* c, int layer, float* g, size_t n) { return param_io(c, layer, g, n, false, true); }
+extern "C" int acc_param_count(const acc_ctx* c, int layer, size_t* n) {
+  if (!c || !n || layer < 0 || layer >= (int)c->g.layers.size()) return ACC_EINVAL;
+  *n = c->g.params[layer].count;
+  return ACC_OK;
+}
+
+// -------------------------------------------------------------------------- cost model
+extern "C" int acc_set_cost_model(acc_ctx* c, double flops_per_s, double bytes_per_s, double launch_s,
+                                  double d2h, double h2d, double copy_latency_s) {
+  if (!c) return ACC_EINVAL;
+  if (!(flops_per_s > 0) || !(bytes_per_s > 0) || launch_s < 0 || !(d2h > 0) || !(h2d > 0) || copy_latency_s < 0)
+    return c->fail(ACC_EINVAL, "cost model parameters must be positive");
+  c->cm.flops_per_s = flops_per_s; c->cm.bytes_per_s = bytes_per_s; c->cm.launch_s = launch_s;
+  c->cm.d2h_bps = d2h; c->cm.h2d_bps = h2d; c->cm.copy_latency_s = copy_latency_s;
+  c->cm.ks.clear(); c->cm.table.clear(); c->cm.fixed.clear();
+  return ACC_OK;
+}
+
+extern "C" int acc_set_step_times(acc_ctx* c, const double* seconds, int n) {
+  if (!c) return ACC_EINVAL;
+  if (n == 0) { c->cm.fixed.clear(); return ACC_OK; }
+  if (!seconds || n != (int)c->g.steps.size()) return c->fail(ACC_EINVAL, "need one time per step");
+  for (int i = 0; i < n; ++i) if (!(seconds[i] >= 0)) return c->fail(ACC_EINVAL, "negative step time");
+  c->cm.fixed.assign(seconds, seconds + n);
+  return ACC_OK;
+}
+
+// ---------------------------------------------------------------------------- planning
+namespace {
+
+int install_plan(acc_ctx* c, Plan&& p, acc_plan_summary* out, double t0) {
+  if (c->have_res) {
+    if (p.budget > c->res.pool_bytes) return c->fail(ACC_EPOOL, "budget exceeds the pool");
+    if (p.host_bytes > c->res.host_bytes) return c->fail(ACC_EHOSTMEM, "pinned host arena smaller than the swapped maps");
+    HIPCHK(c, hipStreamSynchronize(c->s_c));
+    HIPCHK(c, hipStreamSynchronize(c->s_o));
+    HIPCHK(c, hipStreamSynchronize(c->s_i));
+    c->drop_events();
+    const int ns = (int)c->g.steps.size();
+    c->ev_step.assign(ns, nullptr);
+    for (const Instr& in : p.instrs)
+      if (in.op == I_COMPUTE && in.record)
+        HIPCHK(c, hipEventCreateWithFlags(&c->ev_step[in.arg], hipEventDisableTiming));
+    c->ev_d2h.assign(p.n_d2h, nullptr);
+    c->ev_h2d.assign(p.n_h2d, nullptr);
+    for (auto& e : c->ev_d2h) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    for (auto& e : c->ev_h2d) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  }
+  c->plan = std::move(p);
+  c->stats = acc_stats{};
+  if (out) {
+    const Plan& P = c->plan;
+    std::memset(out, 0, sizeof *out);
+    out->n_steps = (int)c->g.steps.size();
+    out->n_maps = (int)c->g.maps.size();
+    out->n_swapped = P.n_swapped;
+    out->n_instr = (int)P.instrs.size();
+    out->bytes_swapped = P.bytes_swapped;
+    for (int t : c->g.maps) out->bytes_maps += P.tbytes[t];
+    out->static_bytes = c->g.static_bytes();
+    out->peak_bytes = out->static_bytes + P.dyn_peak;
+    std::vector<uint8_t> all(c->g.tensors.size(), 0), none(c->g.tensors.size(), 0);
+    for (int t : c->g.maps) all[t] = 1;
+    out->layer_peak_bytes = out->static_bytes + live_peak(c->g, P.k, all);
+    out->noswap_peak_bytes = out->static_bytes + live_peak(c->g, P.k, none);
+    out->host_bytes = P.host_bytes;
+    out->t_compute = P.t_compute;
+    out->t_iter = P.t_iter;
+    out->t_stall = P.t_stall;
+    out->plan_ms = now_ms() - t0;
+  }
+  return ACC_OK;
+}
+
+}  // namespace
+
+extern "C" int acc_plan_swaps(acc_ctx* c, int minibatch, size_t budget_bytes, int mode, acc_plan_summary* out) {
+  if (!c) return ACC_EINVAL;
+  const double t0 = now_ms();
+  if (minibatch <= 0) return c->fail(ACC_EINVAL, "minibatch must be positive");
+  c->plan.valid = false;
+  Plan p;
+  std::string why;
+  const int rc = make_plan(c->g, c->cm, minibatch, budget_bytes, mode, &p, &why);
+  if (rc != ACC_OK) return c->fail(rc, why);
+  return install_plan(c, std::move(p), out, t0);
+}
+
+extern "C" int acc_plan_explicit(acc_ctx* c, int minibatch, size_t budget_bytes, const uint8_t* swap, int n_maps,
+                                 acc_plan_summary* out) {
+  if (!c) return ACC_EINVAL;
+  const double t0 = now_ms();
+  if (minibatch <= 0 || !swap || n_maps != (int)c->g.maps.size()) return c->fail(ACC_EINVAL, "need one flag per map");
+  c->plan.valid = false;
+  std::vector<uint8_t> sw(c->g.tensors.size(), 0);
+  for (int i = 0; i < n_maps; ++i) sw[c->g.maps[i]] = swap[i] ? 1 : 0;
+  Plan p;
+  std::string why;
+  if (!build_plan(c->g, minibatch, budget_bytes, sw, PlanOptions(), &p, &why)) return c->fail(ACC_EUNTRAINABLE, why);
+  simulate(c->g, c->cm, &p);
+  p.mode = -1;
+  return install_plan(c, std::move(p), out, t0);
+}
+
+extern "C" int acc_get_step_count(const acc_ctx* c) { return c ? (int)c->g.steps.size() : ACC_EINVAL; }
+extern "C" int acc_get_tensor_count(const acc_ctx* c) { return c ? (int)c->g.tensors.size() : ACC_EINVAL; }
+
+extern "C" int acc_get_step_info(const acc_ctx* c, int step, acc_step_info* out) {
+  if (!c || !out || step < 0 || step >= (int)c->g.steps.size()) return ACC_EINVAL;
+  const Step& s = c->g.steps[step];
+  std::memset(out, 0, sizeof *out);
+  out->kind = s.kind; out->layer = s.layer; out->backward = s.phase;
+  const int k = c->plan.valid ? c->plan.k : 1;
+  out->flops = s.flops_per_image * k;
+  if (c->plan.valid) {
+    out->t_compute = c->plan.t_cost[step]; out->t_ready = c->plan.t_ready[step];
+    out->t_start = c->plan.t_start[step]; out->t_end = c->plan.t_end[step];
+  }
+  return ACC_OK;
+}
+
+extern "C" int acc_get_tensor_info(const acc_ctx* c, int t, acc_tensor_info* out) {
+  if (!c || !out || t < 0 || t >= (int)c->g.tensors.size()) return ACC_EINVAL;
+  const Tensor& T = c->g.tensors[t];
+  std::memset(out, 0, sizeof *out);
+  out->kind = T.kind; out->producer_step = T.producer; out->last_fwd_step = T.last_fwd;
+  out->first_bwd_step = T.first_bwd; out->last_step = T.last; out->is_map = T.is_map;
+  if (c->plan.valid) {
+    const size_t stat = c->g.static_bytes();
+    out->swapped = c->plan.swapped[t]; out->bytes = c->plan.tbytes[t];
+    out->offset = stat + c->plan.off1[t]; out->offset2 = stat + c->plan.off2[t]; out->host_offset = c->plan.host_off[t];
+  } else {
+    out->bytes = c->g.bytes(t, 1);
+  }
+  return ACC_OK;
+}
+
+extern "C" int acc_get_step_io(const acc_ctx* c, int step, int32_t* reads, int max_reads, int32_t* writes, int max_writes) {
+  if (!c || step < 0 || step >= (int)c->g.steps.size()) return ACC_EINVAL;
+  const Step& s = c->g.steps[step];
+  if ((int)s.reads.size() > max_reads || (int)s.writes.size() > max_writes) return ACC_EINVAL;
+  for (size_t i = 0; i < s.reads.size(); ++i) reads[i] = s.reads[i];
+  for (size_t i = 0; i < s.writes.size(); ++i) writes[i] = s.writes[i];
+  return (int)(s.reads.size() * 256 + s.writes.size());
+}
+
+// ---------------------------------------------------------------------------- executor
+namespace {
+
+hipError_t fill_pseudo_input(acc_ctx* c, float* p, size_t count);
+
+// launches the kernels of one step on the compute stream
+hipError_t run_step(acc_ctx* c, int j, float lr) {
+  const Graph& g = c->g;
+  const Step& s = g.steps[j];
+  const int k = c->plan.k;
+  auto ptr = [&](int t) -> float* { return t < 0 ? nullptr : (float*)(c->dyn + c->cur_off[t]); };
+  auto T = [&](int t) -> const Tensor& { return g.tensors[t]; };
+  hipStream_t st = c->s_c;
+  const acc_layer* l = s.layer >= 0 ? &g.layers[s.layer] : nullptr;
+  float* w = s.layer >= 0 ? c->d_params + g.params[s.layer].offset : nullptr;
+  float* dw = s.layer >= 0 ? c->d_grads + g.params[s.layer].offset : nullptr;
+  switch (s.kind) {
+    case K_INPUT_F:
+      return nchw_to_nhwc(ptr(s.x), ptr(s.y), k, g.in_c, g.in_h * g.in_w, st);
+    case K_CONV_F: {
+      ConvGeom cg{};
+      cg.in = ptr(s.x); cg.w = w; cg.out = ptr(s.y);
+      cg.n_img = k; cg.h = T(s.x).h; cg.wd = T(s.x).w; cg.c = l->cin;
+      cg.p = T(s.y).h; cg.q = T(s.y).w; cg.n_out = l->cout;
+      cg.r = l->r; cg.s = l->s; cg.stride = l->stride; cg.pad = l->pad;
+      cg.out_h = cg.p; cg.out_w = cg.q; cg.out_stride = 1; cg.accumulate = 0;
+      return conv_igemm(cg, st);
+    }
+    case K_BN_F: {
+      float* stat = c->d_stats + g.params[s.layer].stat_offset;
+      return bn_forward(ptr(s.x), w, w + l->cin, ptr(s.res), ptr(s.y), stat, stat + l->cin,
+                        (long)k * T(s.x).h * T(s.x).w, l->cin, s.relu, 1e-5f, ptr(s.ws), st);
+    }
+    case K_MAXPOOL_F:
+      return maxpool_forward(ptr(s.x), ptr(s.y), k, T(s.x).h, T(s.x).w, T(s.x).c, l->r, l->s, l->stride, l->pad, st);
+    case K_GAP_F:
+      return gap_forward(ptr(s.x), ptr(s.y), k, T(s.x).h * T(s.x).w, T(s.x).c, st);
+    case K_FC_F: {
+      ConvGeom cg{};
+      cg.in = ptr(s.x); cg.w = w; cg.out = ptr(s.y);
+      cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cin; cg.p = 1; cg.q = 1; cg.n_out = l->cout;
+      cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
+      hipError_t e = conv_igemm(cg, st);
+      if (e != hipSuccess) return e;
+      return bias_add(ptr(s.y), w + (size_t)l->cout * l->cin, k, l->cout, st);
+    }
+    case K_LOSS_F:
+      return softmax_ce_forward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.ws), c->d_loss, k, g.classes, st);
+    case K_LOSS_B:
+      return softmax_ce_backward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.dx), k, g.classes, st);
+    case K_FC_B: {
+      WgradGeom wg{};
+      wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw;
+      wg.n_img = k; wg.h = 1; wg.wd = 1; wg.cin = l->cin; wg.p = 1; wg.q = 1; wg.cout = l->cout;
+      wg.r = 1; wg.s = 1; wg.stride = 1; wg.pad = 0; wg.workspace = ptr(s.ws2);
+      hipError_t e = conv_wgrad(wg, st);
+      if (e != hipSuccess) return e;
+      e = column_sum(ptr(s.dy), dw + (size_t)l->cout * l->cin, k, l->cout, st);
+      if (e != hipSuccess) return e;
+      e = filter_flip_transpose(w, ptr(s.ws), l->cout, l->cin, 1, 1, st);
+      if (e != hipSuccess) return e;
+      ConvGeom cg{};
+      cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx);
+      cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cout; cg.p = 1; cg.q = 1; cg.n_out = l->cin;
+      cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
+      cg.accumulate = s.dx_accumulate;
+      return conv_igemm(cg, st);
+    }
+    case K_GAP_B:
+      return gap_backward(ptr(s.dy), ptr(s.dx), k, T(s.dx).h * T(s.dx).w, T(s.dx).c, s.dx_accumulate, st);
+    case K_MAXPOOL_B:
+      return maxpool_backward(ptr(s.x), ptr(s.dy), ptr(s.dx), k, T(s.x).h, T(s.x).w, T(s.x).c, l->r, l->s,
+                              l->stride, l->pad, s.dx_accumulate, st);
+    case K_BN_B: {
+      float* stat = c->d_stats + g.params[s.layer].stat_offset;
+      return bn_backward(ptr(s.x), ptr(s.dy), ptr(s.y), w, stat, stat + l->cin, ptr(s.dx), dw, dw + l->cin,
+                         s.g_inplace ? ptr(s.dy) : nullptr, (long)k * T(s.x).h * T(s.x).w, l->cin, ptr(s.ws), st);
+    }
+    case K_CONV_B: {
+      const int h = T(s.x).h, wd = T(s.x).w, ho = T(s.dy).h, wo = T(s.dy).w;
+      WgradGeom wg{};
+      wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw;
+      wg.n_img = k; wg.h = h; wg.wd = wd; wg.cin = l->cin; wg.p = ho; wg.q = wo; wg.cout = l->cout;
+      wg.r = l->r; wg.s = l->s; wg.stride = l->stride; wg.pad = l->pad;
+      wg.workspace = ptr(s.ws2);
+      hipError_t e = conv_wgrad(wg, st);
+      if (e != hipSuccess || s.dx < 0) return e;
+      e = filter_flip_transpose(w, ptr(s.ws), l->cout, l->cin, l->r, l->s, st);
+      if (e != hipSuccess) return e;
+      ConvGeom cg{};
+      cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx);
+      cg.n_img = k; cg.h = ho; cg.wd = wo; cg.c = l->cout; cg.n_out = l->cin;
+      cg.r = l->r; cg.s = l->s; cg.stride = 1; cg.accumulate = s.dx_accumulate;
+      cg.out_h = h; cg.out_w = wd;
+      if (l->stride == 1) {
+        cg.p = h; cg.q = wd; cg.pad = l->r - 1 - l->pad; cg.out_stride = 1;
+      } else {  // 1x1, pad 0: dense product on the strided positions, zeros elsewhere
+        cg.p = ho; cg.q = wo; cg.pad = 0; cg.out_stride = l->stride;
+        if (!s.dx_accumulate) {
+          e = fill_zero(ptr(s.dx), (size_t)k * h * wd * l->cin, st);
+          if (e != hipSuccess) return e;
+        }
+      }
+      return conv_igemm(cg, st);
+    }
+    case K_SGD:
+      return sgd_update(c->d_params, c->d_grads, lr, g.param_elems, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, const int32_t* labels, float lr,
+                              float* loss_out) {
+  if (!c) return ACC_EINVAL;
+  if (!c->have_res) return c->fail(ACC_ESTATE, "context has no device resources");
+  if (!c->plan.valid) return c->fail(ACC_ESTATE, "call acc_plan_swaps first");
+  if (!c->calibrating && (!images || !labels)) return c->fail(ACC_EINVAL, "images / labels are null");
+  if (images_loc != ACC_LOC_HOST && images_loc != ACC_LOC_DEVICE) return c->fail(ACC_EINVAL, "bad images_loc");
+  const Plan& P = c->plan;
+  const Graph& g = c->g;
+  const int ns = (int)g.steps.size();
+  const double t_host0 = now_ms();
+  c->cur_off = P.off1;
+  if (c->profiling) {
+    if ((int)c->prof_a.size() != ns) {
+      c->prof_a.assign(ns, nullptr); c->prof_b.assign(ns, nullptr);
+      for (int j = 0; j < ns; ++j) { HIPCHK(c, hipEventCreate(&c->prof_a[j])); HIPCHK(c, hipEventCreate(&c->prof_b[j])); }
+    }
+    const size_t nc = P.n_d2h + P.n_h2d;
+    if (c->prof_copy_a.size() != nc) {
+      for (hipEvent_t e : c->prof_copy_a) (void)hipEventDestroy(e);
+      for (hipEvent_t e : c->prof_copy_b) (void)hipEventDestroy(e);
+      c->prof_copy_a.assign(nc, nullptr); c->prof_copy_b.assign(nc, nullptr);
+      for (size_t i = 0; i < nc; ++i) { HIPCHK(c, hipEventCreate(&c->prof_copy_a[i])); HIPCHK(c, hipEventCreate(&c->prof_copy_b[i])); }
+    }
+  }
+  uint64_t bytes_out = 0, bytes_in = 0;
+  HIPCHK(c, hipEventRecord(c->ev_begin, c->s_c));
+  for (const Instr& in : P.instrs) {
+    switch (in.op) {
+      case I_LOAD_INPUT: {
+        void* dst = c->dyn + c->cur_off[in.arg];
+        if (c->calibrating) {
+          if (in.arg == g.t_stage) {
+            hipError_t e = fill_pseudo_input(c, (float*)dst, (size_t)P.k * g.in_c * g.in_h * g.in_w);
+            if (e != hipSuccess) return c->hipfail(e, "fill_pseudo_input");
+          } else {
+            hipError_t e = fill_zero((float*)dst, (size_t)P.k, c->s_i);
+            if (e != hipSuccess) return c->hipfail(e, "fill_zero(labels)");
+          }
+        } else if (in.arg == g.t_stage) {
+          const size_t bytes = (size_t)P.k * g.in_c * g.in_h * g.in_w * sizeof(float);
+          HIPCHK(c, hipMemcpyAsync(dst, images, bytes,
+                                   images_loc == ACC_LOC_HOST ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice, c->s_i));
+        } else {
+          HIPCHK(c, hipMemcpyAsync(dst, labels, (size_t)P.k * sizeof(int32_t), hipMemcpyHostToDevice, c->s_i));
+        }
+        HIPCHK(c, hipEventRecord(c->ev_h2d[in.seq], c->s_i));
+        break;
+      }
+      case I_COMPUTE: {
+        if (in.wait_d2h >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_d2h[in.wait_d2h], 0));
+        if (in.wait_h2d >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_h2d[in.wait_h2d], 0));
+        if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_a[in.arg], c->s_c));
+        hipError_t e = run_step(c, in.arg, lr);
+        if (e != hipSuccess) {
+          char buf[96];
+          snprintf(buf, sizeof buf, "step %d (%s)", in.arg, step_kind_name(g.steps[in.arg].kind));
+          (void)hipStreamSynchronize(c->s_c); (void)hipStreamSynchronize(c->s_o); (void)hipStreamSynchronize(c->s_i);
+          return c->hipfail(e, buf);
+        }
+        if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_b[in.arg], c->s_c));
+        if (in.record) HIPCHK(c, hipEventRecord(c->ev_step[in.arg], c->s_c));
+        break;
+      }
+      case I_OFFLOAD: {
+        HIPCHK(c, hipStreamWaitEvent(c->s_o, c->ev_step[in.wait_step], 0));
+        if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_copy_a[in.seq], c->s_o));
+        HIPCHK(c, hipMemcpyAsync((char*)c->res.host + P.host_off[in.arg], c->dyn + P.off1[in.arg], P.tbytes[in.arg],
+                                 hipMemcpyDeviceToHost, c->s_o));
+        if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_copy_b[in.seq], c->s_o));
+        HIPCHK(c, hipEventRecord(c->ev_d2h[in.seq], c->s_o));
+        bytes_out += P.tbytes[in.arg];
+        break;
+      }
+      case I_PREFETCH: {
+        if (in.wait_step >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_i, c->ev_step[in.wait_step], 0));
+        if (in.wait_d2h >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_i, c->ev_d2h[in.wait_d2h], 0));
+        if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_copy_a[P.n_d2h + in.seq], c->s_i));
+        HIPCHK(c, hipMemcpyAsync(c->dyn + P.off2[in.arg], (char*)c->res.host + P.host_off[in.arg], P.tbytes[in.arg],
+                                 hipMemcpyHostToDevice, c->s_i));
+        if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_copy_b[P.n_d2h + in.seq], c->s_i));
+        HIPCHK(c, hipEventRecord(c->ev_h2d[in.seq], c->s_i));
+        c->cur_off[in.arg] = P.off2[in.arg];
+        bytes_in += P.tbytes[in.arg];
+        break;
+      }
+    }
+  }
+  HIPCHK(c, hipMemcpyAsync(c->h_loss, c->d_loss, sizeof(float), hipMemcpyDeviceToHost, c->s_c));
+  HIPCHK(c, hipEventRecord(c->ev_end, c->s_c));
+  const double t_issued = now_ms();
+  HIPCHK(c, hipStreamSynchronize(c->s_c));
+  HIPCHK(c, hipStreamSynchronize(c->s_o));
+  HIPCHK(c, hipStreamSynchronize(c->s_i));
+  const double t_done = now_ms();
+  if (loss_out) *loss_out = *c->h_loss;
+  c->stats.step_ms = t_done - t_host0;
+  c->stats.host_issue_ms = t_issued - t_host0;
+  c->stats.peak_pool_bytes = g.static_bytes() + P.dyn_peak;
+  c->stats.bytes_out = bytes_out;
+  c->stats.bytes_in = bytes_in;
+  c->stats.steps_run += 1;
+  c->stats.d2h_ms = c->stats.h2d_ms = 0;
+  if (c->profiling) {
+    c->step_ms.assign(ns, 0.0);
+    for (int j = 0; j < ns; ++j) {
+      float ms = 0;
+      HIPCHK(c, hipEventElapsedTime(&ms, c->prof_a[j], c->prof_b[j]));
+      c->step_ms[j] = ms;
+    }
+    for (const Instr& in : P.instrs) {
+      if (in.op != I_OFFLOAD && in.op != I_PREFETCH) continue;
+      const size_t idx = in.op == I_OFFLOAD ? (size_t)in.seq : (size_t)P.n_d2h + in.seq;
+      float ms = 0;
+      HIPCHK(c, hipEventElapsedTime(&ms, c->prof_copy_a[idx], c->prof_copy_b[idx]));
+      (in.op == I_OFFLOAD ? c->stats.d2h_ms : c->stats.h2d_ms) += ms;
+    }
+  }
+  return ACC_OK;
+}
+
+extern "C" int acc_get_stats(acc_ctx* c, acc_stats* out) {
+  if (!c || !out) return ACC_EINVAL;
+  *out = c->stats;
+  return ACC_OK;
+}
+
+extern "C" int acc_set_profiling(acc_ctx* c, int on) {
+  if (!c) return ACC_EINVAL;
+  c->profiling = on != 0;
+  return ACC_OK;
+}
+
+extern "C" int acc_get_step_times_ms(acc_ctx* c, double* ms, int n) {
+  if (!c || !ms) return ACC_EINVAL;
+  if (n != (int)c->g.steps.size() || c->step_ms.size() != (size_t)n) return c->fail(ACC_ESTATE, "no profiled step yet");
+  std::copy(c->step_ms.begin(), c->step_ms.end(), ms);
+  return ACC_OK;
+}
+
+// ------------------------------------------------------------------------- calibration
+namespace {
+
+__global__ void pseudo_input_kernel(float* p, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+    uint32_t h = (uint32_t)i * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    p[i] = (float)(int32_t)h * (1.0f / 2147483648.0f);   // in [-1, 1)
+  }
+}
+
+hipError_t fill_pseudo_input(acc_ctx* c, float* p, size_t count) {
+  hipLaunchKernelGGL(pseudo_input_kernel, dim3(2048), dim3(256), 0, c->s_i, p, count);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+extern "C" int acc_calibrate(acc_ctx* c, const int* ks, int nk) {
+  if (!c) return ACC_EINVAL;
+  if (!c->have_res) return c->fail(ACC_ESTATE, "context has no device resources");
+  if (!ks || nk <= 0) return c->fail(ACC_EINVAL, "need at least one minibatch size");
+  std::vector<int> kk(ks, ks + nk);
+  std::sort(kk.begin(), kk.end());
+  kk.erase(std::unique(kk.begin(), kk.end()), kk.end());
+  if (kk[0] <= 0) return c->fail(ACC_EINVAL, "minibatch must be positive");
+  const int ns = (int)c->g.steps.size();
+
+  // dynamic information 2: transfer rates on the side streams (Eq. 5's Bandwidth_avail)
+  {
+    size_t big = std::min<size_t>((size_t)256 << 20, std::min(c->dyn_cap, c->res.host_bytes));
+    big &= ~(size_t)255;
+    const size_t small = std::min<size_t>((size_t)1 << 20, big);
+    if (big >= ((size_t)8 << 20)) {
+      hipEvent_t a, b;
+      HIPCHK(c, hipEventCreate(&a));
+      HIPCHK(c, hipEventCreate(&b));
+      double t[2][2];
+      for (int dir = 0; dir < 2; ++dir) {
+        hipStream_t st = dir == 0 ? c->s_o : c->s_i;
+        for (int sz = 0; sz < 2; ++sz) {
+          const size_t bytes = sz == 0 ? small : big;
+          float best = 1e30f;
+          for (int rep = 0; rep < 3; ++rep) {
+            HIPCHK(c, hipEventRecord(a, st));
+            if (dir == 0) HIPCHK(c, hipMemcpyAsync(c->res.host, c->dyn, bytes, hipMemcpyDeviceToHost, st));
+            else HIPCHK(c, hipMemcpyAsync(c->dyn, c->res.host, bytes, hipMemcpyHostToDevice, st));
+            HIPCHK(c, hipEventRecord(b, st));
+            HIPCHK(c, hipStreamSynchronize(st));
+            float ms = 0;
+            HIPCHK(c, hipEventElapsedTime(&ms, a, b));
+            best = std::min(best, ms);
+          }
+          t[dir][sz] = best * 1e-3;
+        }
+      }
+      (void)hipEventDestroy(a);
+      (void)hipEventDestroy(b);
+      const double bw_o = (double)(big - small) / std::max(1e-9, t[0][1] - t[0][0]);
+      const double bw_i = (double)(big - small) / std::max(1e-9, t[1][1] - t[1][0]);
+      c->cm.d2h_bps = bw_o;
+      c->cm.h2d_bps = bw_i;
+      const double lat = 0.5 * ((t[0][0] - small / bw_o) + (t[1][0] - small / bw_i));
+      c->cm.copy_latency_s = std::max(0.0, lat);
+    }
+  }
+
+  // dynamic information 1: per-step compute time at each minibatch, taken from real
+  // iterations (no swap if the pool allows it, else the naive swap-everything strategy)
+  const bool was_prof = c->profiling;
+  std::vector<int> ok_ks;
+  std::vector<std::vector<double>> table;
+  c->cm.fixed.clear();
+  for (int k : kk) {
+    Plan p;
+    std::string why;
+    int rc = make_plan(c->g, c->cm, k, c->res.pool_bytes, ACC_PLAN_NONE, &p, &why);
+    if (rc != ACC_OK) rc = make_plan(c->g, c->cm, k, c->res.pool_bytes, ACC_PLAN_NAIVE_ALL, &p, &why);
+    if (rc != ACC_OK) continue;   // does not fit this pool at all
+    rc = install_plan(c, std::move(p), nullptr, now_ms());
+    if (rc != ACC_OK) { if (rc == ACC_EHOSTMEM) continue; return rc; }
+    c->calibrating = true;
+    c->profiling = true;
+    std::vector<double> best(ns, 1e30);
+    int rc2 = ACC_OK;
+    for (int it = 0; it < 3 && rc2 == ACC_OK; ++it) {
+      float loss;
+      rc2 = acc_train_step(c, nullptr, ACC_LOC_DEVICE, nullptr, 0.0f, &loss);
+      if (rc2 == ACC_OK && it > 0)
+        for (int j = 0; j < ns; ++j) best[j] = std::min(best[j], c->step_ms[j] * 1e-3);
+    }
+    c->calibrating = false;
+    c->profiling = was_prof;
+    if (rc2 != ACC_OK) return rc2;
+    ok_ks.push_back(k);
+    table.push_back(best);
+  }
+  c->plan.valid = false;
+  if (ok_ks.empty()) return c->fail(ACC_EPOOL, "no calibration minibatch fits the pool");
+  c->cm.ks = ok_ks;
+  c->cm.table = table;
+  return ACC_OK;
+}

@@ -1,0 +1,340 @@
+// The small kernels that close the training step: filter flip/transposition for the data
+// gradient, max-pooling, global average pooling, bias, softmax cross-entropy, SGD.
+// None of them is on the roofline-critical path; all are coalesced along the channel
+// axis of NHWC and use fixed-order reductions.
+#include "kernels.h"
+
+namespace acc {
+namespace {
+
+constexpr int THREADS = 256;
+
+inline unsigned grid_for(size_t work, size_t cap = 256 * 32) {
+  size_t b = (work + THREADS - 1) / THREADS;
+  if (b < 1) b = 1;
+  return (unsigned)(b < cap ? b : cap);
+}
+
+// wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci]; a 32x32 LDS tile transposes (co, ci)
+// so that both the read (ci fastest) and the write (co fastest) are coalesced.
+__global__ __launch_bounds__(256) void flip_transpose_kernel(const float* __restrict__ w,
+                                                             float* __restrict__ wt, int cout, int cin,
+                                                             int r, int s) {
+  __shared__ float tile[32][33];
+  const int tap = blockIdx.z;                       // r'*s + t' of the output
+  const int kr = r - 1 - tap / s, kt = s - 1 - tap % s;
+  const int src_tap = kr * s + kt;
+  const int co0 = blockIdx.y * 32, ci0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    const int co = co0 + i, ci = ci0 + tx;
+    tile[i][tx] = (co < cout && ci < cin) ? w[((size_t)co * r * s + src_tap) * cin + ci] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int ci = ci0 + i, co = co0 + tx;
+    if (ci < cin && co < cout) wt[((size_t)ci * r * s + tap) * cout + co] = tile[tx][i];
+  }
+}
+
+// one thread per (n, p, q, 4 channels); the first maximum in (r, t) scan order wins
+__global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __restrict__ x,
+                                                              float* __restrict__ y, int n, int h, int wd,
+                                                              int c, int r, int s, int stride, int pad,
+                                                              int ho, int wo) {
+  const int cg = c >> 2;
+  const size_t total = (size_t)n * ho * wo * cg;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    const int g = (int)(i % cg);
+    size_t rest = i / cg;
+    const int q = (int)(rest % wo); rest /= wo;
+    const int p = (int)(rest % ho);
+    const int img = (int)(rest / ho);
+    float4 best = make_float4(0.f, 0.f, 0.f, 0.f);
+    bool have = false;
+    for (int kr = 0; kr < r; ++kr) {
+      const int iy = p * stride + kr - pad;
+      if ((unsigned)iy >= (unsigned)h) continue;
+      for (int kt = 0; kt < s; ++kt) {
+        const int ix = q * stride + kt - pad;
+        if ((unsigned)ix >= (unsigned)wd) continue;
+        const float4 v = *reinterpret_cast<const float4*>(x + ((size_t)(img * h + iy) * wd + ix) * c + g * 4);
+        if (!have) { best = v; have = true; }
+        else {
+          best.x = v.x > best.x ? v.x : best.x;
+          best.y = v.y > best.y ? v.y : best.y;
+          best.z = v.z > best.z ? v.z : best.z;
+          best.w = v.w > best.w ? v.w : best.w;
+        }
+      }
+    }
+    *reinterpret_cast<float4*>(y + i * 4) = best;
+  }
+}
+
+// Gather form of the max-pool gradient: one thread per input element (n, iy, ix, ch);
+// for every window that covers it, find the window's first maximum again and take the
+// window's dy if this element is the winner.
+__global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __restrict__ x,
+                                                              const float* __restrict__ dy, float* dx,
+                                                              int n, int h, int wd, int c, int r, int s,
+                                                              int stride, int pad, int ho, int wo,
+                                                              int accumulate) {
+  const size_t total = (size_t)n * h * wd * c;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    const int ch = (int)(i % c);
+    size_t rest = i / c;
+    const int ix = (int)(rest % wd); rest /= wd;
+    const int iy = (int)(rest % h);
+    const int img = (int)(rest / h);
+    // windows p with p*stride - pad <= iy <= p*stride - pad + r - 1
+    int p_lo = (iy + pad - r + 1 + stride - 1);
+    p_lo = p_lo > 0 ? p_lo / stride : 0;
+    int p_hi = (iy + pad) / stride; if (p_hi > ho - 1) p_hi = ho - 1;
+    int q_lo = (ix + pad - s + 1 + stride - 1);
+    q_lo = q_lo > 0 ? q_lo / stride : 0;
+    int q_hi = (ix + pad) / stride; if (q_hi > wo - 1) q_hi = wo - 1;
+    float acc = 0.f;
+    for (int p = p_lo; p <= p_hi; ++p)
+      for (int q = q_lo; q <= q_hi; ++q) {
+        float best = 0.f; int by = -1, bx = -1;
+        for (int kr = 0; kr < r; ++kr) {
+          const int yy = p * stride + kr - pad;
+          if ((unsigned)yy >= (unsigned)h) continue;
+          for (int kt = 0; kt < s; ++kt) {
+            const int xx = q * stride + kt - pad;
+            if ((unsigned)xx >= (unsigned)wd) continue;
+            const float v = x[((size_t)(img * h + yy) * wd + xx) * c + ch];
+            if (by < 0 || v > best) { best = v; by = yy; bx = xx; }
+          }
+        }
+        if (by == iy && bx == ix) acc += dy[((size_t)(img * ho + p) * wo + q) * c + ch];
+      }
+    dx[i] = accumulate ? dx[i] + acc : acc;
+  }
+}
+
+// y[n][c] = mean over hw of x[n][hw][c]
+__global__ __launch_bounds__(THREADS) void gap_fwd_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                          int n, int hw, int c) {
+  const size_t total = (size_t)n * c;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    const int ch = (int)(i % c);
+    const int img = (int)(i / c);
+    float sum = 0.f;
+    for (int k = 0; k < hw; ++k) sum += x[((size_t)img * hw + k) * c + ch];
+    y[i] = sum / (float)hw;
+  }
+}
+
+__global__ __launch_bounds__(THREADS) void gap_bwd_kernel(const float* __restrict__ dy, float* dx, int n,
+                                                          int hw, int c, int accumulate) {
+  const size_t total = (size_t)n * hw * c;
+  const float inv = 1.f / (float)hw;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    const int ch = (int)(i % c);
+    const int img = (int)(i / ((size_t)hw * c));
+    const float v = dy[(size_t)img * c + ch] * inv;
+    dx[i] = accumulate ? dx[i] + v : v;
+  }
+}
+
+__global__ __launch_bounds__(THREADS) void bias_add_kernel(float* y, const float* __restrict__ b, size_t total,
+                                                           int c) {
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS)
+    y[i] += b[i % c];
+}
+
+// db[ch] = sum over rows, one thread per channel, rows in order
+__global__ __launch_bounds__(THREADS) void column_sum_kernel(const float* __restrict__ dy,
+                                                             float* __restrict__ db, long rows, int c) {
+  const int ch = blockIdx.x * THREADS + threadIdx.x;
+  if (ch >= c) return;
+  float sum = 0.f;
+  for (long r = 0; r < rows; ++r) sum += dy[(size_t)r * c + ch];
+  db[ch] = sum;
+}
+
+// Fixed-order block reductions (tree over a power-of-two block, same order every run).
+__device__ __forceinline__ float block_max(float v, float* sh) {
+  sh[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = THREADS / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] = fmaxf(sh[threadIdx.x], sh[threadIdx.x + s]);
+    __syncthreads();
+  }
+  const float r = sh[0];
+  __syncthreads();
+  return r;
+}
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+  sh[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = THREADS / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+    __syncthreads();
+  }
+  const float r = sh[0];
+  __syncthreads();
+  return r;
+}
+
+// one workgroup per sample: loss_rows[i] = logsumexp(z_i) - z_i[label]; optionally
+// dz = (softmax - onehot) / n
+__global__ __launch_bounds__(THREADS) void softmax_ce_kernel(const float* __restrict__ z,
+                                                             const int32_t* __restrict__ labels,
+                                                             float* __restrict__ loss_rows,
+                                                             float* __restrict__ dz, int n, int classes) {
+  __shared__ float sh[THREADS];
+  const int i = blockIdx.x;
+  const float* zi = z + (size_t)i * classes;
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < classes; j += THREADS) mx = fmaxf(mx, zi[j]);
+  mx = block_max(mx, sh);
+  float se = 0.f;
+  for (int j = threadIdx.x; j < classes; j += THREADS) se += expf(zi[j] - mx);
+  se = block_sum(se, sh);
+  const float lse = mx + logf(se);
+  const int lab = labels[i];
+  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lse - zi[lab];
+  if (dz) {
+    const float inv_n = 1.f / (float)n;
+    for (int j = threadIdx.x; j < classes; j += THREADS)
+      dz[(size_t)i * classes + j] = (expf(zi[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_n;
+  }
+}
+
+// loss = (1/n) * sum of rows, added in index order by one wave-sized loop
+__global__ void loss_mean_kernel(const float* __restrict__ loss_rows, float* __restrict__ loss, int n) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += (double)loss_rows[i];
+    *loss = (float)(s / n);
+  }
+}
+
+__global__ __launch_bounds__(THREADS) void sgd_kernel(float* __restrict__ w, const float* __restrict__ g,
+                                                      float lr, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < count; i += (size_t)gridDim.x * THREADS)
+    w[i] = fmaf(-lr, g[i], w[i]);
+}
+
+__global__ __launch_bounds__(THREADS) void fill_zero_kernel(float* __restrict__ p, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < count; i += (size_t)gridDim.x * THREADS)
+    p[i] = 0.f;
+}
+
+// y[n][hw][c] = x[n][c][hw]: reads coalesced along hw for each channel, one pixel per thread
+__global__ __launch_bounds__(THREADS) void nchw_to_nhwc_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                               int n, int c, int hw) {
+  const size_t total = (size_t)n * hw;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    const size_t img = i / hw, pos = i - img * hw;
+    const float* src = x + img * (size_t)c * hw + pos;
+    float* dst = y + i * c;
+    for (int ch = 0; ch < c; ++ch) dst[ch] = src[(size_t)ch * hw];
+  }
+}
+
+}  // namespace
+
+hipError_t nchw_to_nhwc(const float* x, float* y, int n, int c, int hw, hipStream_t st) {
+  if (!x || !y || n <= 0 || c <= 0 || hw <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3(grid_for((size_t)n * hw)), dim3(THREADS), 0, st, x, y, n, c, hw);
+  return hipGetLastError();
+}
+
+hipError_t filter_flip_transpose(const float* w, float* wt, int cout, int cin, int r, int s,
+                                 hipStream_t st) {
+  if (!w || !wt || cout <= 0 || cin <= 0 || r <= 0 || s <= 0 || r * s > 65535) return hipErrorInvalidValue;
+  const dim3 grid((cin + 31) / 32, (cout + 31) / 32, r * s);
+  if (grid.y > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(flip_transpose_kernel, grid, dim3(256), 0, st, w, wt, cout, cin, r, s);
+  return hipGetLastError();
+}
+
+hipError_t maxpool_forward(const float* x, float* y, int n, int h, int wd, int c, int r, int s,
+                           int stride, int pad, hipStream_t st) {
+  if (!x || !y || n <= 0 || h <= 0 || wd <= 0 || c <= 0 || (c & 3) || r <= 0 || s <= 0 || stride <= 0 ||
+      pad < 0 || pad >= r || pad >= s)
+    return hipErrorInvalidValue;
+  const int ho = (h + 2 * pad - r) / stride + 1, wo = (wd + 2 * pad - s) / stride + 1;
+  if (ho <= 0 || wo <= 0) return hipErrorInvalidValue;
+  const size_t total = (size_t)n * ho * wo * (c / 4);
+  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total)), dim3(THREADS), 0, st, x, y, n, h, wd, c, r, s,
+                     stride, pad, ho, wo);
+  return hipGetLastError();
+}
+
+hipError_t maxpool_backward(const float* x, const float* dy, float* dx, int n, int h, int wd, int c,
+                            int r, int s, int stride, int pad, int accumulate, hipStream_t st) {
+  if (!x || !dy || !dx || n <= 0 || h <= 0 || wd <= 0 || c <= 0 || r <= 0 || s <= 0 || stride <= 0 ||
+      pad < 0 || pad >= r || pad >= s)
+    return hipErrorInvalidValue;
+  const int ho = (h + 2 * pad - r) / stride + 1, wo = (wd + 2 * pad - s) / stride + 1;
+  if (ho <= 0 || wo <= 0) return hipErrorInvalidValue;
+  const size_t total = (size_t)n * h * wd * c;
+  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total)), dim3(THREADS), 0, st, x, dy, dx, n, h, wd, c,
+                     r, s, stride, pad, ho, wo, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t gap_forward(const float* x, float* y, int n, int hw, int c, hipStream_t st) {
+  if (!x || !y || n <= 0 || hw <= 0 || c <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gap_fwd_kernel, dim3(grid_for((size_t)n * c)), dim3(THREADS), 0, st, x, y, n, hw, c);
+  return hipGetLastError();
+}
+
+hipError_t gap_backward(const float* dy, float* dx, int n, int hw, int c, int accumulate, hipStream_t st) {
+  if (!dy || !dx || n <= 0 || hw <= 0 || c <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gap_bwd_kernel, dim3(grid_for((size_t)n * hw * c)), dim3(THREADS), 0, st, dy, dx, n, hw,
+                     c, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t bias_add(float* y, const float* b, long rows, int c, hipStream_t st) {
+  if (!y || !b || rows <= 0 || c <= 0) return hipErrorInvalidValue;
+  const size_t total = (size_t)rows * c;
+  hipLaunchKernelGGL(bias_add_kernel, dim3(grid_for(total)), dim3(THREADS), 0, st, y, b, total, c);
+  return hipGetLastError();
+}
+
+hipError_t column_sum(const float* dy, float* db, long rows, int c, hipStream_t st) {
+  if (!dy || !db || rows <= 0 || c <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(column_sum_kernel, dim3((c + THREADS - 1) / THREADS), dim3(THREADS), 0, st, dy, db, rows,
+                     c);
+  return hipGetLastError();
+}
+
+hipError_t softmax_ce_forward(const float* z, const int32_t* labels, float* loss_rows, float* loss,
+                              int n, int classes, hipStream_t st) {
+  if (!z || !labels || !loss_rows || !loss || n <= 0 || classes <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(n), dim3(THREADS), 0, st, z, labels, loss_rows,
+                     (float*)nullptr, n, classes);
+  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(64), 0, st, loss_rows, loss, n);
+  return hipGetLastError();
+}
+
+hipError_t softmax_ce_backward(const float* z, const int32_t* labels, float* dz, int n, int classes,
+                               hipStream_t st) {
+  if (!z || !labels || !dz || n <= 0 || classes <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(n), dim3(THREADS), 0, st, z, labels, (float*)nullptr, dz, n,
+                     classes);
+  return hipGetLastError();
+}
+
+hipError_t sgd_update(float* w, const float* g, float lr, size_t count, hipStream_t st) {
+  if (!w || !g) return hipErrorInvalidValue;
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(count)), dim3(THREADS), 0, st, w, g, lr, count);
+  return hipGetLastError();
+}
+
+hipError_t fill_zero(float* p, size_t count, hipStream_t st) {
+  if (!p) return hipErrorInvalidValue;
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(count)), dim3(THREADS), 0, st, p, count);
+  return hipGetLastError();
+}
+
+}  // namespace acc

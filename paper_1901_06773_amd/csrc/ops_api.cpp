@@ -1,0 +1,94 @@
+// Single-operation entry points of the C ABI: thin argument checks around the kernel
+// launchers, for per-layer parity tests and roofline measurements.
+#include <hip/hip_runtime.h>
+
+#include "../../include/accudnn.h"
+#include "kernels.h"
+
+using namespace acc;
+
+namespace {
+inline size_t al256(size_t b) { return (b + 255) & ~(size_t)255; }
+inline int out_dim(int in, int r, int stride, int pad) { return (in + 2 * pad - r) / stride + 1; }
+inline bool conv_ok(int n, int h, int w, int cin, int cout, int r, int s, int stride, int pad) {
+  return n > 0 && h > 0 && w > 0 && cin > 0 && cout > 0 && r > 0 && s == r && stride > 0 && pad >= 0 && pad < r &&
+         h + 2 * pad >= r && w + 2 * pad >= s;
+}
+inline int status(hipError_t e) { return e == hipSuccess ? ACC_OK : (e == hipErrorInvalidValue ? ACC_EINVAL : ACC_EHIP); }
+}  // namespace
+
+extern "C" size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, int r, int s, int stride, int pad) {
+  if (!conv_ok(n, h, w, cin, cout, r, s, stride, pad)) return 0;
+  const int ho = out_dim(h, r, stride, pad), wo = out_dim(w, s, stride, pad);
+  return al256(wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s)) + al256((size_t)cout * cin * r * s * sizeof(float));
+}
+
+extern "C" int acc_op_conv_fwd(const float* x, const float* w, float* y, int n, int h, int wd, int cin, int cout,
+                               int r, int s, int stride, int pad, void* stream) {
+  if (!x || !w || !y || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+  ConvGeom g{};
+  g.in = x; g.w = w; g.out = y;
+  g.n_img = n; g.h = h; g.wd = wd; g.c = cin;
+  g.p = out_dim(h, r, stride, pad); g.q = out_dim(wd, s, stride, pad); g.n_out = cout;
+  g.r = r; g.s = s; g.stride = stride; g.pad = pad;
+  g.out_h = g.p; g.out_w = g.q; g.out_stride = 1;
+  return status(conv_igemm(g, (hipStream_t)stream));
+}
+
+extern "C" int acc_op_conv_dgrad(const float* dy, const float* w, float* dx, int n, int h, int wd, int cin, int cout,
+                                 int r, int s, int stride, int pad, int accumulate, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!dy || !w || !dx || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+  if (stride > 1 && (r > 1 || pad > 0)) return ACC_EINVAL;   // strided data gradient: 1x1 only
+  const size_t filt = al256((size_t)cout * cin * r * s * sizeof(float));
+  if (!workspace || workspace_bytes < filt) return ACC_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  float* wt = (float*)workspace;
+  hipError_t e = filter_flip_transpose(w, wt, cout, cin, r, s, st);
+  if (e != hipSuccess) return status(e);
+  const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
+  ConvGeom g{};
+  g.in = dy; g.w = wt; g.out = dx;
+  g.n_img = n; g.h = ho; g.wd = wo; g.c = cout; g.n_out = cin;
+  g.r = r; g.s = s; g.stride = 1; g.accumulate = accumulate;
+  g.out_h = h; g.out_w = wd;
+  if (stride == 1) {
+    g.p = h; g.q = wd; g.pad = r - 1 - pad; g.out_stride = 1;
+  } else {
+    g.p = ho; g.q = wo; g.pad = 0; g.out_stride = stride;
+    if (!accumulate) {
+      e = fill_zero(dx, (size_t)n * h * wd * cin, st);
+      if (e != hipSuccess) return status(e);
+    }
+  }
+  return status(conv_igemm(g, st));
+}
+
+extern "C" int acc_op_conv_wgrad(const float* x, const float* dy, float* dw, int n, int h, int wd, int cin, int cout,
+                                 int r, int s, int stride, int pad, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  if (!x || !dy || !dw || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+  const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
+  const size_t need = wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s);
+  if (need && (!workspace || workspace_bytes < need)) return ACC_EINVAL;
+  WgradGeom g{};
+  g.x = x; g.dy = dy; g.dw = dw;
+  g.n_img = n; g.h = h; g.wd = wd; g.cin = cin; g.p = ho; g.q = wo; g.cout = cout;
+  g.r = r; g.s = s; g.stride = stride; g.pad = pad; g.workspace = (float*)workspace;
+  return status(conv_wgrad(g, (hipStream_t)stream));
+}
+
+extern "C" size_t acc_op_bn_workspace(int c) { return c > 0 ? al256(bn_workspace_bytes(c)) : 0; }
+
+extern "C" int acc_op_bn_fwd(const float* x, const float* gamma, const float* beta, const float* res, float* y,
+                             float* mean, float* istd, int rows, int c, int relu, float eps, void* workspace,
+                             void* stream) {
+  return status(bn_forward(x, gamma, beta, res, y, mean, istd, rows, c, relu, eps, workspace, (hipStream_t)stream));
+}
+
+extern "C" int acc_op_bn_bwd(const float* x, const float* dy, const float* y, const float* gamma, const float* mean,
+                             const float* istd, float* dx, float* dgamma, float* dbeta, float* g_out, int rows, int c,
+                             void* workspace, void* stream) {
+  return status(bn_backward(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, rows, c, workspace,
+                            (hipStream_t)stream));
+}

@@ -1,0 +1,190 @@
+"""GPU parity of the single operations (C ABI acc_op_*) against the CPU oracle,
+element by element, on seeded inputs that span several tiles and a ragged tail.
+
+Tolerance (fp32 MFMA / fp32 vector arithmetic against the oracle's double
+accumulation): ||gpu - oracle||_2 <= 1e-4 ||oracle||_2 and
+max|gpu - oracle| <= 1e-4 max|oracle| per tensor."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import synth as S
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def B():
+    from paper_1901_06773_amd import binding
+    return binding
+
+
+def close(gpu: np.ndarray, ref: np.ndarray, what: str, tol: float = TOL):
+    gpu = gpu.astype(np.float64); ref = ref.astype(np.float64)
+    assert gpu.shape == ref.shape, what
+    assert np.isfinite(gpu).all(), f"{what}: non-finite values"
+    nr = np.linalg.norm(ref)
+    assert np.linalg.norm(gpu - ref) <= tol * max(nr, 1e-30), \
+        f"{what}: rel l2 {np.linalg.norm(gpu - ref) / max(nr, 1e-30):.3e}"
+    assert np.abs(gpu - ref).max() <= tol * max(np.abs(ref).max(), 1e-30), \
+        f"{what}: max abs {np.abs(gpu - ref).max():.3e} vs scale {np.abs(ref).max():.3e}"
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def nhwc(a):   # NCHW numpy -> NHWC numpy
+    return np.ascontiguousarray(a.transpose(0, 2, 3, 1))
+
+
+def nchw(a):
+    return np.ascontiguousarray(a.transpose(0, 3, 1, 2))
+
+
+def ohwi(w):   # OIHW -> OHWI
+    return np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+
+
+def oihw(w):
+    return np.ascontiguousarray(w.transpose(0, 3, 1, 2))
+
+
+def rnd(seed, *shape):
+    return S.normal(seed, int(np.prod(shape))).astype(np.float32).reshape(shape)
+
+
+CONV_CASES = [  # n, h, w, cin, cout, r, stride, pad
+    (2, 14, 14, 64, 96, 3, 1, 1),      # fast path, N tail, M = 392 (ragged over 128 and 64)
+    (3, 9, 9, 128, 256, 1, 1, 0),      # 1x1, M = 243
+    (2, 16, 16, 64, 128, 1, 2, 0),     # strided 1x1 (projection shortcut)
+    (2, 9, 9, 32, 64, 1, 2, 0),        # strided 1x1, odd size
+    (5, 28, 28, 32, 64, 3, 1, 1),      # several tiles (M = 3920)
+    (2, 16, 16, 16, 16, 3, 1, 1),      # config-1 sized: per-element path
+    (2, 16, 16, 64, 16, 1, 1, 0),      # fast loader with cout < 64
+    (2, 12, 10, 20, 24, 3, 1, 1),      # channels not a multiple of 32, non-square image
+    (1, 7, 7, 96, 40, 3, 1, 1),        # single image, ragged everything
+    (2, 23, 23, 8, 16, 7, 2, 3),       # stem-like filter
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_fwd(case):
+    n, h, w, cin, cout, r, stride, pad = case
+    x = rnd(1, n, cin, h, w); wt = rnd(2, cout, cin, r, r) * np.float32(np.sqrt(2.0 / (cin * r * r)))
+    ref = O.conv_fwd(x, wt, stride, pad)
+    dx, dw = dev(nhwc(x)), dev(ohwi(wt))
+    y = torch.full((n, ref.shape[2], ref.shape[3], cout), float("nan"), device="cuda")
+    B().op_conv_fwd(dx, dw, y, stride, pad)
+    torch.cuda.synchronize()
+    close(nchw(y.cpu().numpy()), ref, f"conv_fwd {case}")
+
+
+@pytest.mark.parametrize("case", [c for c in CONV_CASES if c[6] == 1 or c[5] == 1])
+@pytest.mark.parametrize("accumulate", [False, True])
+def test_conv_dgrad(case, accumulate):
+    n, h, w, cin, cout, r, stride, pad = case
+    wt = rnd(2, cout, cin, r, r) * np.float32(np.sqrt(2.0 / (cin * r * r)))
+    ho, wo = O.out_dim(h, r, stride, pad), O.out_dim(w, r, stride, pad)
+    dy = rnd(3, n, cout, ho, wo)
+    ref = O.conv_dgrad(dy, wt, (n, cin, h, w), stride, pad)
+    base = rnd(4, n, cin, h, w) if accumulate else None
+    if accumulate:
+        ref = (ref.astype(np.float64) + base).astype(np.float32)
+    b = B()
+    ws = torch.empty(max(b.op_conv_workspace(n, h, w, cin, cout, r, stride, pad), 256), dtype=torch.uint8, device="cuda")
+    dxt = dev(nhwc(base)) if accumulate else torch.full((n, h, w, cin), float("nan"), device="cuda")
+    b.op_conv_dgrad(dev(nhwc(dy)), dev(ohwi(wt)), dxt, stride, pad, ws, accumulate)
+    torch.cuda.synchronize()
+    close(nchw(dxt.cpu().numpy()), ref, f"conv_dgrad {case} acc={accumulate}")
+
+
+WGRAD_CASES = CONV_CASES + [
+    (16, 28, 28, 64, 64, 3, 1, 1),     # M = 12544: split over the minibatch positions
+    (4, 14, 14, 256, 128, 1, 1, 0),    # 128-wide column tiles
+    (8, 1, 1, 64, 10, 1, 1, 0),        # fc-shaped, cout not a multiple of 4
+]
+
+
+@pytest.mark.parametrize("case", WGRAD_CASES)
+def test_conv_wgrad(case):
+    n, h, w, cin, cout, r, stride, pad = case
+    x = rnd(1, n, cin, h, w)
+    ho, wo = O.out_dim(h, r, stride, pad), O.out_dim(w, r, stride, pad)
+    dy = rnd(3, n, cout, ho, wo)
+    ref = O.conv_wgrad(x, dy, (cout, cin, r, r), stride, pad)
+    b = B()
+    ws = torch.empty(max(b.op_conv_workspace(n, h, w, cin, cout, r, stride, pad), 256), dtype=torch.uint8, device="cuda")
+    dw = torch.full((cout, r, r, cin), float("nan"), device="cuda")
+    b.op_conv_wgrad(dev(nhwc(x)), dev(nhwc(dy)), dw, stride, pad, ws)
+    torch.cuda.synchronize()
+    close(oihw(dw.cpu().numpy()), ref, f"conv_wgrad {case}")
+
+
+BN_CASES = [  # n, c, h, w
+    (2, 16, 16, 16),
+    (3, 64, 7, 9),
+    (2, 256, 14, 14),
+    (5, 2048, 3, 3),       # two column slices
+    (1, 12, 1, 1),         # single element per channel: variance 0
+    (4, 1024, 1, 1),
+    (37, 64, 11, 13),      # many slabs, ragged rows
+]
+
+
+@pytest.mark.parametrize("case", BN_CASES)
+@pytest.mark.parametrize("variant", ["plain", "relu", "add_relu"])
+def test_bn_fwd_bwd(case, variant):
+    n, c, h, w = case
+    x = rnd(5, n, c, h, w) * np.float32(1.7) + np.float32(0.3)
+    gamma = (1.0 + 0.2 * rnd(6, c)).astype(np.float32)
+    beta = (0.1 * rnd(7, c)).astype(np.float32)
+    res = rnd(8, n, c, h, w) if variant == "add_relu" else None
+    relu = variant != "plain"
+    bn, mean, istd = O.bn_fwd(x, gamma, beta, O.BN_EPS)
+    pre = bn if res is None else bn + res
+    ref_y = O.relu_fwd(pre) if relu else pre
+    b = B()
+    ws = torch.empty(b.op_bn_workspace(c), dtype=torch.uint8, device="cuda")
+    xd = dev(nhwc(x))
+    y = torch.full_like(xd, float("nan"))
+    m_d = torch.empty(c, device="cuda"); i_d = torch.empty(c, device="cuda")
+    b.op_bn_fwd(xd, dev(gamma), dev(beta), dev(nhwc(res)) if res is not None else None, y, m_d, i_d, relu, O.BN_EPS, ws)
+    torch.cuda.synchronize()
+    close(nchw(y.cpu().numpy()), ref_y, f"bn_fwd y {case} {variant}")
+    close(m_d.cpu().numpy(), mean, "bn mean", 1e-5)
+    close(i_d.cpu().numpy(), istd, "bn istd", 1e-5)
+
+    # backward: dy masked by the ReLU output, dx / dgamma / dbeta; masked gradient in place
+    dy = rnd(9, n, c, h, w)
+    g = O.relu_bwd(ref_y, dy) if relu else dy
+    ref_dx, ref_dg, ref_db = O.bn_bwd(x, g, gamma, mean, istd)
+    dyd = dev(nhwc(dy))
+    dxd = torch.full_like(xd, float("nan"))
+    dg_d = torch.empty(c, device="cuda"); db_d = torch.empty(c, device="cuda")
+    y_ref_d = dev(nhwc(ref_y))     # mask taken from the oracle's output: same decision on both sides
+    b.op_bn_bwd(xd, dyd, y_ref_d if relu else None, dev(gamma), dev(mean.astype(np.float32)),
+                dev(istd.astype(np.float32)), dxd, dg_d, db_d, dyd if variant == "add_relu" else None, ws)
+    torch.cuda.synchronize()
+    scale = 1e-4 if n * h * w > 1 else 1e-3
+    close(nchw(dxd.cpu().numpy()), ref_dx, f"bn_bwd dx {case} {variant}", scale)
+    close(dg_d.cpu().numpy(), ref_dg, "bn dgamma", scale)
+    close(db_d.cpu().numpy(), ref_db, "bn dbeta")
+    if variant == "add_relu":
+        np.testing.assert_array_equal(nchw(dyd.cpu().numpy()), g)   # masking is exact
+
+
+def test_bad_arguments_are_rejected():
+    b = B()
+    x = torch.zeros(1, 4, 4, 8, device="cuda")
+    w = torch.zeros(8, 3, 3, 8, device="cuda")
+    y = torch.zeros(1, 4, 4, 8, device="cuda")
+    with pytest.raises(b.AccError):
+        b.op_conv_fwd(x, w, y, 0, 1)        # stride 0
+    with pytest.raises(b.AccError):
+        b.op_conv_fwd(x, w, y, 1, 3)        # pad >= r
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(b.AccError):
+        b.op_conv_dgrad(y, w, x, 2, 1, ws)  # strided 3x3 data gradient is not supported
