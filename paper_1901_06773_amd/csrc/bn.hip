@@ -143,7 +143,7 @@ __device__ __forceinline__ void sum_partials(const double* __restrict__ part, in
   *out1 = a1;
 }
 
-// forward:  mean, istd; coef[0] = scale = gamma*istd, coef[1] = shift = beta - mean*scale
+// forward:  mean, istd; coef[0] = scale = gamma*istd, coef[1] = mean, coef[2] = beta
 __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
     const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ beta,
     float* __restrict__ mean, float* __restrict__ istd, float* __restrict__ coef, long rows, int c,
@@ -162,7 +162,8 @@ __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
   istd[ch] = (float)is;
   const double scale = (double)gamma[ch] * is;
   coef[ch] = (float)scale;
-  coef[c + ch] = (float)((double)beta[ch] - mu * scale);
+  coef[c + ch] = (float)mu;
+  coef[2 * c + ch] = beta[ch];
 }
 
 // backward: dbeta, dgamma; coef[0] = a = gamma*istd, coef[1] = dbeta/m, coef[2] = dgamma/m
@@ -183,7 +184,8 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_finish_kernel(
   coef[2 * c + ch] = (float)(dg / m);
 }
 
-// y = relu?(x*scale + shift (+ res)), float4 per thread, grid-stride
+// y = relu?((x-mean)*scale + beta (+ res)), float4 per thread, grid-stride.  Subtracting the
+// mean first keeps the result exact where x equals the mean (a channel of constant values).
 __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restrict__ x,
                                                            const float* __restrict__ res,
                                                            const float* __restrict__ coef,
@@ -194,12 +196,13 @@ __global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restri
     const int g = (int)(i % cg);
     const float4 xv = reinterpret_cast<const float4*>(x)[i];
     const float4 sc = reinterpret_cast<const float4*>(coef)[g];
-    const float4 sh = reinterpret_cast<const float4*>(coef + c)[g];
+    const float4 mu = reinterpret_cast<const float4*>(coef + c)[g];
+    const float4 be = reinterpret_cast<const float4*>(coef + 2 * c)[g];
     float4 o;
-    o.x = fmaf(xv.x, sc.x, sh.x);
-    o.y = fmaf(xv.y, sc.y, sh.y);
-    o.z = fmaf(xv.z, sc.z, sh.z);
-    o.w = fmaf(xv.w, sc.w, sh.w);
+    o.x = fmaf(xv.x - mu.x, sc.x, be.x);
+    o.y = fmaf(xv.y - mu.y, sc.y, be.y);
+    o.z = fmaf(xv.z - mu.z, sc.z, be.z);
+    o.w = fmaf(xv.w - mu.w, sc.w, be.w);
     if (res) {
       const float4 rv = reinterpret_cast<const float4*>(res)[i];
       o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
