@@ -175,8 +175,20 @@ int acc_get_step_io(const acc_ctx* ctx, int step, int32_t* reads, int max_reads,
 int acc_train_step(acc_ctx* ctx, const float* images, int images_loc, const int32_t* labels,
                    float lr, float* loss_out);
 int acc_get_stats(acc_ctx* ctx, acc_stats* out);
-/* profiling = 1 records timing events around every kernel group and copy (slower) */
-int acc_set_profiling(acc_ctx* ctx, int on);
+/* level 0: off.  1: timing events around every step and every copy.  2: timing events
+ * directly around every convolution kernel launch.  3: both.  Events cost host time. */
+int acc_set_profiling(acc_ctx* ctx, int level);
+/* Per convolution kernel instance, summed over the last train_step run at level 2 or 3:
+ * launches, milliseconds between the events around the launches, algorithmic flops
+ * (2 * k*Ho*Wo * Cout * Cin*R*S per GEMM).  Returns the number of entries written. */
+typedef struct {
+  char name[48];
+  int32_t launches;
+  int32_t reserved;
+  double ms;
+  double flops;
+} acc_kernel_profile;
+int acc_get_kernel_profile(acc_ctx* ctx, acc_kernel_profile* out, int max_entries);
 /* per-step kernel time of the last profiled train_step, milliseconds; n = step count */
 int acc_get_step_times_ms(acc_ctx* ctx, double* ms, int n);
 

@@ -78,6 +78,11 @@ class acc_stats(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class acc_kernel_profile(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("reserved", C.c_int32),
+                ("ms", C.c_double), ("flops", C.c_double)]
+
+
 # every symbol include/accudnn.h declares, with its signature
 _VP, _I, _SZ, _F, _D = C.c_void_p, C.c_int, C.c_size_t, C.c_float, C.c_double
 _PROTOS = {
@@ -103,6 +108,7 @@ _PROTOS = {
     "acc_get_stats": (_I, [_VP, C.POINTER(acc_stats)]),
     "acc_set_profiling": (_I, [_VP, _I]),
     "acc_get_step_times_ms": (_I, [_VP, C.POINTER(_D), _I]),
+    "acc_get_kernel_profile": (_I, [_VP, C.POINTER(acc_kernel_profile), _I]),
     "acc_op_conv_workspace": (_SZ, [_I] * 9),
     "acc_op_conv_fwd": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_VP]),
     "acc_op_conv_dgrad": (_I, [_VP, _VP, _VP] + [_I] * 10 + [_VP, _SZ, _VP]),
@@ -268,8 +274,15 @@ class Context:
         self._check(_lib.acc_get_stats(self._h, C.byref(s)))
         return s.as_dict()
 
-    def set_profiling(self, on: bool):
-        self._check(_lib.acc_set_profiling(self._h, 1 if on else 0))
+    def set_profiling(self, level: int):
+        """0 off, 1 per step and copy, 2 per convolution kernel launch, 3 both."""
+        self._check(_lib.acc_set_profiling(self._h, int(level)))
+
+    def kernel_profile(self) -> list:
+        arr = (acc_kernel_profile * 16)()
+        n = self._check(_lib.acc_get_kernel_profile(self._h, arr, 16))
+        return [dict(name=arr[i].name.decode(), launches=arr[i].launches, ms=arr[i].ms, flops=arr[i].flops)
+                for i in range(n)]
 
     def step_times_ms(self) -> np.ndarray:
         n = self.step_count()

@@ -240,19 +240,33 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 }
 
 template <int BM, int BN, bool FAST>
-hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st) {
+hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchProbe* probe) {
   const int tm = (M + BM - 1) / BM, tn = (g.n_out + BN - 1) / BN;
   const long tiles = (long)tm * tn;
   if (tiles <= 0 || tiles > (1L << 30)) return hipErrorInvalidValue;
   const int grid = (int)((tiles + 7) / 8 * 8);
+  if (probe->before) (void)hipEventRecord(probe->before, st);
   hipLaunchKernelGGL((igemm_kernel<BM, BN, FAST>), dim3(grid), dim3(256), 0, st, g, M, K, tn,
                      (int)tiles);
+  if (probe->after) (void)hipEventRecord(probe->after, st);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t conv_igemm(const ConvGeom& g, hipStream_t st) {
+const char* conv_variant_name(int v) {
+  static const char* names[V_COUNT] = {"igemm_kernel<128,128,fast>", "igemm_kernel<128,64,fast>",
+                                       "igemm_kernel<64,64,fast>", "igemm_kernel<64,64,generic>",
+                                       "wgrad_kernel<128,128,fast>", "wgrad_kernel<128,64,fast>",
+                                       "wgrad_kernel<64,128,fast>", "wgrad_kernel<64,64,fast>",
+                                       "wgrad_kernel<64,64,generic>"};
+  return (v >= 0 && v < V_COUNT) ? names[v] : "?";
+}
+
+hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
+  LaunchProbe local;
+  if (!probe) probe = &local;
+  int* variant = &probe->variant;
   if (!g.in || !g.w || !g.out) return hipErrorInvalidValue;
   if (g.n_img <= 0 || g.h <= 0 || g.wd <= 0 || g.c <= 0 || g.p <= 0 || g.q <= 0 || g.n_out <= 0 ||
       g.r <= 0 || g.s <= 0 || g.stride <= 0 || g.pad < 0 || g.out_stride <= 0)
@@ -266,7 +280,7 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st) {
   if (M >= (1L << 31) || K >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31))
     return hipErrorInvalidValue;
   const bool fast = (g.c % BK == 0) && !g.in_nchw;
-  if (!fast) return launch<64, 64, false>(g, (int)M, (int)K, st);
+  if (!fast) { *variant = V_IGEMM_GENERIC; return launch<64, 64, false>(g, (int)M, (int)K, st, probe); }
   // tile choice depends on the GEMM shape only (never on addresses or on the swap plan)
   auto cost = [&](int bm, int bn, double eff) {
     const double tiles = (double)((M + bm - 1) / bm) * ((g.n_out + bn - 1) / bn);
@@ -276,9 +290,10 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st) {
   const double c128 = g.n_out > 64 ? cost(128, 128, 1.0) : 1e300;
   const double c12864 = cost(128, 64, 0.92);
   const double c64 = cost(64, 64, 0.80);
-  if (c128 <= c12864 && c128 <= c64) return launch<128, 128, true>(g, (int)M, (int)K, st);
-  if (c12864 <= c64) return launch<128, 64, true>(g, (int)M, (int)K, st);
-  return launch<64, 64, true>(g, (int)M, (int)K, st);
+  if (c128 <= c12864 && c128 <= c64) { *variant = V_IGEMM_128x128; return launch<128, 128, true>(g, (int)M, (int)K, st, probe); }
+  if (c12864 <= c64) { *variant = V_IGEMM_128x64; return launch<128, 64, true>(g, (int)M, (int)K, st, probe); }
+  *variant = V_IGEMM_64x64;
+  return launch<64, 64, true>(g, (int)M, (int)K, st, probe);
 }
 
 }  // namespace acc

@@ -255,7 +255,7 @@ size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, 
   return (size_t)splits * cout * r * s * cin * sizeof(float);
 }
 
-hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st) {
+hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe) {
   if (!g.x || !g.dy || !g.dw) return hipErrorInvalidValue;
   if (g.n_img <= 0 || g.h <= 0 || g.wd <= 0 || g.cin <= 0 || g.p <= 0 || g.q <= 0 || g.cout <= 0 ||
       g.r <= 0 || g.s <= 0 || g.stride <= 0 || g.pad < 0)
@@ -273,11 +273,15 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st) {
 #define WG_LAUNCH(BM_, BN_, FAST_)                                                              \
   hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, FAST_>), grid, dim3(256), 0, st, g, (int)Mrows,   \
                      (int)J, c.tiles_j, c.chunks_per_split, out, count)
-  if (!c.fast) WG_LAUNCH(64, 64, false);
-  else if (c.bm == 128 && c.bn == 128) WG_LAUNCH(128, 128, true);
-  else if (c.bm == 128 && c.bn == 64) WG_LAUNCH(128, 64, true);
-  else if (c.bm == 64 && c.bn == 128) WG_LAUNCH(64, 128, true);
-  else WG_LAUNCH(64, 64, true);
+  int v;
+  if (probe && probe->before) (void)hipEventRecord(probe->before, st);
+  if (!c.fast) { v = V_WGRAD_GENERIC; WG_LAUNCH(64, 64, false); }
+  else if (c.bm == 128 && c.bn == 128) { v = V_WGRAD_128x128; WG_LAUNCH(128, 128, true); }
+  else if (c.bm == 128 && c.bn == 64) { v = V_WGRAD_128x64; WG_LAUNCH(128, 64, true); }
+  else if (c.bm == 64 && c.bn == 128) { v = V_WGRAD_64x128; WG_LAUNCH(64, 128, true); }
+  else { v = V_WGRAD_64x64; WG_LAUNCH(64, 64, true); }
+  if (probe && probe->after) (void)hipEventRecord(probe->after, st);
+  if (probe) probe->variant = v;
 #undef WG_LAUNCH
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -49,7 +49,13 @@ struct acc_ctx {
   std::vector<hipEvent_t> prof_a, prof_b, prof_copy_a, prof_copy_b;
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
   bool profiling = false;
+  bool kernel_profiling = false;
   bool calibrating = false;     // input batch is synthesised on the device
+  struct KProbe { int variant; double flops; hipEvent_t a, b; };
+  std::vector<KProbe> kprobes;  // one per convolution kernel launch of the last profiled step
+  size_t kprobes_used = 0;
+  double k_ms[V_COUNT] = {}, k_flops[V_COUNT] = {};
+  long k_launches[V_COUNT] = {};
   std::vector<double> step_ms;
   std::vector<size_t> cur_off;  // per tensor, while executing
   acc_stats stats{};
@@ -59,6 +65,21 @@ struct acc_ctx {
   int hipfail(hipError_t e, const char* what) {
     err = std::string(what) + ": " + hipGetErrorString(e);
     return ACC_EHIP;
+  }
+  // hands out an event pair for one kernel launch (kernel-level profiling only)
+  LaunchProbe* next_probe(LaunchProbe* lp, double flops) {
+    if (!kernel_profiling) return nullptr;
+    if (kprobes_used == kprobes.size()) {
+      KProbe kp{-1, 0.0, nullptr, nullptr};
+      if (hipEventCreate(&kp.a) != hipSuccess || hipEventCreate(&kp.b) != hipSuccess) return nullptr;
+      kprobes.push_back(kp);
+    }
+    KProbe& kp = kprobes[kprobes_used++];
+    kp.flops = flops;
+    kp.variant = -1;
+    lp->before = kp.a;
+    lp->after = kp.b;
+    return lp;
   }
   void drop_events() {
     for (auto* v : {&ev_step, &ev_d2h, &ev_h2d, &prof_a, &prof_b, &prof_copy_a, &prof_copy_b}) {
@@ -185,6 +206,7 @@ extern "C" void acc_destroy(acc_ctx* c) {
     (void)hipStreamSynchronize(c->s_o);
     (void)hipStreamSynchronize(c->s_i);
     c->drop_events();
+    for (auto& kp : c->kprobes) { (void)hipEventDestroy(kp.a); (void)hipEventDestroy(kp.b); }
     if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
     if (c->ev_end) (void)hipEventDestroy(c->ev_end);
     if (c->h_loss) (void)hipHostFree(c->h_loss);
@@ -362,6 +384,22 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
   const acc_layer* l = s.layer >= 0 ? &g.layers[s.layer] : nullptr;
   float* w = s.layer >= 0 ? c->d_params + g.params[s.layer].offset : nullptr;
   float* dw = s.layer >= 0 ? c->d_grads + g.params[s.layer].offset : nullptr;
+  auto igemm = [&](const ConvGeom& cg, double flops) {
+    LaunchProbe lp;
+    LaunchProbe* pp = c->next_probe(&lp, flops);
+    const hipError_t e = conv_igemm(cg, st, pp);
+    if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
+    return e;
+  };
+  auto wgrad = [&](const WgradGeom& wg, double flops) {
+    LaunchProbe lp;
+    LaunchProbe* pp = c->next_probe(&lp, flops);
+    const hipError_t e = conv_wgrad(wg, st, pp);
+    if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
+    return e;
+  };
+  // algorithmic flops of one of the three GEMMs of a convolution at this minibatch
+  const double conv_flops = s.flops_per_image * k / (s.phase == 1 && s.dx >= 0 ? 2.0 : 1.0);
   switch (s.kind) {
     case K_INPUT_F:
       return nchw_to_nhwc(ptr(s.x), ptr(s.y), k, g.in_c, g.in_h * g.in_w, st);
@@ -372,7 +410,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.p = T(s.y).h; cg.q = T(s.y).w; cg.n_out = l->cout;
       cg.r = l->r; cg.s = l->s; cg.stride = l->stride; cg.pad = l->pad;
       cg.out_h = cg.p; cg.out_w = cg.q; cg.out_stride = 1; cg.accumulate = 0;
-      return conv_igemm(cg, st);
+      return igemm(cg, conv_flops);
     }
     case K_BN_F: {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
@@ -388,7 +426,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.in = ptr(s.x); cg.w = w; cg.out = ptr(s.y);
       cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cin; cg.p = 1; cg.q = 1; cg.n_out = l->cout;
       cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
-      hipError_t e = conv_igemm(cg, st);
+      hipError_t e = igemm(cg, conv_flops);
       if (e != hipSuccess) return e;
       return bias_add(ptr(s.y), w + (size_t)l->cout * l->cin, k, l->cout, st);
     }
@@ -401,7 +439,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw;
       wg.n_img = k; wg.h = 1; wg.wd = 1; wg.cin = l->cin; wg.p = 1; wg.q = 1; wg.cout = l->cout;
       wg.r = 1; wg.s = 1; wg.stride = 1; wg.pad = 0; wg.workspace = ptr(s.ws2);
-      hipError_t e = conv_wgrad(wg, st);
+      hipError_t e = wgrad(wg, conv_flops);
       if (e != hipSuccess) return e;
       e = column_sum(ptr(s.dy), dw + (size_t)l->cout * l->cin, k, l->cout, st);
       if (e != hipSuccess) return e;
@@ -412,7 +450,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cout; cg.p = 1; cg.q = 1; cg.n_out = l->cin;
       cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
       cg.accumulate = s.dx_accumulate;
-      return conv_igemm(cg, st);
+      return igemm(cg, conv_flops);
     }
     case K_GAP_B:
       return gap_backward(ptr(s.dy), ptr(s.dx), k, T(s.dx).h * T(s.dx).w, T(s.dx).c, s.dx_accumulate, st);
@@ -431,7 +469,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       wg.n_img = k; wg.h = h; wg.wd = wd; wg.cin = l->cin; wg.p = ho; wg.q = wo; wg.cout = l->cout;
       wg.r = l->r; wg.s = l->s; wg.stride = l->stride; wg.pad = l->pad;
       wg.workspace = ptr(s.ws2);
-      hipError_t e = conv_wgrad(wg, st);
+      hipError_t e = wgrad(wg, conv_flops);
       if (e != hipSuccess || s.dx < 0) return e;
       e = filter_flip_transpose(w, ptr(s.ws), l->cout, l->cin, l->r, l->s, st);
       if (e != hipSuccess) return e;
@@ -449,7 +487,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
           if (e != hipSuccess) return e;
         }
       }
-      return conv_igemm(cg, st);
+      return igemm(cg, conv_flops);
     }
     case K_SGD:
       return sgd_update(c->d_params, c->d_grads, lr, g.param_elems, st);
@@ -485,6 +523,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
     }
   }
   uint64_t bytes_out = 0, bytes_in = 0;
+  c->kprobes_used = 0;
   HIPCHK(c, hipEventRecord(c->ev_begin, c->s_c));
   for (const Instr& in : P.instrs) {
     switch (in.op) {
@@ -562,6 +601,18 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   c->stats.bytes_in = bytes_in;
   c->stats.steps_run += 1;
   c->stats.d2h_ms = c->stats.h2d_ms = 0;
+  if (c->kernel_profiling) {
+    for (int v = 0; v < V_COUNT; ++v) { c->k_ms[v] = 0; c->k_flops[v] = 0; c->k_launches[v] = 0; }
+    for (size_t i = 0; i < c->kprobes_used; ++i) {
+      const acc_ctx::KProbe& kp = c->kprobes[i];
+      if (kp.variant < 0 || kp.variant >= V_COUNT) continue;
+      float ms = 0;
+      HIPCHK(c, hipEventElapsedTime(&ms, kp.a, kp.b));
+      c->k_ms[kp.variant] += ms;
+      c->k_flops[kp.variant] += kp.flops;
+      c->k_launches[kp.variant] += 1;
+    }
+  }
   if (c->profiling) {
     c->step_ms.assign(ns, 0.0);
     for (int j = 0; j < ns; ++j) {
@@ -586,10 +637,26 @@ extern "C" int acc_get_stats(acc_ctx* c, acc_stats* out) {
   return ACC_OK;
 }
 
-extern "C" int acc_set_profiling(acc_ctx* c, int on) {
+extern "C" int acc_set_profiling(acc_ctx* c, int level) {
   if (!c) return ACC_EINVAL;
-  c->profiling = on != 0;
+  c->profiling = level == 1 || level == 3;
+  c->kernel_profiling = level == 2 || level == 3;
   return ACC_OK;
+}
+
+extern "C" int acc_get_kernel_profile(acc_ctx* c, acc_kernel_profile* out, int max_entries) {
+  if (!c || !out || max_entries < 0) return ACC_EINVAL;
+  int n = 0;
+  for (int v = 0; v < V_COUNT && n < max_entries; ++v) {
+    if (!c->k_launches[v]) continue;
+    std::memset(&out[n], 0, sizeof out[n]);
+    snprintf(out[n].name, sizeof out[n].name, "%s", conv_variant_name(v));
+    out[n].launches = (int32_t)c->k_launches[v];
+    out[n].ms = c->k_ms[v];
+    out[n].flops = c->k_flops[v];
+    ++n;
+  }
+  return n;
 }
 
 extern "C" int acc_get_step_times_ms(acc_ctx* c, double* ms, int n) {

@@ -25,7 +25,16 @@ struct ConvGeom {
   int in_nchw;              // input stored NCHW (network images); generic path only
 };
 
-hipError_t conv_igemm(const ConvGeom& g, hipStream_t st);
+// Optional probe of one launch: which template instance ran (index into conv_variant_name())
+// and, when the two events are set, timestamps recorded directly around the main kernel.
+struct LaunchProbe {
+  int variant = -1;
+  hipEvent_t before = nullptr, after = nullptr;
+};
+hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
+enum { V_IGEMM_128x128 = 0, V_IGEMM_128x64, V_IGEMM_64x64, V_IGEMM_GENERIC, V_WGRAD_128x128, V_WGRAD_128x64,
+       V_WGRAD_64x128, V_WGRAD_64x64, V_WGRAD_GENERIC, V_COUNT };
+const char* conv_variant_name(int v);
 
 // dw[co][(r,t,ci)] = sum_{img,p,q} dy[img,p,q,co] * x[img, p*stride+r-pad, q*stride+t-pad, ci]
 struct WgradGeom {
@@ -40,7 +49,7 @@ struct WgradGeom {
 };
 int wgrad_splits(int n_img, int p, int q, int cin, int cout, int r, int s);
 size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s);
-hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st);
+hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
 
 // wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci]  (filter of the transposed convolution)
 hipError_t filter_flip_transpose(const float* w, float* wt, int cout, int cin, int r, int s,
