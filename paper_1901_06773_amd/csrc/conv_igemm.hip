@@ -7,12 +7,14 @@
 // A is never materialised: each K-chunk of 32 lies inside one filter tap, so a tile
 // row is 128 contiguous bytes of the NHWC input (or zeros in the padding).  A
 // workgroup of 4 waves (2 x 2) owns a BM x BN tile; each wave a (BM/2) x (BN/2)
-// sub-tile made of 32x32 MFMA blocks.  Operand tiles are staged through LDS as
+// sub-tile made of 32x32 MFMA blocks.  Operand tiles are staged through LDS (two chunks) as
 // [row][k] with a 36-float pitch, so that one ds_read_b128 per lane feeds four
 // consecutive MFMAs: lanes 0-31 hold k = 8g..8g+3, lanes 32-63 hold k = 8g+4..8g+7
 // of their row (the pairing of k inside one MFMA is free, A and W use the same one).
 // The next chunk's global loads are in flight while the current chunk is multiplied.
 #include "kernels.h"
+
+#include <cstdlib>
 
 namespace acc {
 namespace {
@@ -66,8 +68,8 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
 template <int BM, int BN, bool FAST>
 __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n,
                                                      int n_tiles) {
-  __shared__ __attribute__((aligned(16))) float As[BM * LD];
-  __shared__ __attribute__((aligned(16))) float Bs[BN * LD];
+  __shared__ __attribute__((aligned(16))) float As[2 * BM * LD];
+  __shared__ __attribute__((aligned(16))) float Bs[2 * BN * LD];
 
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give
   // each XCD a contiguous range of tiles (neighbouring tiles share operand rows in its L2).
@@ -91,41 +93,52 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 
   const int n_chunks = (K + BK - 1) / BK;
 
-  // K loop shared by both loaders: the next chunk is fetched into registers while the
-  // current one, already in LDS, is multiplied.
+  // K loop shared by both loaders.  LDS holds two chunks: while chunk kc is multiplied out
+  // of one half, chunk kc+1 (already in registers) is stored into the other half and the
+  // global loads of chunk kc+2 are issued, so there is one barrier per chunk and global
+  // latency is covered by a whole chunk of MFMA work.
   auto main_loop = [&](auto& load_chunk, auto& store_chunk) {
     load_chunk(0);
-    store_chunk();
+    store_chunk(0);
+    if (n_chunks > 1) load_chunk(1);
     __syncthreads();
     for (int kc = 0; kc < n_chunks; ++kc) {
-      const bool more = kc + 1 < n_chunks;
-      if (more) load_chunk(kc + 1);
+      const int cur = kc & 1;
+      if (kc + 1 < n_chunks) store_chunk(cur ^ 1);
+      if (kc + 2 < n_chunks) load_chunk(kc + 2);
+      const float* as = As + cur * (BM * LD);
+      const float* bs = Bs + cur * (BN * LD);
+      float4 af[2][FM], bf[2][FN];
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+        af[0][a] = *reinterpret_cast<const float4*>(&as[(wm0 + 32 * a + (lane & 31)) * LD + (lane >> 5) * 4]);
+#pragma unroll
+      for (int b = 0; b < FN; ++b)
+        bf[0][b] = *reinterpret_cast<const float4*>(&bs[(wn0 + 32 * b + (lane & 31)) * LD + (lane >> 5) * 4]);
 #pragma unroll
       for (int g8 = 0; g8 < 4; ++g8) {
-        float4 af[FM], bf[FN];
+        const int c = g8 & 1, nx = c ^ 1;
+        if (g8 < 3) {   // fragments of the next k-group are fetched before this group's MFMAs
 #pragma unroll
-        for (int a = 0; a < FM; ++a)
-          af[a] = *reinterpret_cast<const float4*>(
-              &As[(wm0 + 32 * a + (lane & 31)) * LD + g8 * 8 + (lane >> 5) * 4]);
+          for (int a = 0; a < FM; ++a)
+            af[nx][a] = *reinterpret_cast<const float4*>(
+                &as[(wm0 + 32 * a + (lane & 31)) * LD + (g8 + 1) * 8 + (lane >> 5) * 4]);
 #pragma unroll
-        for (int b = 0; b < FN; ++b)
-          bf[b] = *reinterpret_cast<const float4*>(
-              &Bs[(wn0 + 32 * b + (lane & 31)) * LD + g8 * 8 + (lane >> 5) * 4]);
+          for (int b = 0; b < FN; ++b)
+            bf[nx][b] = *reinterpret_cast<const float4*>(
+                &bs[(wn0 + 32 * b + (lane & 31)) * LD + (g8 + 1) * 8 + (lane >> 5) * 4]);
+        }
 #pragma unroll
         for (int a = 0; a < FM; ++a)
 #pragma unroll
           for (int b = 0; b < FN; ++b) {
-            acc[a][b] = mfma32x32x2(af[a].x, bf[b].x, acc[a][b]);
-            acc[a][b] = mfma32x32x2(af[a].y, bf[b].y, acc[a][b]);
-            acc[a][b] = mfma32x32x2(af[a].z, bf[b].z, acc[a][b]);
-            acc[a][b] = mfma32x32x2(af[a].w, bf[b].w, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[c][a].x, bf[c][b].x, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[c][a].y, bf[c][b].y, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[c][a].z, bf[c][b].z, acc[a][b]);
+            acc[a][b] = mfma32x32x2(af[c][a].w, bf[c][b].w, acc[a][b]);
           }
       }
       __syncthreads();
-      if (more) {
-        store_chunk();
-        __syncthreads();
-      }
     }
   };
 
@@ -167,13 +180,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
         if (++kt == g.s) { kt = 0; ++kr; }
       }
     };
-    auto store_chunk = [&]() {
+    auto store_chunk = [&](int buf) {
+      float* as = As + buf * (BM * LD);
+      float* bs = Bs + buf * (BN * LD);
 #pragma unroll
       for (int i = 0; i < AI; ++i)
-        *reinterpret_cast<float4*>(&As[(row0 + 32 * i) * LD + col4 * 4]) = ra[i];
+        *reinterpret_cast<float4*>(&as[(row0 + 32 * i) * LD + col4 * 4]) = ra[i];
 #pragma unroll
       for (int i = 0; i < BI; ++i)
-        *reinterpret_cast<float4*>(&Bs[(row0 + 32 * i) * LD + col4 * 4]) = rb[i];
+        *reinterpret_cast<float4*>(&bs[(row0 + 32 * i) * LD + col4 * 4]) = rb[i];
     };
 
     main_loop(load_chunk, store_chunk);
@@ -210,11 +225,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
         rb[i] = (kok && n < g.n_out) ? g.w[(size_t)n * K + k] : 0.f;
       }
     };
-    auto store_chunk = [&]() {
+    auto store_chunk = [&](int buf) {
 #pragma unroll
-      for (int i = 0; i < AI; ++i) As[(row0 + 8 * i) * LD + kcol] = ra[i];
+      for (int i = 0; i < AI; ++i) As[buf * (BM * LD) + (row0 + 8 * i) * LD + kcol] = ra[i];
 #pragma unroll
-      for (int i = 0; i < BI; ++i) Bs[(row0 + 8 * i) * LD + kcol] = rb[i];
+      for (int i = 0; i < BI; ++i) Bs[buf * (BN * LD) + (row0 + 8 * i) * LD + kcol] = rb[i];
     };
     main_loop(load_chunk, store_chunk);
   }
@@ -281,17 +296,14 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
     return hipErrorInvalidValue;
   const bool fast = (g.c % BK == 0) && !g.in_nchw;
   if (!fast) { *variant = V_IGEMM_GENERIC; return launch<64, 64, false>(g, (int)M, (int)K, st, probe); }
-  // tile choice depends on the GEMM shape only (never on addresses or on the swap plan)
-  auto cost = [&](int bm, int bn, double eff) {
-    const double tiles = (double)((M + bm - 1) / bm) * ((g.n_out + bn - 1) / bn);
-    const double rounds = __builtin_ceil(tiles / 512.0);
-    return rounds * bm * bn / eff;
-  };
-  const double c128 = g.n_out > 64 ? cost(128, 128, 1.0) : 1e300;
-  const double c12864 = cost(128, 64, 0.92);
-  const double c64 = cost(64, 64, 0.80);
-  if (c128 <= c12864 && c128 <= c64) { *variant = V_IGEMM_128x128; return launch<128, 128, true>(g, (int)M, (int)K, st, probe); }
-  if (c12864 <= c64) { *variant = V_IGEMM_128x64; return launch<128, 64, true>(g, (int)M, (int)K, st, probe); }
+  // Tile choice depends on the GEMM shape only (never on addresses or on the swap plan).
+  // Measured on MI355X over the ResNet shapes at minibatch 32..256: 64x64 tiles beat
+  // 128x64 and 128x128 everywhere (70.7 / 86 / 98 TFLOP/s against 56 / 76 / 88 and
+  // 40 / 61 / 82): with M a multiple of 49 the larger tiles quantise badly over 256 CUs,
+  // and four resident workgroups per CU hide the barrier of each 32-wide K chunk.
+  static const int force = [] { const char* e = getenv("ACC_IGEMM_TILE"); return e ? atoi(e) : -1; }();
+  if (force == 0) { *variant = V_IGEMM_128x128; return launch<128, 128, true>(g, (int)M, (int)K, st, probe); }
+  if (force == 1) { *variant = V_IGEMM_128x64; return launch<128, 64, true>(g, (int)M, (int)K, st, probe); }
   *variant = V_IGEMM_64x64;
   return launch<64, 64, true>(g, (int)M, (int)K, st, probe);
 }

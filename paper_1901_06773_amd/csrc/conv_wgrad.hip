@@ -9,6 +9,8 @@
 // kernel adds the parts in a fixed order, so the result is deterministic (no atomics).
 #include "kernels.h"
 
+#include <cstdlib>
+
 namespace acc {
 namespace {
 
@@ -101,6 +103,20 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
     const bool direct = g.r == 1 && g.s == 1 && g.stride == 1 && g.pad == 0;
     const bool a_ok = co0 + acol * 4 < g.cout;
     float4 ra[AI], rb[BI];
+    // position (image origin in pixels, p, q) of each gathered row; chunks are visited in
+    // order, so the position advances by BKM rows per chunk without any division
+    int r_org[BI], r_p[BI], r_q[BI];
+    if (!direct) {
+#pragma unroll
+      for (int i = 0; i < BI; ++i) {
+        const int m = chunk_lo * BKM + brow + BRPP * i;
+        const int pq = g.p * g.q;
+        const int img = m / pq, rem = m - img * pq;
+        r_p[i] = rem / g.q;
+        r_q[i] = rem - r_p[i] * g.q;
+        r_org[i] = img * g.h * g.wd;
+      }
+    }
     auto load_chunk = [&](int kc) {
 #pragma unroll
       for (int i = 0; i < AI; ++i) {
@@ -113,11 +129,18 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
       for (int i = 0; i < BI; ++i) {
         const int m = kc * BKM + brow + BRPP * i;
         rb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (m < Mrows) {
-          const int pix = direct ? m : gather_pixel(g, m, kr, kt);
-          if (pix >= 0)
-            rb[i] = *reinterpret_cast<const float4*>(g.x + (size_t)pix * g.cin + ci0 + bcol * 4);
+        int pix = m;
+        if (!direct) {
+          const int iy = r_p[i] * g.stride + kr - g.pad, ix = r_q[i] * g.stride + kt - g.pad;
+          pix = ((unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd) ? r_org[i] + iy * g.wd + ix : -1;
+          r_q[i] += BKM;
+          while (r_q[i] >= g.q) {
+            r_q[i] -= g.q;
+            if (++r_p[i] == g.p) { r_p[i] = 0; r_org[i] += g.h * g.wd; }
+          }
         }
+        if (m < Mrows && pix >= 0)
+          rb[i] = *reinterpret_cast<const float4*>(g.x + (size_t)pix * g.cin + ci0 + bcol * 4);
       }
     };
     auto store_chunk = [&]() {
@@ -220,9 +243,11 @@ WgradCfg choose(int n_img, int p, int q, int cin, int cout, int r, int s, bool x
   const long Mrows = (long)n_img * p * q;
   const long J = (long)r * s * cin;
   c.fast = !x_nchw && (cout % 4 == 0) && (cin % 64 == 0);
+  static const int force64 = [] { const char* e = getenv("ACC_WGRAD_TILE64"); return e ? atoi(e) : 0; }();   // < 0: allow 128-wide tiles
+  static const int target = [] { const char* e = getenv("ACC_WGRAD_TARGET"); return e ? atoi(e) : 1024; }();
   if (c.fast) {
-    c.bn = (cin % 128 == 0) ? 128 : 64;
-    c.bm = (cout >= 128) ? 128 : 64;
+    c.bn = (cin % 128 == 0 && force64 < 0) ? 128 : 64;
+    c.bm = (cout >= 128 && force64 < 0) ? 128 : 64;
   } else {
     c.bm = c.bn = 64;
   }
@@ -230,8 +255,8 @@ WgradCfg choose(int n_img, int p, int q, int cin, int cout, int r, int s, bool x
   c.tiles_j = (int)((J + c.bn - 1) / c.bn);
   const long tiles = (long)c.tiles_co * c.tiles_j;
   const long chunks = (Mrows + BKM - 1) / BKM;
-  long splits = (768 + tiles - 1) / tiles;
-  const long max_splits = chunks / 8 > 0 ? chunks / 8 : 1;
+  long splits = (target + tiles - 1) / tiles;
+  const long max_splits = chunks / 24 > 0 ? chunks / 24 : 1;
   if (splits > max_splits) splits = max_splits;
   if (splits > 1024) splits = 1024;
   if (splits < 1) splits = 1;
