@@ -168,6 +168,18 @@ int acc_get_tensor_info(const acc_ctx* ctx, int tensor, acc_tensor_info* out);
 int acc_get_step_io(const acc_ctx* ctx, int step, int32_t* reads, int max_reads, int32_t* writes,
                     int max_writes);
 
+/* The instruction list of the current plan, in issue order.  op: 0 load input (swap-in
+ * stream), 1 compute step (compute stream), 2 offload (swap-out stream), 3 prefetch
+ * (swap-in stream).  arg: tensor id, or step index for op 1.  wait_*: the instruction first
+ * waits for the event recorded after that compute step / after the offload resp. prefetch
+ * (or input load) with that sequence number; -1 = none.  seq: own sequence number among
+ * offloads resp. among prefetches and input loads.  record: op 1 records its step event. */
+typedef struct {
+  int32_t op, arg, wait_step, wait_d2h, wait_h2d, seq, record, reserved;
+} acc_instr;
+int acc_get_instr_count(const acc_ctx* ctx);
+int acc_get_instr(const acc_ctx* ctx, int index, acc_instr* out);
+
 /* ---- execution --------------------------------------------------------------------- */
 /* One forward / backward / SGD step at the planned minibatch.  images: fp32 NCHW,
  * pinned host (ACC_LOC_HOST) or device (ACC_LOC_DEVICE); labels: int32, host.  Blocks

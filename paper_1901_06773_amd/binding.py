@@ -78,6 +78,11 @@ class acc_stats(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class acc_instr(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("op", "arg", "wait_step", "wait_d2h", "wait_h2d", "seq", "record",
+                                          "reserved")]
+
+
 class acc_kernel_profile(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("reserved", C.c_int32),
                 ("ms", C.c_double), ("flops", C.c_double)]
@@ -104,6 +109,8 @@ _PROTOS = {
     "acc_get_step_info": (_I, [_VP, _I, C.POINTER(acc_step_info)]),
     "acc_get_tensor_info": (_I, [_VP, _I, C.POINTER(acc_tensor_info)]),
     "acc_get_step_io": (_I, [_VP, _I, C.POINTER(C.c_int32), _I, C.POINTER(C.c_int32), _I]),
+    "acc_get_instr_count": (_I, [_VP]),
+    "acc_get_instr": (_I, [_VP, _I, C.POINTER(acc_instr)]),
     "acc_train_step": (_I, [_VP, _VP, _I, _VP, _F, C.POINTER(_F)]),
     "acc_get_stats": (_I, [_VP, C.POINTER(acc_stats)]),
     "acc_set_profiling": (_I, [_VP, _I]),
@@ -258,6 +265,15 @@ class Context:
         w = (C.c_int32 * 16)()
         rc = self._check(_lib.acc_get_step_io(self._h, j, r, 16, w, 16))
         return list(r[: rc // 256]), list(w[: rc % 256])
+
+    def instructions(self) -> list:
+        """The plan's instruction list as dicts (op, arg, wait_step, wait_d2h, wait_h2d, seq, record)."""
+        out = []
+        ins = acc_instr()
+        for i in range(self._check(_lib.acc_get_instr_count(self._h))):
+            self._check(_lib.acc_get_instr(self._h, i, C.byref(ins)))
+            out.append({n: getattr(ins, n) for n, _ in ins._fields_ if n != "reserved"})
+        return out
 
     # ---- execution
     def train_step(self, images, labels: np.ndarray, lr: float) -> float:

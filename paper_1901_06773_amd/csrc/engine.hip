@@ -368,6 +368,19 @@ extern "C" int acc_get_step_io(const acc_ctx* c, int step, int32_t* reads, int m
   return (int)(s.reads.size() * 256 + s.writes.size());
 }
 
+extern "C" int acc_get_instr_count(const acc_ctx* c) {
+  if (!c) return ACC_EINVAL;
+  return c->plan.valid ? (int)c->plan.instrs.size() : 0;
+}
+
+extern "C" int acc_get_instr(const acc_ctx* c, int i, acc_instr* out) {
+  if (!c || !out || !c->plan.valid || i < 0 || i >= (int)c->plan.instrs.size()) return ACC_EINVAL;
+  const Instr& in = c->plan.instrs[i];
+  out->op = in.op; out->arg = in.arg; out->wait_step = in.wait_step; out->wait_d2h = in.wait_d2h;
+  out->wait_h2d = in.wait_h2d; out->seq = in.seq; out->record = in.record ? 1 : 0; out->reserved = 0;
+  return ACC_OK;
+}
+
 // ---------------------------------------------------------------------------- executor
 namespace {
 

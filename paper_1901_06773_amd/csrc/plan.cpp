@@ -451,6 +451,37 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
     }
     if (!changed) break;
   }
+  // Local refinement: move a swap to a neighbouring map (in producer order) when that
+  // shortens the predicted iteration; which of two adjacent maps leaves the GPU decides
+  // how well its copies hide behind the steps in between.
+  const int nm = (int)g.maps.size();
+  for (int pass = 0; pass < 2; ++pass) {
+    bool changed = false;
+    for (int i = 0; i < nm; ++i) {
+      if (!cur[g.maps[i]]) continue;
+      for (int d = -2; d <= 2; ++d) {
+        const int j = i + d;
+        if (d == 0 || j < 0 || j >= nm || cur[g.maps[j]] || !cur[g.maps[i]]) continue;
+        cur[g.maps[i]] = 0;
+        cur[g.maps[j]] = 1;
+        Plan trial;
+        std::string w2;
+        bool better = false;
+        if (build_plan(g, k, budget, cur, opt, &trial, &w2)) {
+          simulate(g, cm, &trial);
+          better = trial.t_iter < best.t_iter * (1.0 - 1e-6);
+        }
+        if (better) {
+          best = std::move(trial);
+          changed = true;
+        } else {
+          cur[g.maps[i]] = 1;
+          cur[g.maps[j]] = 0;
+        }
+      }
+    }
+    if (!changed) break;
+  }
   *out = std::move(best);
   out->mode = mode;
   *why = "";
