@@ -93,86 +93,113 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 
   const int n_chunks = (K + BK - 1) / BK;
 
-  // K loop shared by both loaders.  LDS holds two chunks: while chunk kc is multiplied out
-  // of one half, chunk kc+1 (already in registers) is stored into the other half and the
-  // global loads of chunk kc+2 are issued, so there is one barrier per chunk and global
-  // latency is covered by a whole chunk of MFMA work.
-  auto main_loop = [&](auto& load_chunk, auto& store_chunk) {
-    load_chunk(0);
-    store_chunk(0);
-    if (n_chunks > 1) load_chunk(1);
-    __syncthreads();
-    for (int kc = 0; kc < n_chunks; ++kc) {
-      const int cur = kc & 1;
-      if (kc + 1 < n_chunks) store_chunk(cur ^ 1);
-      if (kc + 2 < n_chunks) load_chunk(kc + 2);
-      const float* as = As + cur * (BM * LD);
-      const float* bs = Bs + cur * (BN * LD);
-      float4 af[2][FM], bf[2][FN];
+  // K loop shared by both loaders.  LDS holds two chunks and registers hold two more:
+  // while chunk kc is multiplied out of one LDS half, chunk kc+1 moves from registers into
+  // the other half and the global loads of chunk kc+3 are issued into the registers just
+  // freed (chunk kc+2 is already on its way).  One barrier per chunk; a global load has
+  // two whole chunks of MFMA work to complete before anything waits for it.
+  auto compute_chunk = [&](int cur) {
+    const float* as = As + cur * (BM * LD);
+    const float* bs = Bs + cur * (BN * LD);
+    float4 af[2][FM], bf[2][FN];
 #pragma unroll
-      for (int a = 0; a < FM; ++a)
-        af[0][a] = *reinterpret_cast<const float4*>(&as[(wm0 + 32 * a + (lane & 31)) * LD + (lane >> 5) * 4]);
+    for (int a = 0; a < FM; ++a)
+      af[0][a] = *reinterpret_cast<const float4*>(&as[(wm0 + 32 * a + (lane & 31)) * LD + (lane >> 5) * 4]);
 #pragma unroll
-      for (int b = 0; b < FN; ++b)
-        bf[0][b] = *reinterpret_cast<const float4*>(&bs[(wn0 + 32 * b + (lane & 31)) * LD + (lane >> 5) * 4]);
+    for (int b = 0; b < FN; ++b)
+      bf[0][b] = *reinterpret_cast<const float4*>(&bs[(wn0 + 32 * b + (lane & 31)) * LD + (lane >> 5) * 4]);
 #pragma unroll
-      for (int g8 = 0; g8 < 4; ++g8) {
-        const int c = g8 & 1, nx = c ^ 1;
-        if (g8 < 3) {   // fragments of the next k-group are fetched before this group's MFMAs
-#pragma unroll
-          for (int a = 0; a < FM; ++a)
-            af[nx][a] = *reinterpret_cast<const float4*>(
-                &as[(wm0 + 32 * a + (lane & 31)) * LD + (g8 + 1) * 8 + (lane >> 5) * 4]);
-#pragma unroll
-          for (int b = 0; b < FN; ++b)
-            bf[nx][b] = *reinterpret_cast<const float4*>(
-                &bs[(wn0 + 32 * b + (lane & 31)) * LD + (g8 + 1) * 8 + (lane >> 5) * 4]);
-        }
+    for (int g8 = 0; g8 < 4; ++g8) {
+      const int c = g8 & 1, nx = c ^ 1;
+      if (g8 < 3) {   // fragments of the next k-group are fetched before this group's MFMAs
 #pragma unroll
         for (int a = 0; a < FM; ++a)
+          af[nx][a] = *reinterpret_cast<const float4*>(
+              &as[(wm0 + 32 * a + (lane & 31)) * LD + (g8 + 1) * 8 + (lane >> 5) * 4]);
 #pragma unroll
-          for (int b = 0; b < FN; ++b) {
-            acc[a][b] = mfma32x32x2(af[c][a].x, bf[c][b].x, acc[a][b]);
-            acc[a][b] = mfma32x32x2(af[c][a].y, bf[c][b].y, acc[a][b]);
-            acc[a][b] = mfma32x32x2(af[c][a].z, bf[c][b].z, acc[a][b]);
-            acc[a][b] = mfma32x32x2(af[c][a].w, bf[c][b].w, acc[a][b]);
-          }
+        for (int b = 0; b < FN; ++b)
+          bf[nx][b] = *reinterpret_cast<const float4*>(
+              &bs[(wn0 + 32 * b + (lane & 31)) * LD + (g8 + 1) * 8 + (lane >> 5) * 4]);
       }
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b) {
+          acc[a][b] = mfma32x32x2(af[c][a].x, bf[c][b].x, acc[a][b]);
+          acc[a][b] = mfma32x32x2(af[c][a].y, bf[c][b].y, acc[a][b]);
+          acc[a][b] = mfma32x32x2(af[c][a].z, bf[c][b].z, acc[a][b]);
+          acc[a][b] = mfma32x32x2(af[c][a].w, bf[c][b].w, acc[a][b]);
+        }
+    }
+  };
+  // load_chunk(set, kc) fills register set `set`; store_chunk(set, buf) moves it to LDS
+  auto main_loop = [&](auto& load_chunk, auto& store_chunk) {
+    load_chunk(0, 0);
+    store_chunk(0, 0);
+    if (n_chunks > 1) load_chunk(1, 1);
+    if (n_chunks > 2) load_chunk(0, 2);
+    __syncthreads();
+    for (int kc = 0; kc < n_chunks; kc += 2) {
+      // even chunk: the next one (odd) waits in register set 1
+      if (kc + 1 < n_chunks) store_chunk(1, 1);
+      if (kc + 3 < n_chunks) load_chunk(1, kc + 3);
+      compute_chunk(0);
+      __syncthreads();
+      if (kc + 1 >= n_chunks) break;
+      // odd chunk: the next one (even) waits in register set 0
+      if (kc + 2 < n_chunks) store_chunk(0, 0);
+      if (kc + 4 < n_chunks) load_chunk(0, kc + 4);
+      compute_chunk(1);
       __syncthreads();
     }
   };
 
   if constexpr (FAST) {
+    // Addresses are split into a per-lane 32-bit byte offset that never changes (the row's
+    // pixel, shifted by the padding margin so that it is never negative) and a uniform
+    // base that moves with the filter tap and the channel chunk, so the K loop spends no
+    // vector instructions on addresses; whether a tap falls into the padding is one bit of
+    // a per-row mask built once.
     constexpr int AI = BM / 32, BI = BN / 32;
     const int col4 = tid & 7, row0 = tid >> 3;
-    RowPos rp[AI];
-#pragma unroll
-    for (int i = 0; i < AI; ++i) rp[i] = decode_row(g, m0 + row0 + 32 * i, M);
-    const float* wrow[BI];
+    const int margin = g.pad * g.wd + g.pad;               // pixels
+    uint32_t a_voff[AI], a_mask[AI], b_voff[BI];
     bool wok[BI];
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const RowPos rp = decode_row(g, m0 + row0 + 32 * i, M);
+      a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * 4) + col4 * 16;
+      uint32_t mask = 0;
+      for (int kr = 0; kr < g.r; ++kr)
+        for (int kt = 0; kt < g.s; ++kt) {
+          const bool ok = rp.ok && (unsigned)(rp.iy0 + kr) < (unsigned)g.h && (unsigned)(rp.ix0 + kt) < (unsigned)g.wd;
+          mask |= (ok ? 1u : 0u) << (kr * g.s + kt);
+        }
+      a_mask[i] = mask;
+    }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int n = n0 + row0 + 32 * i;
       wok[i] = n < g.n_out;
-      wrow[i] = g.w + (size_t)(wok[i] ? n : 0) * K + col4 * 4;
+      b_voff[i] = (uint32_t)(wok[i] ? n : 0) * (uint32_t)(K * 4) + col4 * 16;
     }
-    float4 ra[AI], rb[BI];
-    int kr = 0, kt = 0, c0 = 0;  // tap and channel offset of the chunk being loaded
+    float4 ra[2][AI], rb[2][BI];
+    int kr = 0, kt = 0, c0 = 0;  // tap and channel offset of the chunk being loaded (uniform)
 
-    auto load_chunk = [&](int kc) {
+    auto load_chunk = [&](int set, int kc) {
+      const int tap = kr * g.s + kt;
+      const char* abase = reinterpret_cast<const char*>(g.in) +
+                          ((long)(kr * g.wd + kt - margin) * g.c + c0) * 4;
+      const char* bbase = reinterpret_cast<const char*>(g.w) + (long)kc * (BK * 4);
 #pragma unroll
       for (int i = 0; i < AI; ++i) {
-        const int iy = rp[i].iy0 + kr, ix = rp[i].ix0 + kt;
-        const bool ok = rp[i].ok && (unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd;
-        ra[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ok)
-          ra[i] = *reinterpret_cast<const float4*>(
-              g.in + ((size_t)(rp[i].pix + iy * g.wd + ix) * g.c + c0 + col4 * 4));
+        ra[set][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if ((a_mask[i] >> tap) & 1u) ra[set][i] = *reinterpret_cast<const float4*>(abase + a_voff[i]);
       }
 #pragma unroll
       for (int i = 0; i < BI; ++i) {
-        rb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (wok[i]) rb[i] = *reinterpret_cast<const float4*>(wrow[i] + (size_t)kc * BK);
+        rb[set][i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (wok[i]) rb[set][i] = *reinterpret_cast<const float4*>(bbase + b_voff[i]);
       }
       c0 += BK;
       if (c0 == g.c) {
@@ -180,15 +207,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
         if (++kt == g.s) { kt = 0; ++kr; }
       }
     };
-    auto store_chunk = [&](int buf) {
+    auto store_chunk = [&](int set, int buf) {
       float* as = As + buf * (BM * LD);
       float* bs = Bs + buf * (BN * LD);
 #pragma unroll
       for (int i = 0; i < AI; ++i)
-        *reinterpret_cast<float4*>(&as[(row0 + 32 * i) * LD + col4 * 4]) = ra[i];
+        *reinterpret_cast<float4*>(&as[(row0 + 32 * i) * LD + col4 * 4]) = ra[set][i];
 #pragma unroll
       for (int i = 0; i < BI; ++i)
-        *reinterpret_cast<float4*>(&bs[(row0 + 32 * i) * LD + col4 * 4]) = rb[i];
+        *reinterpret_cast<float4*>(&bs[(row0 + 32 * i) * LD + col4 * 4]) = rb[set][i];
     };
 
     main_loop(load_chunk, store_chunk);
@@ -199,8 +226,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     RowPos rp[AI];
 #pragma unroll
     for (int i = 0; i < AI; ++i) rp[i] = decode_row(g, m0 + row0 + 8 * i, M);
-    float ra[AI], rb[BI];
-    auto load_chunk = [&](int kc) {
+    float ra[2][AI], rb[2][BI];
+    auto load_chunk = [&](int set, int kc) {
       const int k = kc * BK + kcol;
       const bool kok = k < K;
       const int kk = kok ? k : 0;
@@ -217,19 +244,19 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
                                        : (size_t)(rp[i].pix + iy * g.wd + ix) * g.c + c;
           v = g.in[off];
         }
-        ra[i] = v;
+        ra[set][i] = v;
       }
 #pragma unroll
       for (int i = 0; i < BI; ++i) {
         const int n = n0 + row0 + 8 * i;
-        rb[i] = (kok && n < g.n_out) ? g.w[(size_t)n * K + k] : 0.f;
+        rb[set][i] = (kok && n < g.n_out) ? g.w[(size_t)n * K + k] : 0.f;
       }
     };
-    auto store_chunk = [&](int buf) {
+    auto store_chunk = [&](int set, int buf) {
 #pragma unroll
-      for (int i = 0; i < AI; ++i) As[buf * (BM * LD) + (row0 + 8 * i) * LD + kcol] = ra[i];
+      for (int i = 0; i < AI; ++i) As[buf * (BM * LD) + (row0 + 8 * i) * LD + kcol] = ra[set][i];
 #pragma unroll
-      for (int i = 0; i < BI; ++i) Bs[buf * (BN * LD) + (row0 + 8 * i) * LD + kcol] = rb[i];
+      for (int i = 0; i < BI; ++i) Bs[buf * (BN * LD) + (row0 + 8 * i) * LD + kcol] = rb[set][i];
     };
     main_loop(load_chunk, store_chunk);
   }
@@ -294,7 +321,11 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   const long K = (long)g.r * g.s * g.c;
   if (M >= (1L << 31) || K >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31))
     return hipErrorInvalidValue;
-  const bool fast = (g.c % BK == 0) && !g.in_nchw;
+  // fast loader: 32-channel chunks, at most 32 filter taps (one validity bit each), and
+  // every per-lane byte offset below 2^32
+  const bool fast = (g.c % BK == 0) && !g.in_nchw && g.r * g.s <= 32 &&
+                    ((long)g.n_img * g.h * g.wd + 2L * g.pad * (g.wd + 1)) * g.c * 4 < (1L << 32) &&
+                    (long)g.n_out * K * 4 < (1L << 32);
   if (!fast) { *variant = V_IGEMM_GENERIC; return launch<64, 64, false>(g, (int)M, (int)K, st, probe); }
   // Tile choice depends on the GEMM shape only (never on addresses or on the swap plan).
   // Measured on MI355X over the ResNet shapes at minibatch 32..256: 64x64 tiles beat
