@@ -22,7 +22,6 @@ struct ConvGeom {
   int r, s, stride, pad;
   int out_h, out_w, out_stride;
   int accumulate;           // out += result
-  int in_nchw;              // input stored NCHW (network images); generic path only
 };
 
 // Optional probe of one launch: which template instance ran (index into conv_variant_name())
@@ -32,8 +31,7 @@ struct LaunchProbe {
   hipEvent_t before = nullptr, after = nullptr;
 };
 hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
-enum { V_IGEMM_128x128 = 0, V_IGEMM_128x64, V_IGEMM_64x64, V_IGEMM_GENERIC, V_WGRAD_128x128, V_WGRAD_128x64,
-       V_WGRAD_64x128, V_WGRAD_64x64, V_WGRAD_GENERIC, V_COUNT };
+enum { V_IGEMM_FAST = 0, V_IGEMM_GENERIC, V_WGRAD_FAST, V_WGRAD_GENERIC, V_COUNT };
 const char* conv_variant_name(int v);
 
 // dw[co][(r,t,ci)] = sum_{img,p,q} dy[img,p,q,co] * x[img, p*stride+r-pad, q*stride+t-pad, ci]
@@ -44,10 +42,8 @@ struct WgradGeom {
   int n_img, h, wd, cin;
   int p, q, cout;
   int r, s, stride, pad;
-  int x_nchw;
   float* workspace;         // split-K partials, wgrad_workspace_bytes() bytes (may be null if 0)
 };
-int wgrad_splits(int n_img, int p, int q, int cin, int cout, int r, int s);
 size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s);
 hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
 
