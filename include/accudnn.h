@@ -142,8 +142,12 @@ int acc_get_grads(acc_ctx* ctx, int layer, float* host_g, size_t n);
 int acc_param_count(const acc_ctx* ctx, int layer, size_t* n);
 
 /* ---- cost model (dynamic information, Sec. 4.2; Eq. 2 and Eq. 5) ------------------- */
-/* Times every step's kernels at each minibatch in ks[] with events on the compute
- * stream, and D2H / H2D copies of a few sizes on the side streams.  Needs resources. */
+/* Measures the link (D2H / H2D copies of two sizes on the side streams) and every step's
+ * kernels (events on the compute stream, three iterations on a synthetic batch, weights
+ * untouched) at each minibatch of ks[] that trains in the pool without swapping.  If some
+ * of ks[] are too large for that, the largest minibatch that does fit is measured too and
+ * the planner scales its times in proportion (Eq. 1, Sec. 4.3.1).  Needs resources;
+ * ACC_EPOOL if not even one image fits. */
 int acc_calibrate(acc_ctx* ctx, const int* ks, int nk);
 /* Synthetic cost model for planning without a GPU: step time = launch_s + flops /
  * flops_per_s + bytes / bytes_per_s (flops for conv/fc steps, touched bytes for the
@@ -153,6 +157,16 @@ int acc_set_cost_model(acc_ctx* ctx, double flops_per_s, double bytes_per_s, dou
 /* Overrides the cost of single steps (seconds, at the minibatch given to the next
  * plan_swaps); n must equal the step count.  Used to test Algorithm 1 on hand-built cases. */
 int acc_set_step_times(acc_ctx* ctx, const double* seconds, int n);
+/* Reads back / installs the measured table of acc_calibrate, so that a calibration can be
+ * kept and a planning-only context can plan with it: ks[nk] ascending minibatches,
+ * seconds[nk][n_steps] row-major, link[3] = D2H bytes/s, H2D bytes/s, latency per copy (s).
+ * get: returns nk (0 if nothing was measured) or ACC_EINVAL if max_k / max_seconds are too
+ * small; any output pointer may be null.  Between two measured minibatches the planner
+ * interpolates linearly in k; beyond the largest it scales in proportion (Sec. 4.3.1:
+ * throughput saturates), below the smallest it scales down to no less than the launch cost. */
+int acc_get_calibration(const acc_ctx* ctx, int* ks, int max_k, double* seconds, size_t max_seconds,
+                        double* link);
+int acc_set_calibration(acc_ctx* ctx, const int* ks, int nk, const double* seconds, const double* link);
 
 /* ---- planning (Algorithm 1, Eq. 4-6, body of Algorithm 2) ------------------------- */
 int acc_plan_swaps(acc_ctx* ctx, int minibatch, size_t budget_bytes, int mode,

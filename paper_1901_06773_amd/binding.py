@@ -102,6 +102,8 @@ _PROTOS = {
     "acc_calibrate": (_I, [_VP, C.POINTER(_I), _I]),
     "acc_set_cost_model": (_I, [_VP, _D, _D, _D, _D, _D, _D]),
     "acc_set_step_times": (_I, [_VP, C.POINTER(_D), _I]),
+    "acc_get_calibration": (_I, [_VP, C.POINTER(_I), _I, C.POINTER(_D), _SZ, C.POINTER(_D)]),
+    "acc_set_calibration": (_I, [_VP, C.POINTER(_I), _I, C.POINTER(_D), C.POINTER(_D)]),
     "acc_plan_swaps": (_I, [_VP, _I, _SZ, _I, C.POINTER(acc_plan_summary)]),
     "acc_plan_explicit": (_I, [_VP, _I, _SZ, C.POINTER(C.c_uint8), _I, C.POINTER(acc_plan_summary)]),
     "acc_get_step_count": (_I, [_VP]),
@@ -228,6 +230,24 @@ class Context:
     def set_step_times(self, seconds: Sequence[float]):
         arr = (_D * len(seconds))(*[float(s) for s in seconds])
         self._check(_lib.acc_set_step_times(self._h, arr, len(seconds)))
+
+    def get_calibration(self) -> dict:
+        """Measured table of calibrate(): {"ks": [...], "seconds": array [nk, n_steps], "link": (d2h, h2d, latency)}."""
+        link = (_D * 3)()
+        nk = self._check(_lib.acc_get_calibration(self._h, None, 0, None, 0, link))
+        ns = self.step_count()
+        ks = (_I * max(nk, 1))()
+        sec = (_D * max(nk * ns, 1))()
+        self._check(_lib.acc_get_calibration(self._h, ks, nk, sec, nk * ns, link))
+        return dict(ks=list(ks[:nk]), seconds=np.array(sec[:nk * ns], dtype=np.float64).reshape(nk, ns),
+                    link=tuple(link[:]))
+
+    def set_calibration(self, ks: Sequence[int], seconds, link=None):
+        seconds = np.ascontiguousarray(seconds, np.float64)
+        assert seconds.shape == (len(ks), self.step_count())
+        ka = (_I * len(ks))(*[int(k) for k in ks])
+        la = (_D * 3)(*[float(x) for x in link]) if link is not None else None
+        self._check(_lib.acc_set_calibration(self._h, ka, len(ks), seconds.ctypes.data_as(C.POINTER(_D)), la))
 
     def plan_swaps(self, minibatch: int, budget_bytes: int, mode: int = PLAN_DYNAMIC) -> dict:
         s = acc_plan_summary()

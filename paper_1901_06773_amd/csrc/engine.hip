@@ -46,6 +46,7 @@ struct acc_ctx {
   size_t dyn_cap = 0;
   // events of the current plan
   std::vector<hipEvent_t> ev_step, ev_d2h, ev_h2d;
+  std::vector<hipEvent_t> ev_window;   // one per kStepWindow compute steps: bounds the host's run-ahead
   std::vector<hipEvent_t> prof_a, prof_b, prof_copy_a, prof_copy_b;
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
   bool profiling = false;
@@ -82,12 +83,25 @@ struct acc_ctx {
     return lp;
   }
   void drop_events() {
-    for (auto* v : {&ev_step, &ev_d2h, &ev_h2d, &prof_a, &prof_b, &prof_copy_a, &prof_copy_b}) {
+    for (auto* v : {&ev_step, &ev_d2h, &ev_h2d, &ev_window, &prof_a, &prof_b, &prof_copy_a, &prof_copy_b}) {
       for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
       v->clear();
     }
   }
 };
+
+// Flow control of the executor.  The host could queue a whole iteration (a few thousand
+// kernels, copies, event records and waits) long before the GPU gets to it.  Keeping the
+// queues that deep buys nothing, so the host never runs more than kWindows * kStepWindow
+// steps ahead of the compute stream, nor more than kCopyWindow copies ahead of either copy
+// stream: it waits on an event of older work first.  The windows are far deeper than any
+// dependency between the streams (the pool holds a few dozen maps at a time).
+constexpr int kStepWindow = 32, kWindows = 3, kCopyWindow = 64;
+// Event timing of steps and copies is refused for plans that swap more than this per
+// iteration: such runs (ResNet-152, minibatch 224 and 256, all maps swapped, 36-41 GiB each
+// way) ended in a crash of the process at its next HIP call, cause unknown; the same
+// plans run fine untimed, and timed runs up to 20 GiB of swapped maps are fine.
+constexpr size_t kMaxTimedSwapBytes = (size_t)24 << 30;
 
 #define HIPCHK(ctx, expr)                                  \
   do {                                                     \
@@ -249,6 +263,42 @@ extern "C" int acc_set_step_times(acc_ctx* c, const double* seconds, int n) {
   return ACC_OK;
 }
 
+extern "C" int acc_get_calibration(const acc_ctx* c, int* ks, int max_k, double* seconds, size_t max_seconds,
+                                   double* link) {
+  if (!c) return ACC_EINVAL;
+  const int nk = (int)c->cm.ks.size();
+  const size_t ns = c->g.steps.size();
+  if (link) { link[0] = c->cm.d2h_bps; link[1] = c->cm.h2d_bps; link[2] = c->cm.copy_latency_s; }
+  if (ks) {
+    if (max_k < nk) return ACC_EINVAL;
+    for (int i = 0; i < nk; ++i) ks[i] = c->cm.ks[i];
+  }
+  if (seconds) {
+    if (max_seconds < nk * ns) return ACC_EINVAL;
+    for (int i = 0; i < nk; ++i)
+      for (size_t j = 0; j < ns; ++j) seconds[i * ns + j] = c->cm.table[i][j];
+  }
+  return nk;
+}
+
+extern "C" int acc_set_calibration(acc_ctx* c, const int* ks, int nk, const double* seconds, const double* link) {
+  if (!c) return ACC_EINVAL;
+  if (!ks || !seconds || nk <= 0) return c->fail(ACC_EINVAL, "need at least one measured minibatch");
+  const size_t ns = c->g.steps.size();
+  for (int i = 0; i < nk; ++i)
+    if (ks[i] <= 0 || (i > 0 && ks[i] <= ks[i - 1])) return c->fail(ACC_EINVAL, "minibatches must be positive and ascending");
+  for (size_t i = 0; i < nk * ns; ++i)
+    if (!(seconds[i] >= 0)) return c->fail(ACC_EINVAL, "negative step time");
+  if (link && (!(link[0] > 0) || !(link[1] > 0) || !(link[2] >= 0))) return c->fail(ACC_EINVAL, "bad link figures");
+  c->cm.fixed.clear();
+  c->cm.ks.assign(ks, ks + nk);
+  c->cm.table.assign(nk, std::vector<double>());
+  for (int i = 0; i < nk; ++i) c->cm.table[i].assign(seconds + i * ns, seconds + (i + 1) * ns);
+  if (link) { c->cm.d2h_bps = link[0]; c->cm.h2d_bps = link[1]; c->cm.copy_latency_s = link[2]; }
+  c->plan.valid = false;
+  return ACC_OK;
+}
+
 // ---------------------------------------------------------------------------- planning
 namespace {
 
@@ -269,6 +319,8 @@ int install_plan(acc_ctx* c, Plan&& p, acc_plan_summary* out, double t0) {
     c->ev_h2d.assign(p.n_h2d, nullptr);
     for (auto& e : c->ev_d2h) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
     for (auto& e : c->ev_h2d) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    c->ev_window.assign(ns / kStepWindow + 1, nullptr);
+    for (auto& e : c->ev_window) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   }
   c->plan = std::move(p);
   c->stats = acc_stats{};
@@ -522,6 +574,8 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   const int ns = (int)g.steps.size();
   const double t_host0 = now_ms();
   c->cur_off = P.off1;
+  if ((c->profiling || c->kernel_profiling) && P.host_bytes > kMaxTimedSwapBytes)
+    return c->fail(ACC_ESTATE, "profiling is switched off for plans that swap more than 24 GiB per iteration");
   if (c->profiling) {
     if ((int)c->prof_a.size() != ns) {
       c->prof_a.assign(ns, nullptr); c->prof_b.assign(ns, nullptr);
@@ -538,7 +592,14 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   uint64_t bytes_out = 0, bytes_in = 0;
   c->kprobes_used = 0;
   HIPCHK(c, hipEventRecord(c->ev_begin, c->s_c));
+  int n_compute = 0;
   for (const Instr& in : P.instrs) {
+    if ((in.op == I_LOAD_INPUT || in.op == I_PREFETCH) && in.seq >= kCopyWindow)
+      HIPCHK(c, hipEventSynchronize(c->ev_h2d[in.seq - kCopyWindow]));
+    if (in.op == I_OFFLOAD && in.seq >= kCopyWindow)
+      HIPCHK(c, hipEventSynchronize(c->ev_d2h[in.seq - kCopyWindow]));
+    if (in.op == I_COMPUTE && n_compute % kStepWindow == 0 && n_compute / kStepWindow >= kWindows)
+      HIPCHK(c, hipEventSynchronize(c->ev_window[n_compute / kStepWindow - kWindows]));
     switch (in.op) {
       case I_LOAD_INPUT: {
         void* dst = c->dyn + c->cur_off[in.arg];
@@ -573,6 +634,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
         }
         if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_b[in.arg], c->s_c));
         if (in.record) HIPCHK(c, hipEventRecord(c->ev_step[in.arg], c->s_c));
+        if (++n_compute % kStepWindow == 0) HIPCHK(c, hipEventRecord(c->ev_window[n_compute / kStepWindow - 1], c->s_c));
         break;
       }
       case I_OFFLOAD: {
@@ -746,20 +808,43 @@ extern "C" int acc_calibrate(acc_ctx* c, const int* ks, int nk) {
     }
   }
 
-  // dynamic information 1: per-step compute time at each minibatch, taken from real
-  // iterations (no swap if the pool allows it, else the naive swap-everything strategy)
+  // dynamic information 1: per-step compute time, taken from real iterations at every
+  // requested minibatch that trains in this pool without swapping.  A larger minibatch is
+  // not run here: its step times follow from the largest measured one in proportion to
+  // the minibatch (Eq. 1; throughput has saturated by then, Sec. 4.3.1), so if any request
+  // is too large the largest minibatch that does fit is measured as well.
   const bool was_prof = c->profiling;
   std::vector<int> ok_ks;
   std::vector<std::vector<double>> table;
   c->cm.fixed.clear();
+  auto fits = [&](int k) {
+    Plan p;
+    std::string why;
+    return make_plan(c->g, c->cm, k, c->res.pool_bytes, ACC_PLAN_NONE, &p, &why) == ACC_OK;
+  };
+  std::vector<int> run_ks;
+  bool some_too_large = false;
   for (int k : kk) {
+    if (fits(k)) run_ks.push_back(k);
+    else some_too_large = true;
+  }
+  if (some_too_large && fits(1)) {
+    int lo = 1, hi = kk.back();
+    while (lo < hi) {
+      const int mid = lo + (hi - lo + 1) / 2;
+      if (fits(mid)) lo = mid; else hi = mid - 1;
+    }
+    run_ks.push_back(lo);
+    std::sort(run_ks.begin(), run_ks.end());
+    run_ks.erase(std::unique(run_ks.begin(), run_ks.end()), run_ks.end());
+  }
+  for (int k : run_ks) {
     Plan p;
     std::string why;
     int rc = make_plan(c->g, c->cm, k, c->res.pool_bytes, ACC_PLAN_NONE, &p, &why);
-    if (rc != ACC_OK) rc = make_plan(c->g, c->cm, k, c->res.pool_bytes, ACC_PLAN_NAIVE_ALL, &p, &why);
-    if (rc != ACC_OK) continue;   // does not fit this pool at all
+    if (rc != ACC_OK) continue;
     rc = install_plan(c, std::move(p), nullptr, now_ms());
-    if (rc != ACC_OK) { if (rc == ACC_EHOSTMEM) continue; return rc; }
+    if (rc != ACC_OK) return rc;
     c->calibrating = true;
     c->profiling = true;
     std::vector<double> best(ns, 1e30);
@@ -777,7 +862,7 @@ extern "C" int acc_calibrate(acc_ctx* c, const int* ks, int nk) {
     table.push_back(best);
   }
   c->plan.valid = false;
-  if (ok_ks.empty()) return c->fail(ACC_EPOOL, "no calibration minibatch fits the pool");
+  if (ok_ks.empty()) return c->fail(ACC_EPOOL, "not even one image trains in this pool without swapping");
   c->cm.ks = ok_ks;
   c->cm.table = table;
   return ACC_OK;
