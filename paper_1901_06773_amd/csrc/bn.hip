@@ -4,8 +4,8 @@
 // The work is bandwidth bound, so every kernel reads whole float4 channel groups of
 // consecutive rows (a wave covers 1 KiB of contiguous memory per load).  Reductions
 // over rows run in two fixed-order stages (per-slab partials in double, then one
-// thread per channel adds the slabs in order): no atomics, results do not depend on
-// timing or addresses.
+// wave per channel adds the slabs in a fixed order): no atomics, results do not depend
+// on timing or addresses.
 //
 // workspace layout (bn_workspace_bytes): double part[2][MAX_SLABS][c] | float coef[4][c]
 #include "kernels.h"
@@ -13,10 +13,10 @@
 namespace acc {
 namespace {
 
-constexpr int MAX_SLABS = 256;  // row slabs of the reduction grid (upper bound)
+constexpr int MAX_SLABS = 1024;     // row slabs of the reduction grid (upper bound)
+constexpr int ROWS_PER_THREAD = 4;  // rows a thread of the reduction sums at least (else fewer slabs)
 constexpr int THREADS = 256;
-constexpr int FIN_CH = 16;      // channels per workgroup of the finishing kernels
-constexpr int FIN_LANES = THREADS / FIN_CH;
+constexpr int FIN_CH = THREADS / 64;  // the finishing kernels give every channel one wave
 
 struct ReduceShape {
   int tpr;        // threads across one row (each owns 4 channels)
@@ -63,10 +63,7 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
       mu[0] = m4.x; mu[1] = m4.y; mu[2] = m4.z; mu[3] = m4.w;
       is[0] = i4.x; is[1] = i4.y; is[2] = i4.z; is[3] = i4.w;
     }
-#pragma unroll 4
-    for (long r = r_lo + lane_r; r < r_hi; r += rpi) {
-      const size_t off = (size_t)r * c + (size_t)cg * 4;
-      const float4 xv = *reinterpret_cast<const float4*>(x + off);
+    auto add_row = [&](const float4& xv, const float4& gv, const float4& yv) {
       const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
       if (MODE == 0) {
 #pragma unroll
@@ -76,10 +73,8 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
           s1[j] += d * d;
         }
       } else {
-        const float4 gv = *reinterpret_cast<const float4*>(dy + off);
         float gs[4] = {gv.x, gv.y, gv.z, gv.w};
         if (y) {
-          const float4 yv = *reinterpret_cast<const float4*>(y + off);
           const float ys[4] = {yv.x, yv.y, yv.z, yv.w};
 #pragma unroll
           for (int j = 0; j < 4; ++j) gs[j] = ys[j] > 0.f ? gs[j] : 0.f;
@@ -91,6 +86,29 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
           s1[j] += gd * (double)((xs[j] - mu[j]) * is[j]);
         }
       }
+    };
+    // four rows per trip: all their loads are issued before the first sum needs one
+    constexpr int U = 4;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    long r = r_lo + lane_r;
+    for (; r + (long)(U - 1) * rpi < r_hi; r += (long)U * rpi) {
+      float4 xv[U], gv[U], yv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const size_t off = (size_t)(r + (long)u * rpi) * c + (size_t)cg * 4;
+        xv[u] = *reinterpret_cast<const float4*>(x + off);
+        gv[u] = MODE == 1 ? *reinterpret_cast<const float4*>(dy + off) : zero4;
+        yv[u] = (MODE == 1 && y) ? *reinterpret_cast<const float4*>(y + off) : zero4;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) add_row(xv[u], gv[u], yv[u]);
+    }
+    for (; r < r_hi; r += rpi) {
+      const size_t off = (size_t)r * c + (size_t)cg * 4;
+      const float4 xv = *reinterpret_cast<const float4*>(x + off);
+      const float4 gv = MODE == 1 ? *reinterpret_cast<const float4*>(dy + off) : zero4;
+      const float4 yv = (MODE == 1 && y) ? *reinterpret_cast<const float4*>(y + off) : zero4;
+      add_row(xv, gv, yv);
     }
   }
 #pragma unroll
@@ -118,29 +136,36 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
   }
 }
 
-// Adds the slab partials of FIN_CH channels per workgroup in a fixed order: lane s of a
-// channel adds slabs s, s+FIN_LANES, ...; the channel's first lane then adds the lanes.
+// Adds the slab partials of one channel per wave in a fixed order: lane l adds slabs l,
+// l+64, ..., then a butterfly over the wave adds the lanes (every lane ends with the same sum).
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
 __device__ __forceinline__ void sum_partials(const double* __restrict__ part, int c, int slabs, int ch,
-                                             int s, double (*sh)[FIN_LANES][FIN_CH], double* out0,
-                                             double* out1) {
-  double a0 = 0.0, a1 = 0.0;
-  if (ch < c)
-    for (int k = s; k < slabs; k += FIN_LANES) {
-      a0 += part[((size_t)0 * MAX_SLABS + k) * c + ch];
-      a1 += part[((size_t)1 * MAX_SLABS + k) * c + ch];
-    }
-  const int cl = threadIdx.x % FIN_CH;
-  sh[0][s][cl] = a0;
-  sh[1][s][cl] = a1;
-  __syncthreads();
-  if (s == 0) {
-    for (int k = 1; k < FIN_LANES; ++k) {
-      a0 += sh[0][k][cl];
-      a1 += sh[1][k][cl];
-    }
+                                             int lane, double* out0, double* out1) {
+  // every load of the lane is issued before the first sum: the partials were written by
+  // other compute units a moment ago, so each access pays a full trip to memory
+  constexpr int PER_LANE = MAX_SLABS / 64;
+  double v0[PER_LANE], v1[PER_LANE];
+  const double* p0 = part + (ch < c ? ch : 0);
+  const double* p1 = p0 + (size_t)MAX_SLABS * c;
+#pragma unroll
+  for (int u = 0; u < PER_LANE; ++u) {
+    const int k = lane + 64 * u;
+    const bool ok = ch < c && k < slabs;
+    const size_t at = ok ? (size_t)k * c : 0;   // slab 0 always exists; its value is dropped
+    const double w0 = p0[at], w1 = p1[at];
+    v0[u] = ok ? w0 : 0.0;
+    v1[u] = ok ? w1 : 0.0;
   }
-  *out0 = a0;
-  *out1 = a1;
+  double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+  for (int u = 0; u < PER_LANE; ++u) { a0 += v0[u]; a1 += v1[u]; }
+  *out0 = wave_sum(a0);
+  *out1 = wave_sum(a1);
 }
 
 // forward:  mean, istd; coef[0] = scale = gamma*istd, coef[1] = mean, coef[2] = beta
@@ -148,11 +173,10 @@ __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
     const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ beta,
     float* __restrict__ mean, float* __restrict__ istd, float* __restrict__ coef, long rows, int c,
     float eps, int slabs) {
-  __shared__ double sh[2][FIN_LANES][FIN_CH];
-  const int ch = blockIdx.x * FIN_CH + threadIdx.x % FIN_CH, s = threadIdx.x / FIN_CH;
+  const int ch = blockIdx.x * FIN_CH + threadIdx.x / 64, lane = threadIdx.x & 63;
   double sum, ss;
-  sum_partials(part, c, slabs, ch, s, sh, &sum, &ss);
-  if (s != 0 || ch >= c) return;
+  sum_partials(part, c, slabs, ch, lane, &sum, &ss);
+  if (lane != 0 || ch >= c) return;
   const double m = (double)rows;
   const double mu = sum / m;
   double var = ss / m - mu * mu;
@@ -171,11 +195,10 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_finish_kernel(
     const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ istd,
     float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef, long rows, int c,
     int slabs) {
-  __shared__ double sh[2][FIN_LANES][FIN_CH];
-  const int ch = blockIdx.x * FIN_CH + threadIdx.x % FIN_CH, s = threadIdx.x / FIN_CH;
+  const int ch = blockIdx.x * FIN_CH + threadIdx.x / 64, lane = threadIdx.x & 63;
   double db, dg;
-  sum_partials(part, c, slabs, ch, s, sh, &db, &dg);
-  if (s != 0 || ch >= c) return;
+  sum_partials(part, c, slabs, ch, lane, &db, &dg);
+  if (lane != 0 || ch >= c) return;
   dbeta[ch] = (float)db;
   dgamma[ch] = (float)dg;
   const double m = (double)rows;
@@ -246,9 +269,9 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_apply_kernel(
   }
 }
 
-// slab count: a function of the shape only, at least 8 rows per thread and slab
+// slab count: a function of the shape only, at least ROWS_PER_THREAD rows per thread and slab
 inline int slab_count(long rows, int rpi) {
-  long s = (rows + (long)rpi * 8 - 1) / ((long)rpi * 8);
+  long s = (rows + (long)rpi * ROWS_PER_THREAD - 1) / ((long)rpi * ROWS_PER_THREAD);
   if (s < 1) s = 1;
   if (s > MAX_SLABS) s = MAX_SLABS;
   return (int)s;

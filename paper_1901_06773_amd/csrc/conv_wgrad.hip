@@ -54,14 +54,21 @@ __device__ __forceinline__ int gather_pixel(const WgradGeom& g, int m, int kr, i
 // FAST: cin % 64 == 0 (a tile's columns lie inside one tap), cout % 4 == 0, byte offsets
 // below 2^32.
 template <bool FAST>
-__global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int J, int tiles_j,
-                                                     int chunks_per_split, float* out, size_t split_stride) {
+__global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int J, int tiles_j, int tiles,
+                                                     int splits, int chunks_per_split, float* out,
+                                                     size_t split_stride) {
   __shared__ __attribute__((aligned(16))) float As[2 * BKM * LDT];
   __shared__ __attribute__((aligned(16))) float Bs[2 * BKM * LDT];
 
-  const int tile_co = blockIdx.x / tiles_j, tile_j = blockIdx.x - tile_co * tiles_j;
+  // XCD-aware order: consecutive workgroup ids land on different XCDs, so each XCD gets a
+  // contiguous range of (split, tile) pairs: the tiles of one split read the same rows of
+  // x and dy and find them in that XCD's L2 instead of fetching them once per XCD.
+  const int per_xcd = gridDim.x >> 3;
+  const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (work >= tiles * splits) return;
+  const int split = work / tiles, tile = work - split * tiles;
+  const int tile_co = tile / tiles_j, tile_j = tile - tile_co * tiles_j;
   const int co0 = tile_co * BM, j0 = tile_j * BN;
-  const int split = blockIdx.y;
   const int chunk_lo = split * chunks_per_split;
   const int n_chunks_all = (Mrows + BKM - 1) / BKM;
   const int chunk_hi = min(chunk_lo + chunks_per_split, n_chunks_all);
@@ -306,19 +313,21 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe) {
     return hipErrorInvalidValue;
   const WgradCfg c = choose(Mrows, g.cin, g.cout, g.r, g.s);
   if (c.splits > 1 && !g.workspace) return hipErrorInvalidValue;
-  if (c.splits > 65535) return hipErrorInvalidValue;
+  const long work = (long)c.tiles_co * c.tiles_j * c.splits;
+  if (work > (1L << 30)) return hipErrorInvalidValue;
   const bool fast = (g.cout % 4 == 0) && (g.cin % 64 == 0) && Mrows * g.cout * 4 < (1L << 32) &&
                     (long)g.n_img * g.h * g.wd * g.cin * 4 < (1L << 32);
   float* out = c.splits > 1 ? g.workspace : g.dw;
   const size_t count = (size_t)g.cout * J;
-  const dim3 grid(c.tiles_co * c.tiles_j, c.splits);
+  const dim3 grid((unsigned)((work + 7) / 8 * 8));
+  const int tiles = c.tiles_co * c.tiles_j;
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
   if (fast)
     hipLaunchKernelGGL((wgrad_kernel<true>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j,
-                       c.chunks_per_split, out, count);
+                       tiles, c.splits, c.chunks_per_split, out, count);
   else
     hipLaunchKernelGGL((wgrad_kernel<false>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j,
-                       c.chunks_per_split, out, count);
+                       tiles, c.splits, c.chunks_per_split, out, count);
   if (probe && probe->after) (void)hipEventRecord(probe->after, st);
   if (probe) probe->variant = fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
   hipError_t e = hipGetLastError();

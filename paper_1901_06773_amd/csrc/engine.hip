@@ -55,6 +55,8 @@ struct acc_ctx {
   struct KProbe { int variant; double flops; hipEvent_t a, b; };
   std::vector<KProbe> kprobes;  // one per convolution kernel launch of the last profiled step
   size_t kprobes_used = 0;
+  hipEvent_t empty_pair[2 * 9] = {};  // event pairs with nothing between them: what a probe itself costs
+  double probe_overhead_ms = 0.0;
   double k_ms[V_COUNT] = {}, k_flops[V_COUNT] = {};
   long k_launches[V_COUNT] = {};
   std::vector<double> step_ms;
@@ -221,6 +223,7 @@ extern "C" void acc_destroy(acc_ctx* c) {
     (void)hipStreamSynchronize(c->s_i);
     c->drop_events();
     for (auto& kp : c->kprobes) { (void)hipEventDestroy(kp.a); (void)hipEventDestroy(kp.b); }
+    for (hipEvent_t e : c->empty_pair) if (e) (void)hipEventDestroy(e);
     if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
     if (c->ev_end) (void)hipEventDestroy(c->ev_end);
     if (c->h_loss) (void)hipHostFree(c->h_loss);
@@ -591,6 +594,13 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   }
   uint64_t bytes_out = 0, bytes_in = 0;
   c->kprobes_used = 0;
+  if (c->kernel_profiling) {
+    // the time between two events with no kernel between them is taken off every probe
+    for (hipEvent_t& e : c->empty_pair) {
+      if (!e) HIPCHK(c, hipEventCreate(&e));
+      HIPCHK(c, hipEventRecord(e, c->s_c));
+    }
+  }
   HIPCHK(c, hipEventRecord(c->ev_begin, c->s_c));
   int n_compute = 0;
   for (const Instr& in : P.instrs) {
@@ -678,12 +688,16 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   c->stats.d2h_ms = c->stats.h2d_ms = 0;
   if (c->kernel_profiling) {
     for (int v = 0; v < V_COUNT; ++v) { c->k_ms[v] = 0; c->k_flops[v] = 0; c->k_launches[v] = 0; }
+    float gaps[9];
+    for (int i = 0; i < 9; ++i) HIPCHK(c, hipEventElapsedTime(&gaps[i], c->empty_pair[2 * i], c->empty_pair[2 * i + 1]));
+    std::sort(gaps, gaps + 9);
+    c->probe_overhead_ms = gaps[4];
     for (size_t i = 0; i < c->kprobes_used; ++i) {
       const acc_ctx::KProbe& kp = c->kprobes[i];
       if (kp.variant < 0 || kp.variant >= V_COUNT) continue;
       float ms = 0;
       HIPCHK(c, hipEventElapsedTime(&ms, kp.a, kp.b));
-      c->k_ms[kp.variant] += ms;
+      c->k_ms[kp.variant] += std::max(0.0, (double)ms - c->probe_overhead_ms);
       c->k_flops[kp.variant] += kp.flops;
       c->k_launches[kp.variant] += 1;
     }

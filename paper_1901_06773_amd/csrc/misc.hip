@@ -72,21 +72,26 @@ __global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __res
   }
 }
 
-// Gather form of the max-pool gradient: one thread per input element (n, iy, ix, ch);
-// for every window that covers it, find the window's first maximum again and take the
-// window's dy if this element is the winner.
+// Gather form of the max-pool gradient: one thread per input position and group of V
+// channels (V = 4 as float4 when c % 4 == 0, else 1); for every window that covers the
+// position, find the window's first maximum again and take the window's dy where this
+// position is the winner.  Windows are visited in (p, q) order, so the sum has a fixed order.
+template <int V>
 __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __restrict__ x,
                                                               const float* __restrict__ dy, float* dx,
                                                               int n, int h, int wd, int c, int r, int s,
                                                               int stride, int pad, int ho, int wo,
                                                               int accumulate) {
-  const size_t total = (size_t)n * h * wd * c;
+  struct alignas(4 * V) Vec { float v[V]; };
+  const int cg = c / V;
+  const size_t total = (size_t)n * h * wd * cg;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
-    const int ch = (int)(i % c);
-    size_t rest = i / c;
+    const int g = (int)(i % cg);
+    size_t rest = i / cg;
     const int ix = (int)(rest % wd); rest /= wd;
     const int iy = (int)(rest % h);
     const int img = (int)(rest / h);
+    const int me = iy * wd + ix;
     // windows p with p*stride - pad <= iy <= p*stride - pad + r - 1
     int p_lo = (iy + pad - r + 1 + stride - 1);
     p_lo = p_lo > 0 ? p_lo / stride : 0;
@@ -94,23 +99,39 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __res
     int q_lo = (ix + pad - s + 1 + stride - 1);
     q_lo = q_lo > 0 ? q_lo / stride : 0;
     int q_hi = (ix + pad) / stride; if (q_hi > wo - 1) q_hi = wo - 1;
-    float acc = 0.f;
+    Vec acc;
+#pragma unroll
+    for (int j = 0; j < V; ++j) acc.v[j] = 0.f;
     for (int p = p_lo; p <= p_hi; ++p)
       for (int q = q_lo; q <= q_hi; ++q) {
-        float best = 0.f; int by = -1, bx = -1;
+        Vec best;
+        int at[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) { best.v[j] = 0.f; at[j] = -1; }
         for (int kr = 0; kr < r; ++kr) {
           const int yy = p * stride + kr - pad;
           if ((unsigned)yy >= (unsigned)h) continue;
           for (int kt = 0; kt < s; ++kt) {
             const int xx = q * stride + kt - pad;
             if ((unsigned)xx >= (unsigned)wd) continue;
-            const float v = x[((size_t)(img * h + yy) * wd + xx) * c + ch];
-            if (by < 0 || v > best) { best = v; by = yy; bx = xx; }
+            const Vec v = *reinterpret_cast<const Vec*>(x + ((size_t)(img * h + yy) * wd + xx) * c + g * V);
+#pragma unroll
+            for (int j = 0; j < V; ++j)
+              if (at[j] < 0 || v.v[j] > best.v[j]) { best.v[j] = v.v[j]; at[j] = yy * wd + xx; }
           }
         }
-        if (by == iy && bx == ix) acc += dy[((size_t)(img * ho + p) * wo + q) * c + ch];
+        const Vec d = *reinterpret_cast<const Vec*>(dy + ((size_t)(img * ho + p) * wo + q) * c + g * V);
+#pragma unroll
+        for (int j = 0; j < V; ++j)
+          if (at[j] == me) acc.v[j] += d.v[j];
       }
-    dx[i] = accumulate ? dx[i] + acc : acc;
+    Vec* out = reinterpret_cast<Vec*>(dx + i * V);
+    if (accumulate) {
+      const Vec o = *out;
+#pragma unroll
+      for (int j = 0; j < V; ++j) acc.v[j] = o.v[j] + acc.v[j];
+    }
+    *out = acc;
   }
 }
 
@@ -273,9 +294,15 @@ hipError_t maxpool_backward(const float* x, const float* dy, float* dx, int n, i
     return hipErrorInvalidValue;
   const int ho = (h + 2 * pad - r) / stride + 1, wo = (wd + 2 * pad - s) / stride + 1;
   if (ho <= 0 || wo <= 0) return hipErrorInvalidValue;
-  const size_t total = (size_t)n * h * wd * c;
-  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for(total)), dim3(THREADS), 0, st, x, dy, dx, n, h, wd, c,
-                     r, s, stride, pad, ho, wo, accumulate);
+  if (c % 4 == 0) {
+    const size_t total = (size_t)n * h * wd * (c / 4);
+    hipLaunchKernelGGL(maxpool_bwd_kernel<4>, dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0, st, x, dy, dx, n, h,
+                       wd, c, r, s, stride, pad, ho, wo, accumulate);
+  } else {
+    const size_t total = (size_t)n * h * wd * c;
+    hipLaunchKernelGGL(maxpool_bwd_kernel<1>, dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0, st, x, dy, dx, n, h,
+                       wd, c, r, s, stride, pad, ho, wo, accumulate);
+  }
   return hipGetLastError();
 }
 
