@@ -19,18 +19,18 @@ constexpr int THREADS = 256;
 constexpr int FIN_CH = THREADS / 64;  // the finishing kernels give every channel one wave
 
 struct ReduceShape {
-  int tpr;        // threads across one row (each owns 4 channels)
+  int tpr;        // threads across one row (each owns 4 channels), at most 64
   int rpi;        // rows per iteration of a block
-  int col_slices; // grid.y: slices of 1024 channels
+  int col_slices; // grid.y: slices of 4 * tpr channels
 };
 
 __host__ __device__ inline ReduceShape reduce_shape(int c) {
   ReduceShape s;
   const int cg = c / 4;
-  s.tpr = cg < THREADS ? cg : THREADS;
+  s.tpr = cg < 64 ? cg : 64;
   // tpr need not divide 256: the leftover threads idle
   s.rpi = THREADS / s.tpr;
-  s.col_slices = (cg + THREADS - 1) / THREADS;
+  s.col_slices = (cg + s.tpr - 1) / s.tpr;
   return s;
 }
 
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
   const int tid = threadIdx.x;
   const int lane_r = tid / tpr;            // which row of the iteration
   const int lane_c = tid - lane_r * tpr;   // which channel group
-  const int cg = blockIdx.y * THREADS + lane_c;
+  const int cg = blockIdx.y * tpr + lane_c;
   const bool active = lane_r < rpi && cg * 4 < c;
   const long rows_per_slab = (rows + slabs - 1) / slabs;
   const long r_lo = (long)blockIdx.x * rows_per_slab;
@@ -269,11 +269,14 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_apply_kernel(
   }
 }
 
-// slab count: a function of the shape only, at least ROWS_PER_THREAD rows per thread and slab
-inline int slab_count(long rows, int rpi) {
-  long s = (rows + (long)rpi * ROWS_PER_THREAD - 1) / ((long)rpi * ROWS_PER_THREAD);
+// slab count: a function of the shape only; at least ROWS_PER_THREAD rows per thread and
+// slab, about 1024 workgroups over all column slices (the partials the finishing kernel has
+// to read grow with slabs * c)
+inline int slab_count(long rows, const ReduceShape& rs) {
+  long s = (rows + (long)rs.rpi * ROWS_PER_THREAD - 1) / ((long)rs.rpi * ROWS_PER_THREAD);
+  const long cap = MAX_SLABS / rs.col_slices > 0 ? MAX_SLABS / rs.col_slices : 1;
+  if (s > cap) s = cap;
   if (s < 1) s = 1;
-  if (s > MAX_SLABS) s = MAX_SLABS;
   return (int)s;
 }
 
@@ -297,7 +300,7 @@ hipError_t bn_forward(const float* x, const float* gamma, const float* beta, con
   double* part = static_cast<double*>(workspace);
   float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
   const ReduceShape rs = reduce_shape(c);
-  const int slabs = slab_count(rows, rs.rpi);
+  const int slabs = slab_count(rows, rs);
   hipLaunchKernelGGL(bn_reduce_kernel<0>, dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, nullptr,
                      nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
   hipLaunchKernelGGL(bn_fwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
@@ -317,7 +320,7 @@ hipError_t bn_backward(const float* x, const float* dy, const float* y, const fl
   double* part = static_cast<double*>(workspace);
   float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
   const ReduceShape rs = reduce_shape(c);
-  const int slabs = slab_count(rows, rs.rpi);
+  const int slabs = slab_count(rows, rs);
   hipLaunchKernelGGL(bn_reduce_kernel<1>, dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
                      istd, part, rows, c, rs.tpr, rs.rpi, slabs);
   hipLaunchKernelGGL(bn_bwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
