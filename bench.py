@@ -97,10 +97,19 @@ def main():
 
     # ---- dynamic information: per-step times at the sweep's minibatches, link bandwidth
     t0 = time.time()
-    ctx.calibrate(trainable)
+    fine = list(range(max(1, noswap_max_k - 15), noswap_max_k + 1)) if args.k == "auto" else []
+    ctx.calibrate(sorted(set(trainable + fine)))
     cal = ctx.get_calibration()
     log(f"calibrated at k={cal['ks']} (asked for {trainable}) in {time.time() - t0:.1f}s; "
         f"link {cal['link'][0] / 1e9:.1f} / {cal['link'][1] / 1e9:.1f} GB/s")
+
+    # ---- Algorithm 2 / Eq. 7: the minibatch the performance model expects to be fastest
+    tuner = None
+    if args.k == "auto":
+        tuner, _ = ctx.tune_minibatch(budget, 1, max(sweep_ks))
+        log("tuner", tuner)
+        if tuner["k_best"] not in trainable:
+            trainable = sorted(trainable + [tuner["k_best"]])
 
     cache = {}
 
@@ -241,7 +250,7 @@ def main():
                   predicted_ms=summ["t_iter"] * 1e3, predicted_stall_ms=summ["t_stall"] * 1e3,
                   predicted_compute_ms=summ["t_compute"] * 1e3, plan_ms=summ["plan_ms"],
                   host_issue_ms=stats["host_issue_ms"]),
-        step_ms_by_kind=by_kind, sweep=sweep, noswap_max_k=noswap_max_k, loss=loss,
+        step_ms_by_kind=by_kind, sweep=sweep, noswap_max_k=noswap_max_k, tuner=tuner, loss=loss,
         paper_context="AccUDNN on an NVIDIA M40 (Caffe + cuDNN): ResNet-152, 12 GB budget, k=54, 24 images/s "
                       "(Table 1); 8.3 GB at k=32 with 64% of maps offloaded (Sec. 7.3)")
     print(json.dumps(out))

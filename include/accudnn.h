@@ -171,6 +171,34 @@ int acc_set_calibration(acc_ctx* ctx, const int* ks, int nk, const double* secon
 /* ---- planning (Algorithm 1, Eq. 4-6, body of Algorithm 2) ------------------------- */
 int acc_plan_swaps(acc_ctx* ctx, int minibatch, size_t budget_bytes, int mode,
                    acc_plan_summary* out);
+/* ---- efficiency-optimal minibatch (Sec. 5.1: Eq. 7, Algorithm 2; Sec. 5.2: Eq. 9) --- */
+typedef struct {
+  int32_t k_best;           /* minibatch with the highest predicted images/s              */
+  int32_t k_trainable_max;  /* k_max: largest minibatch in [k_lo, k_hi] that trains at all  */
+  int32_t k_noswap_max;     /* largest minibatch in range that needs no swap (0 if none)   */
+  int32_t n_evaluated;      /* minibatches that were planned and timed by the model       */
+  double images_per_s;      /* k_best / t_iter(k_best), predicted                         */
+  double t_iter;            /* predicted iteration time at k_best, seconds                */
+  double t_stall;           /* predicted stall at k_best, seconds                         */
+  double tune_ms;           /* wall time of the search                                    */
+} acc_tune_result;
+/* Minimises the predicted time per image, t_iter(k) / k (Eq. 3 for one GPU), over the
+ * minibatches of [k_lo, k_hi] that train under the budget (Eq. 4), each with its own swap
+ * plan, and installs the plan of the winner (as acc_plan_swaps(k_best, DYNAMIC) would).
+ * Algorithm 2 walks down from k_max and stops at the first minibatch without a stall
+ * (Eq. 6); that is the optimum when throughput only grows with k.  Here the measured
+ * step times decide instead (on this GPU tile quantisation makes throughput uneven in
+ * k), and a plan with stalls is admitted at its predicted time.  Every minibatch that
+ * needs no swap is evaluated; above that, where one plan costs ~0.1 s, a geometric grid
+ * (ratio 1.15) up to k_max.  Ties go to the larger minibatch.
+ * ACC_EUNTRAINABLE if not even k_lo trains under the budget. */
+int acc_tune_minibatch(acc_ctx* ctx, size_t budget_bytes, int k_lo, int k_hi, acc_tune_result* out,
+                       acc_plan_summary* plan_out);
+/* Eq. 9: the learning rate that keeps the convergence rate when the minibatch grows by
+ * the factor q = k_best / k_base: (1 - (1 - lr_base * c)^q) / c, c = convexity constant
+ * of the objective (0 < lr_base * c < 1).  Returns NaN for arguments outside that range. */
+double acc_adaptive_lr(double lr_base, double c, double q);
+
 /* Plans with an explicit swap decision per map (maps in producer order; 1 = swap). */
 int acc_plan_explicit(acc_ctx* ctx, int minibatch, size_t budget_bytes, const uint8_t* swap,
                       int n_maps, acc_plan_summary* out);

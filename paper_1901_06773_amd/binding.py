@@ -56,6 +56,15 @@ class acc_plan_summary(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class acc_tune_result(C.Structure):
+    _fields_ = [("k_best", C.c_int32), ("k_trainable_max", C.c_int32), ("k_noswap_max", C.c_int32),
+                ("n_evaluated", C.c_int32), ("images_per_s", C.c_double), ("t_iter", C.c_double),
+                ("t_stall", C.c_double), ("tune_ms", C.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
 class acc_step_info(C.Structure):
     _fields_ = [("kind", C.c_int32), ("layer", C.c_int32), ("backward", C.c_int32),
                 ("reserved", C.c_int32), ("flops", C.c_double), ("t_compute", C.c_double),
@@ -105,6 +114,8 @@ _PROTOS = {
     "acc_get_calibration": (_I, [_VP, C.POINTER(_I), _I, C.POINTER(_D), _SZ, C.POINTER(_D)]),
     "acc_set_calibration": (_I, [_VP, C.POINTER(_I), _I, C.POINTER(_D), C.POINTER(_D)]),
     "acc_plan_swaps": (_I, [_VP, _I, _SZ, _I, C.POINTER(acc_plan_summary)]),
+    "acc_tune_minibatch": (_I, [_VP, _SZ, _I, _I, C.POINTER(acc_tune_result), C.POINTER(acc_plan_summary)]),
+    "acc_adaptive_lr": (_D, [_D, _D, _D]),
     "acc_plan_explicit": (_I, [_VP, _I, _SZ, C.POINTER(C.c_uint8), _I, C.POINTER(acc_plan_summary)]),
     "acc_get_step_count": (_I, [_VP]),
     "acc_get_tensor_count": (_I, [_VP]),
@@ -136,6 +147,11 @@ EXPORTED_SYMBOLS = sorted(_PROTOS)
 
 def lib():
     return _lib
+
+
+def adaptive_lr(lr_base: float, c: float, q: float) -> float:
+    """Eq. 9."""
+    return float(_lib.acc_adaptive_lr(float(lr_base), float(c), float(q)))
 
 
 def _layers_array(spec_array: np.ndarray):
@@ -254,6 +270,13 @@ class Context:
         self._check(_lib.acc_plan_swaps(self._h, int(minibatch), int(budget_bytes), int(mode), C.byref(s)))
         self.k = int(minibatch)
         return s.as_dict()
+
+    def tune_minibatch(self, budget_bytes: int, k_lo: int, k_hi: int):
+        """Algorithm 2 / Eq. 7: returns (tune result, plan summary); the winner's plan is installed."""
+        r, s = acc_tune_result(), acc_plan_summary()
+        self._check(_lib.acc_tune_minibatch(self._h, int(budget_bytes), int(k_lo), int(k_hi), C.byref(r), C.byref(s)))
+        self.k = int(r.k_best)
+        return r.as_dict(), s.as_dict()
 
     def plan_explicit(self, minibatch: int, budget_bytes: int, swap: Sequence[int]) -> dict:
         s = acc_plan_summary()

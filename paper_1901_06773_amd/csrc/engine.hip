@@ -17,6 +17,7 @@
 #include "../../include/accudnn.h"
 #include "graph.h"
 #include "kernels.h"
+#include <cmath>
 #include "plan.h"
 
 using namespace acc;
@@ -379,6 +380,69 @@ extern "C" int acc_plan_explicit(acc_ctx* c, int minibatch, size_t budget_bytes,
   simulate(c->g, c->cm, &p);
   p.mode = -1;
   return install_plan(c, std::move(p), out, t0);
+}
+
+extern "C" int acc_tune_minibatch(acc_ctx* c, size_t budget_bytes, int k_lo, int k_hi, acc_tune_result* out,
+                                  acc_plan_summary* plan_out) {
+  if (!c) return ACC_EINVAL;
+  const double t0 = now_ms();
+  if (k_lo <= 0 || k_hi < k_lo || !out) return c->fail(ACC_EINVAL, "need 0 < k_lo <= k_hi and a result struct");
+  c->plan.valid = false;
+  const int nt = (int)c->g.tensors.size();
+  std::vector<uint8_t> none(nt, 0), all(nt, 0);
+  for (int t : c->g.maps) all[t] = 1;
+  auto feasible = [&](int k, const std::vector<uint8_t>& sw) {
+    if (budget_bytes < c->g.static_bytes() + 256) return false;
+    Plan p;
+    std::string why;
+    return build_plan(c->g, k, budget_bytes, sw, PlanOptions(), &p, &why);
+  };
+  auto largest = [&](const std::vector<uint8_t>& sw) {   // feasibility is monotone in k (Eq. 4)
+    if (!feasible(k_lo, sw)) return 0;
+    int lo = k_lo, hi = k_hi;
+    while (lo < hi) {
+      const int mid = lo + (hi - lo + 1) / 2;
+      if (feasible(mid, sw)) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+  };
+  const int k_max = largest(all);
+  if (k_max == 0) return c->fail(ACC_EUNTRAINABLE, "the smallest minibatch of the range does not train under the budget");
+  const int k_fit = largest(none);
+  std::vector<int> cand;
+  for (int k = k_lo; k <= k_fit; ++k) cand.push_back(k);
+  for (double x = std::max(k_fit, k_lo - 1) + 1.0; x <= k_max; x = std::max(x + 1.0, x * 1.15)) cand.push_back((int)x);
+  if (cand.empty() || cand.back() != k_max) cand.push_back(k_max);
+  int best_k = 0, n_eval = 0;
+  double best_rate = -1.0;
+  for (int k : cand) {
+    Plan p;
+    std::string why;
+    if (make_plan(c->g, c->cm, k, budget_bytes, ACC_PLAN_DYNAMIC, &p, &why) != ACC_OK) continue;
+    ++n_eval;
+    const double rate = p.t_iter > 0 ? k / p.t_iter : 0.0;
+    if (rate >= best_rate) { best_rate = rate; best_k = k; }
+  }
+  if (best_k == 0) return c->fail(ACC_EUNTRAINABLE, "no minibatch of the range could be planned");
+  Plan p;
+  std::string why;
+  const int rc = make_plan(c->g, c->cm, best_k, budget_bytes, ACC_PLAN_DYNAMIC, &p, &why);
+  if (rc != ACC_OK) return c->fail(rc, why);
+  out->k_best = best_k;
+  out->k_trainable_max = k_max;
+  out->k_noswap_max = k_fit;
+  out->n_evaluated = n_eval;
+  out->images_per_s = best_rate;
+  out->t_iter = p.t_iter;
+  out->t_stall = p.t_stall;
+  const int rc2 = install_plan(c, std::move(p), plan_out, t0);
+  out->tune_ms = now_ms() - t0;
+  return rc2;
+}
+
+extern "C" double acc_adaptive_lr(double lr_base, double cvx, double q) {
+  if (!(cvx > 0) || !(lr_base > 0) || !(lr_base * cvx < 1) || !(q > 0)) return std::nan("");
+  return (1.0 - std::pow(1.0 - lr_base * cvx, q)) / cvx;
 }
 
 extern "C" int acc_get_step_count(const acc_ctx* c) { return c ? (int)c->g.steps.size() : ACC_EINVAL; }

@@ -369,3 +369,87 @@ def test_planner_against_brute_force_on_toy_networks():
         s = ctx.plan_swaps(k, budget, b.PLAN_DYNAMIC)
         assert s["peak_bytes"] <= budget
         assert s["t_iter"] <= best * 1.10, (frac, s["t_iter"], best)
+
+
+# ------------------------------------------------- efficiency-optimal minibatch (Alg. 2, Eq. 7, Eq. 9)
+def _budget_between(ctx, k_fit, k_swap):
+    """A budget under which k_fit still trains without swapping but k_fit + 1 does not."""
+    b = B()
+    lo = ctx.plan_swaps(k_fit, 1 << 40, b.PLAN_NONE)["peak_bytes"]
+    hi = ctx.plan_swaps(k_fit + 1, 1 << 40, b.PLAN_NONE)["peak_bytes"]
+    assert lo < hi
+    return (lo + hi) // 2
+
+
+def test_tuner_bounds_agree_with_the_planner():
+    b = B()
+    net = S.resnet((1, 1, 2, 1), in_hw=64, classes=100, width=32)
+    ctx = ctx_of(net)
+    ctx.set_cost_model(40e12, 3e12, 4e-6, 50e9, 50e9, 1e-5)
+    budget = _budget_between(ctx, 12, 13)
+    res, summ = ctx.tune_minibatch(budget, 1, 200)
+    # the winner's plan is the installed one
+    assert ctx.k == res["k_best"] and summ["t_iter"] == pytest.approx(res["t_iter"])
+    assert len(ctx.instructions()) == summ["n_instr"]
+    assert res["k_noswap_max"] == 12
+    ctx.plan_swaps(12, budget, b.PLAN_NONE)
+    with pytest.raises(b.AccError):
+        ctx.plan_swaps(13, budget, b.PLAN_NONE)
+    kmax = res["k_trainable_max"]
+    assert 13 <= kmax <= 200
+    ctx.plan_swaps(kmax, budget, b.PLAN_NAIVE_ALL)          # k_max trains with everything swapped ...
+    if kmax < 200:
+        with pytest.raises(b.AccError) as e:                  # ... and k_max + 1 does not (Eq. 4)
+            ctx.plan_swaps(kmax + 1, budget, b.PLAN_DYNAMIC)
+        assert e.value.status == b.ACC_EUNTRAINABLE
+    # no evaluated minibatch is predicted faster
+    assert res["images_per_s"] == pytest.approx(res["k_best"] / res["t_iter"])
+    for k in list(range(1, 13)) + [13, kmax]:
+        s = ctx.plan_swaps(k, budget, b.PLAN_DYNAMIC)
+        assert k / s["t_iter"] <= res["images_per_s"] * (1 + 1e-9), k
+
+
+def test_tuner_follows_measured_step_times():
+    """Step times that rise in stairs of 8 images (what tile quantisation does to a GPU):
+    the best minibatch is the top of the last full stair that fits, not the largest one."""
+    b = B()
+    net = chain(n_units=4, c=32, hw=8)
+    ctx = ctx_of(net)
+    ns = ctx.step_count()
+    ks = list(range(1, 41))
+    table = np.array([[1e-4 * (-(-k // 8)) for _ in range(ns)] for k in ks])
+    ctx.set_calibration(ks, table, (50e9, 50e9, 1e-5))
+    budget = _budget_between(ctx, 21, 22)
+    res, _ = ctx.tune_minibatch(budget, 1, 40)
+    assert res["k_noswap_max"] == 21
+    assert res["k_best"] == 16                      # 16 images cost two stairs, 17..21 cost three
+    # with room for 24 the third stair is full
+    res, _ = ctx.tune_minibatch(_budget_between(ctx, 24, 25), 1, 40)
+    assert res["k_best"] == 24
+
+
+def test_tuner_reports_an_untrainable_range():
+    b = B()
+    net = S.bottleneck_unit()
+    ctx = ctx_of(net)
+    s = ctx.plan_swaps(4, 1 << 40, b.PLAN_NAIVE_ALL)
+    with pytest.raises(b.AccError) as e:
+        ctx.tune_minibatch(s["static_bytes"] + 1024, 4, 8)
+    assert e.value.status == b.ACC_EUNTRAINABLE
+    with pytest.raises(b.AccError):
+        ctx.tune_minibatch(1 << 30, 8, 4)            # empty range
+
+
+def test_adaptive_learning_rate_closed_forms():
+    """Eq. 9 against what it must reduce to: q = 1 gives the base rate, q = 2 gives
+    a(2 - a c), a -> 0 gives the linear scaling rule q a, q -> infinity gives 1/c."""
+    b = B()
+    a, c = 0.1, 0.7
+    assert b.adaptive_lr(a, c, 1.0) == pytest.approx(a, rel=1e-14)
+    assert b.adaptive_lr(a, c, 2.0) == pytest.approx(a * (2 - a * c), rel=1e-14)
+    assert b.adaptive_lr(1e-9, c, 8.0) == pytest.approx(8e-9, rel=1e-6)
+    assert b.adaptive_lr(a, c, 1e6) == pytest.approx(1 / c, rel=1e-12)
+    # the contraction factors of Eq. 8 match: (1 - a c)^(q) == 1 - a* c
+    q = 4.2
+    assert (1 - a * c) ** q == pytest.approx(1 - b.adaptive_lr(a, c, q) * c, rel=1e-13)
+    assert np.isnan(b.adaptive_lr(2.0, 0.7, 2.0)) and np.isnan(b.adaptive_lr(0.1, 0.0, 2.0))
