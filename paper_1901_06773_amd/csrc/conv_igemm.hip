@@ -76,13 +76,36 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
 // FAST: c % 32 == 0, NHWC input, at most 32 filter taps.  Otherwise every element is
 // decoded on its own (any c, K tail); used for the 3-channel stem and for tiny layers.
 template <bool FAST>
-__global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles) {
+__global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
+                                                     int main_grid) {
   __shared__ __attribute__((aligned(16))) float As[2 * BM * LD];
   __shared__ __attribute__((aligned(16))) float Bs[2 * BN * LD];
 
+  if ((int)blockIdx.x >= main_grid) {
+    // side job: 1024 elements of a weight gradient, parts added in their fixed order
+    const ReduceJob& j = g.side;
+    const size_t i4 = ((size_t)(blockIdx.x - main_grid) * 256 + threadIdx.x) * 4;
+    if (i4 >= j.count) return;
+    if (i4 + 4 <= j.count && (j.count & 3) == 0) {
+      float4 sum = *reinterpret_cast<const float4*>(j.part + i4);
+      for (int k = 1; k < j.splits; ++k) {
+        const float4 v = *reinterpret_cast<const float4*>(j.part + (size_t)k * j.count + i4);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+      }
+      *reinterpret_cast<float4*>(j.dw + i4) = sum;
+    } else {
+      for (size_t i = i4; i < j.count && i < i4 + 4; ++i) {
+        float sum = j.part[i];
+        for (int k = 1; k < j.splits; ++k) sum += j.part[(size_t)k * j.count + i];
+        j.dw[i] = sum;
+      }
+    }
+    return;
+  }
+
   // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give
   // each XCD a contiguous range of tiles (neighbouring tiles share operand rows in its L2).
-  const int per_xcd = gridDim.x >> 3;
+  const int per_xcd = main_grid >> 3;
   const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (tile >= n_tiles) return;
   const int tile_m = tile / n_tiles_n, tile_n = tile - tile_m * n_tiles_n;
@@ -304,9 +327,16 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   const int tm = (M + BM - 1) / BM, tn = (g.n_out + BN - 1) / BN;
   const long tiles = (long)tm * tn;
   if (tiles <= 0 || tiles > (1L << 30)) return hipErrorInvalidValue;
-  const int grid = (int)((tiles + 7) / 8 * 8);
+  const int main_grid = (int)((tiles + 7) / 8 * 8);
+  long side_blocks = 0;
+  if (g.side.count) {
+    if (!g.side.part || !g.side.dw || g.side.splits < 1) return hipErrorInvalidValue;
+    side_blocks = (long)((g.side.count + 1023) / 1024);
+  }
+  if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
   if (probe->before) (void)hipEventRecord(probe->before, st);
-  hipLaunchKernelGGL((igemm_kernel<FAST>), dim3(grid), dim3(256), 0, st, g, M, K, tn, (int)tiles);
+  hipLaunchKernelGGL((igemm_kernel<FAST>), dim3((unsigned)(main_grid + side_blocks)), dim3(256), 0, st, g, M, K, tn,
+                     (int)tiles, main_grid);
   if (probe->after) (void)hipEventRecord(probe->after, st);
   return hipGetLastError();
 }

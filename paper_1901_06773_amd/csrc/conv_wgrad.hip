@@ -56,14 +56,36 @@ __device__ __forceinline__ int gather_pixel(const WgradGeom& g, int m, int kr, i
 template <bool FAST>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int J, int tiles_j, int tiles,
                                                      int splits, int chunks_per_split, float* out,
-                                                     size_t split_stride) {
+                                                     size_t split_stride, int main_grid) {
   __shared__ __attribute__((aligned(16))) float As[2 * BKM * LDT];
   __shared__ __attribute__((aligned(16))) float Bs[2 * BKM * LDT];
+
+  if ((int)blockIdx.x >= main_grid) {
+    // side job: one 32 x 32 (co, ci) block of one tap of the flipped, transposed filter
+    const int id = blockIdx.x - main_grid;
+    const int bx = (g.cin + 31) / 32, by = (g.cout + 31) / 32;
+    const int tap = id / (bx * by), rem = id - tap * (bx * by);
+    const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
+    const int kr = g.r - 1 - tap / g.s, kt = g.s - 1 - tap % g.s;
+    const int src_tap = kr * g.s + kt;
+    float (*tile)[33] = reinterpret_cast<float (*)[33]>(As);
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+      const int co = co0f + i, ci = ci0f + tx;
+      tile[i][tx] = (co < g.cout && ci < g.cin) ? g.flip_w[((size_t)co * g.r * g.s + src_tap) * g.cin + ci] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+      const int ci = ci0f + i, co = co0f + tx;
+      if (ci < g.cin && co < g.cout) g.flip_wt[((size_t)ci * g.r * g.s + tap) * g.cout + co] = tile[tx][i];
+    }
+    return;
+  }
 
   // XCD-aware order: consecutive workgroup ids land on different XCDs, so each XCD gets a
   // contiguous range of (split, tile) pairs: the tiles of one split read the same rows of
   // x and dy and find them in that XCD's L2 instead of fetching them once per XCD.
-  const int per_xcd = gridDim.x >> 3;
+  const int per_xcd = main_grid >> 3;
   const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (work >= tiles * splits) return;
   const int split = work / tiles, tile = work - split * tiles;
@@ -302,8 +324,18 @@ size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, 
   return (size_t)c.splits * cout * r * s * cin * sizeof(float);
 }
 
-hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe) {
+hipError_t reduce_parts(const ReduceJob& job, hipStream_t st) {
+  if (job.count == 0) return hipSuccess;
+  if (!job.part || !job.dw || job.splits < 1) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)((job.count + 1023) / 1024);
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, job.part, job.dw, job.count, job.splits);
+  return hipGetLastError();
+}
+
+hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, ReduceJob* deferred) {
+  if (deferred) *deferred = ReduceJob{nullptr, nullptr, 0, 0};
   if (!g.x || !g.dy || !g.dw) return hipErrorInvalidValue;
+  if ((g.flip_w == nullptr) != (g.flip_wt == nullptr)) return hipErrorInvalidValue;
   if (g.n_img <= 0 || g.h <= 0 || g.wd <= 0 || g.cin <= 0 || g.p <= 0 || g.q <= 0 || g.cout <= 0 ||
       g.r <= 0 || g.s <= 0 || g.stride <= 0 || g.pad < 0)
     return hipErrorInvalidValue;
@@ -319,24 +351,26 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe) {
                     (long)g.n_img * g.h * g.wd * g.cin * 4 < (1L << 32);
   float* out = c.splits > 1 ? g.workspace : g.dw;
   const size_t count = (size_t)g.cout * J;
-  const dim3 grid((unsigned)((work + 7) / 8 * 8));
+  const int main_grid = (int)((work + 7) / 8 * 8);
+  const long flip_blocks = g.flip_wt ? (long)((g.cin + 31) / 32) * ((g.cout + 31) / 32) * g.r * g.s : 0;
+  if (main_grid + flip_blocks > (1L << 30)) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(main_grid + flip_blocks));
   const int tiles = c.tiles_co * c.tiles_j;
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
   if (fast)
     hipLaunchKernelGGL((wgrad_kernel<true>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j,
-                       tiles, c.splits, c.chunks_per_split, out, count);
+                       tiles, c.splits, c.chunks_per_split, out, count, main_grid);
   else
     hipLaunchKernelGGL((wgrad_kernel<false>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j,
-                       tiles, c.splits, c.chunks_per_split, out, count);
+                       tiles, c.splits, c.chunks_per_split, out, count, main_grid);
   if (probe && probe->after) (void)hipEventRecord(probe->after, st);
   if (probe) probe->variant = fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (c.splits > 1) {
-    const unsigned blocks = (unsigned)((count + 1023) / 1024);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, g.workspace, g.dw, count,
-                       c.splits);
-    e = hipGetLastError();
+    const ReduceJob job{g.workspace, g.dw, count, c.splits};
+    if (deferred) *deferred = job;
+    else e = reduce_parts(job, st);
   }
   return e;
 }

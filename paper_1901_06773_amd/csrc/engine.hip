@@ -523,10 +523,10 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
     if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
     return e;
   };
-  auto wgrad = [&](const WgradGeom& wg, double flops) {
+  auto wgrad = [&](const WgradGeom& wg, double flops, ReduceJob* deferred) {
     LaunchProbe lp;
     LaunchProbe* pp = c->next_probe(&lp, flops);
-    const hipError_t e = conv_wgrad(wg, st, pp);
+    const hipError_t e = conv_wgrad(wg, st, pp, deferred);
     if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
     return e;
   };
@@ -571,13 +571,17 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw;
       wg.n_img = k; wg.h = 1; wg.wd = 1; wg.cin = l->cin; wg.p = 1; wg.q = 1; wg.cout = l->cout;
       wg.r = 1; wg.s = 1; wg.stride = 1; wg.pad = 0; wg.workspace = ptr(s.ws2);
-      hipError_t e = wgrad(wg, conv_flops);
+      // the transposed filter for the data gradient is written by extra workgroups of the
+      // weight-gradient launch; the parts of the weight gradient are added up by extra
+      // workgroups of the data-gradient launch
+      wg.flip_w = w; wg.flip_wt = ptr(s.ws);
+      ReduceJob job;
+      hipError_t e = wgrad(wg, conv_flops, &job);
       if (e != hipSuccess) return e;
       e = column_sum(ptr(s.dy), dw + (size_t)l->cout * l->cin, k, l->cout, st);
       if (e != hipSuccess) return e;
-      e = filter_flip_transpose(w, ptr(s.ws), l->cout, l->cin, 1, 1, st);
-      if (e != hipSuccess) return e;
       ConvGeom cg{};
+      cg.side = job;
       cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx);
       cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cout; cg.p = 1; cg.q = 1; cg.n_out = l->cin;
       cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
@@ -601,11 +605,13 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       wg.n_img = k; wg.h = h; wg.wd = wd; wg.cin = l->cin; wg.p = ho; wg.q = wo; wg.cout = l->cout;
       wg.r = l->r; wg.s = l->s; wg.stride = l->stride; wg.pad = l->pad;
       wg.workspace = ptr(s.ws2);
-      hipError_t e = wgrad(wg, conv_flops);
-      if (e != hipSuccess || s.dx < 0) return e;
-      e = filter_flip_transpose(w, ptr(s.ws), l->cout, l->cin, l->r, l->s, st);
+      if (s.dx < 0) return wgrad(wg, conv_flops, nullptr);   // first layer: no data gradient
+      wg.flip_w = w; wg.flip_wt = ptr(s.ws);                 // side jobs as in the fc step
+      ReduceJob job;
+      hipError_t e = wgrad(wg, conv_flops, &job);
       if (e != hipSuccess) return e;
       ConvGeom cg{};
+      cg.side = job;
       cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx);
       cg.n_img = k; cg.h = ho; cg.wd = wo; cg.c = l->cout; cg.n_out = l->cin;
       cg.r = l->r; cg.s = l->s; cg.stride = 1; cg.accumulate = s.dx_accumulate;

@@ -12,6 +12,15 @@ namespace acc {
 //   out[m][n] (+)= sum_{r,t,c} in[img, p*stride+r-pad, q*stride+t-pad, c] * w[n][(r,t,c)]
 // with row m = (img, p, q) over a P x Q grid.  The result row is written to pixel
 // (p*out_stride, q*out_stride) of an out_h x out_w image with `n_out` channels.
+// A weight-gradient reduction that has not been launched yet: dw[i] = part[0][i] + part[1][i]
+// + ... (count elements, `splits` parts, in that order).  count == 0: nothing to do.
+struct ReduceJob {
+  const float* part;
+  float* dw;
+  size_t count;
+  int splits;
+};
+
 struct ConvGeom {
   const float* in;
   const float* w;
@@ -22,6 +31,9 @@ struct ConvGeom {
   int r, s, stride, pad;
   int out_h, out_w, out_stride;
   int accumulate;           // out += result
+  // Optional side job: extra workgroups appended to the launch add up the parts of a weight
+  // gradient (independent data; saves a launch of its own).
+  ReduceJob side;
 };
 
 // Optional probe of one launch: which template instance ran (index into conv_variant_name())
@@ -43,9 +55,19 @@ struct WgradGeom {
   int p, q, cout;
   int r, s, stride, pad;
   float* workspace;         // split-K partials, wgrad_workspace_bytes() bytes (may be null if 0)
+  // Optional side job: extra workgroups appended to the launch write the flipped and
+  // transposed filter wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci] of this layer (the data
+  // gradient that follows needs it).  Both null: no side job.
+  const float* flip_w;
+  float* flip_wt;
 };
 size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s);
-hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
+// If `deferred` is given and the gradient is split over the minibatch, the reduction of the
+// parts is not launched but described there (the caller appends it to a later launch or
+// runs reduce_parts); otherwise dw is complete when the stream reaches the end of this call.
+hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe = nullptr,
+                      ReduceJob* deferred = nullptr);
+hipError_t reduce_parts(const ReduceJob& job, hipStream_t st);
 
 // wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci]  (filter of the transposed convolution)
 hipError_t filter_flip_transpose(const float* w, float* wt, int cout, int cin, int r, int s,
