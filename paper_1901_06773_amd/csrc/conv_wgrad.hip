@@ -297,8 +297,9 @@ struct WgradCfg {
   int tiles_co, tiles_j, splits, chunks_per_split;
 };
 
-// Depends on the shape only (never on addresses or on the swap plan): about 1024
-// workgroups in total, at least 24 chunks of 32 rows per split.
+// Depends on the shape only (never on addresses or on the swap plan).  Three workgroups
+// fit a CU (LDS), 768 the chip: the m range is cut into as many parts as keep the launch
+// within that one round, at least 8 chunks of 32 rows each.
 WgradCfg choose(long Mrows, int cin, int cout, int r, int s) {
   WgradCfg c;
   const long J = (long)r * s * cin;
@@ -306,8 +307,8 @@ WgradCfg choose(long Mrows, int cin, int cout, int r, int s) {
   c.tiles_j = (int)((J + BN - 1) / BN);
   const long tiles = (long)c.tiles_co * c.tiles_j;
   const long chunks = (Mrows + BKM - 1) / BKM;
-  long splits = (1024 + tiles - 1) / tiles;
-  const long max_splits = chunks / 24 > 0 ? chunks / 24 : 1;
+  long splits = 768 / tiles;
+  const long max_splits = chunks / 8 > 0 ? chunks / 8 : 1;
   if (splits > max_splits) splits = max_splits;
   if (splits > 1024) splits = 1024;
   if (splits < 1) splits = 1;
