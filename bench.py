@@ -40,6 +40,12 @@ def parse():
     return ap.parse_args()
 
 
+# HBM bytes per launch of the dominant kernel (igemm_kernel<true>), from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this script, scaled by what the same counters read for sgd_kernel
+# (profiles/resnet152_k41_hbm_traffic_pmc.txt).  Known for the profiled workload only.
+MEASURED_TRAFFIC_BYTES = {("resnet152", 41, 8.0): 69.2e6}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -200,7 +206,8 @@ def main():
     conv_ms = sum(r["ms"] for r in kp)
     ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
-                    frac=ach / PEAK_FP32_MFMA_TFLOPS, traffic=None, launches_per_step=dom["launches"],
+                    frac=ach / PEAK_FP32_MFMA_TFLOPS,
+                    traffic=MEASURED_TRAFFIC_BYTES.get((args.net, k, args.budget_gib)), launches_per_step=dom["launches"],
                     avg_launch_us=dom["ms"] * 1e3 / dom["launches"],
                     flop_per_launch=dom["flops"] / dom["launches"],
                     timed_in="the headline run" if timed_swaps else "the no-swap run of the same minibatch")
