@@ -122,12 +122,20 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 
   // One chunk out of LDS half `cur`: 4 k-groups of 8, the fragments of the next group
   // are fetched before the MFMAs of the current one.
-  auto compute_chunk = [&](int cur) {
+  // first fragments of a chunk; fetched early so that their LDS latency hides behind the
+  // stores and global loads of the half-iteration
+  auto first_frag = [&](int cur, float4& a0, float4& b0) {
+    const float* as = As + cur * (BM * LD) + (wm0 + (lane & 31)) * LD + (lane >> 5) * 4;
+    const float* bs = Bs + cur * (BN * LD) + (wn0 + (lane & 31)) * LD + (lane >> 5) * 4;
+    a0 = *reinterpret_cast<const float4*>(as);
+    b0 = *reinterpret_cast<const float4*>(bs);
+  };
+  auto compute_chunk2 = [&](int cur, const float4& a0, const float4& b0) {
     const float* as = As + cur * (BM * LD) + (wm0 + (lane & 31)) * LD + (lane >> 5) * 4;
     const float* bs = Bs + cur * (BN * LD) + (wn0 + (lane & 31)) * LD + (lane >> 5) * 4;
     float4 af[2], bf[2];
-    af[0] = *reinterpret_cast<const float4*>(as);
-    bf[0] = *reinterpret_cast<const float4*>(bs);
+    af[0] = a0;
+    bf[0] = b0;
 #pragma unroll
     for (int g8 = 0; g8 < 4; ++g8) {
       const int c = g8 & 1, nx = c ^ 1;
@@ -140,6 +148,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       acc = mfma32x32x2(af[c].z, bf[c].z, acc);
       acc = mfma32x32x2(af[c].w, bf[c].w, acc);
     }
+  };
+  auto compute_chunk = [&](int cur) {
+    float4 a0, b0;
+    first_frag(cur, a0, b0);
+    compute_chunk2(cur, a0, b0);
   };
 
   // K loop shared by both loaders.  LDS holds two chunks and registers hold two more:
@@ -164,17 +177,24 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       load(ra0, rb0, tap0, 2);
       __syncthreads();
       for (; kc + 4 < n_chunks; kc += 2) {
+        // the first fragments of the chunk are fetched before the stores and loads of this
+        // half-iteration, which then cover their LDS latency
+        float4 fa, fb;
+        sched_fence();
+        first_frag(0, fa, fb);
         sched_fence();
         store(ra1, rb1, tap1, 1);          // chunk kc+1
         load(ra1, rb1, tap1, kc + 3);
         sched_fence();
-        compute_chunk(0);
+        compute_chunk2(0, fa, fb);
         __syncthreads();
+        sched_fence();
+        first_frag(1, fa, fb);
         sched_fence();
         store(ra0, rb0, tap0, 0);          // chunk kc+2
         load(ra0, rb0, tap0, kc + 4);
         sched_fence();
-        compute_chunk(1);
+        compute_chunk2(1, fa, fb);
         __syncthreads();
       }
     } else {

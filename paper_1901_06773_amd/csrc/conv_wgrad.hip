@@ -109,6 +109,23 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
 #pragma unroll
     for (int kk = 0; kk < BKM; kk += 2) acc = mfma32x32x2(as[kk * LDT], bs[kk * LDT], acc);
   };
+  // The same with the first four operand pairs fetched by the caller, early enough for the
+  // stores and global loads of the half-iteration to cover their LDS latency.
+  constexpr int EARLY = 4;
+  auto first_frag = [&](int cur, float (&a)[EARLY], float (&b)[EARLY]) {
+    const float* as = As + cur * (BKM * LDT) + (lane >> 5) * LDT + wm0 + (lane & 31);
+    const float* bs = Bs + cur * (BKM * LDT) + (lane >> 5) * LDT + wn0 + (lane & 31);
+#pragma unroll
+    for (int u = 0; u < EARLY; ++u) { a[u] = as[2 * u * LDT]; b[u] = bs[2 * u * LDT]; }
+  };
+  auto compute_chunk2 = [&](int cur, const float (&a)[EARLY], const float (&b)[EARLY]) {
+    const float* as = As + cur * (BKM * LDT) + (lane >> 5) * LDT + wm0 + (lane & 31);
+    const float* bs = Bs + cur * (BKM * LDT) + (lane >> 5) * LDT + wn0 + (lane & 31);
+#pragma unroll
+    for (int u = 0; u < EARLY; ++u) acc = mfma32x32x2(a[u], b[u], acc);
+#pragma unroll
+    for (int kk = 2 * EARLY; kk < BKM; kk += 2) acc = mfma32x32x2(as[kk * LDT], bs[kk * LDT], acc);
+  };
 
   // same schedule as the forward kernel: chunk c (relative to chunk_lo) lives in LDS half
   // c & 1; chunks c+1 and c+2 wait in the two register sets
@@ -122,17 +139,22 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
       load(r0, 2);
       __syncthreads();
       for (; kc + 4 < n_chunks; kc += 2) {
+        float fa[EARLY], fb[EARLY];
+        sched_fence();
+        first_frag(0, fa, fb);
         sched_fence();
         store(r1, 1);
         load(r1, kc + 3);
         sched_fence();
-        compute_chunk(0);
+        compute_chunk2(0, fa, fb);
         __syncthreads();
+        sched_fence();
+        first_frag(1, fa, fb);
         sched_fence();
         store(r0, 0);
         load(r0, kc + 4);
         sched_fence();
-        compute_chunk(1);
+        compute_chunk2(1, fa, fb);
         __syncthreads();
       }
     } else {
