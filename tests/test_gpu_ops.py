@@ -188,3 +188,72 @@ def test_bad_arguments_are_rejected():
     ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(b.AccError):
         b.op_conv_dgrad(y, w, x, 2, 1, ws)  # strided 3x3 data gradient is not supported
+
+
+# ------------------------------------------------------------------ full-size layers, sampled
+FULL_CASES = [  # the layer shapes of ResNet-152 that carry most of the work, at the benchmark's minibatch
+    (41, 14, 14, 256, 256, 3, 1, 1),
+    (41, 14, 14, 1024, 256, 1, 1, 0),
+    (41, 14, 14, 256, 1024, 1, 1, 0),
+    (41, 28, 28, 128, 128, 3, 1, 1),
+    (41, 56, 56, 64, 256, 1, 1, 0),
+    (41, 56, 56, 256, 512, 1, 2, 0),     # strided projection
+    (41, 7, 7, 512, 512, 3, 1, 1),
+    (41, 224, 224, 3, 64, 7, 2, 3),      # stem (per-element loader)
+]
+
+
+def _sample(rng, shape, count):
+    return [tuple(int(rng.integers(0, d)) for d in shape) for _ in range(count)]
+
+
+@pytest.mark.parametrize("case", FULL_CASES)
+def test_conv_full_size_sampled(case):
+    """Full benchmark shapes (too large for the oracle's whole tensor in seconds): 150 sampled
+    outputs of each of the three GEMMs against the definition written out in float64."""
+    n, h, w, cin, cout, r, stride, pad = case
+    b = B()
+    g = torch.Generator(device="cuda").manual_seed(1234)
+    x = torch.randn(n, h, w, cin, device="cuda", generator=g)
+    wt = torch.randn(cout, r, r, cin, device="cuda", generator=g) * float(np.sqrt(2.0 / (cin * r * r)))
+    ho, wo = (h + 2 * pad - r) // stride + 1, (w + 2 * pad - r) // stride + 1
+    dy = torch.randn(n, ho, wo, cout, device="cuda", generator=g)
+    y = torch.full((n, ho, wo, cout), float("nan"), device="cuda")
+    b.op_conv_fwd(x, wt, y, stride, pad)
+    ws = torch.empty(max(b.op_conv_workspace(n, h, w, cin, cout, r, stride, pad), 256), dtype=torch.uint8, device="cuda")
+    dw = torch.full((cout, r, r, cin), float("nan"), device="cuda")
+    b.op_conv_wgrad(x, dy, dw, stride, pad, ws)
+    do_dgrad = stride == 1 or r == 1
+    if do_dgrad:
+        dx = torch.full((n, h, w, cin), float("nan"), device="cuda")
+        b.op_conv_dgrad(dy, wt, dx, stride, pad, ws, False)
+    torch.cuda.synchronize()
+    X, W_, DY = x.cpu().numpy().astype(np.float64), wt.cpu().numpy().astype(np.float64), dy.cpu().numpy().astype(np.float64)
+    Y, DW = y.cpu().numpy(), dw.cpu().numpy()
+    assert np.isfinite(Y).all() and np.isfinite(DW).all()
+    rng = np.random.default_rng(7)
+    Xp = np.pad(X, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    scale_y, scale_dw = np.abs(Y).max(), np.abs(DW).max()
+    for (i, p, q, co) in _sample(rng, (n, ho, wo, cout), 150):
+        ref = np.sum(Xp[i, p * stride:p * stride + r, q * stride:q * stride + r, :] * W_[co])
+        assert abs(Y[i, p, q, co] - ref) <= TOL * scale_y, ("fwd", case, (i, p, q, co))
+    for (co, kr, kt, ci) in _sample(rng, (cout, r, r, cin), 150):
+        # dw[co,kr,kt,ci] = sum over images and output positions of dy * the input under tap (kr, kt)
+        patch = Xp[:, kr:kr + (ho - 1) * stride + 1:stride, kt:kt + (wo - 1) * stride + 1:stride, ci]
+        ref = np.sum(patch * DY[:, :, :, co])
+        assert abs(DW[co, kr, kt, ci] - ref) <= TOL * scale_dw, ("wgrad", case, (co, kr, kt, ci))
+    if do_dgrad:
+        DX = dx.cpu().numpy()
+        assert np.isfinite(DX).all()
+        scale_dx = np.abs(DX).max()
+        for (i, iy, ix, ci) in _sample(rng, (n, h, w, cin), 150):
+            ref = 0.0
+            for kr in range(r):
+                for kt in range(r):
+                    py, px = iy + pad - kr, ix + pad - kt
+                    if py % stride or px % stride:
+                        continue
+                    py //= stride; px //= stride
+                    if 0 <= py < ho and 0 <= px < wo:
+                        ref += np.dot(DY[i, py, px, :], W_[:, kr, kt, ci])
+            assert abs(DX[i, iy, ix, ci] - ref) <= TOL * scale_dx, ("dgrad", case, (i, iy, ix, ci))

@@ -52,6 +52,7 @@ NETS = {
 }
 
 
+
 def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=64 * MiB, lr=0.1, explicit=None):
     b = B()
     ctx = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w), pool_bytes=pool or budget, host_bytes=host)
@@ -81,6 +82,39 @@ def test_step_matches_oracle(name):
     for i, (a, r) in enumerate(zip(g["weights"], o_w)):
         if r.size:
             close(a, r, f"{name} updated weights of layer {i}")
+
+
+def test_resnet152_at_full_input_size_is_as_close_to_the_exact_step_as_fp32_allows():
+    """The benchmark's network at 224x224 and a minibatch the oracle finishes in seconds.
+    152 layers at random initialisation amplify rounding: the oracle run with fp32 storage
+    and the oracle run entirely in double differ by 1-4 % in the gradients (by 1e-6 in the
+    loss), so 1e-4 against either is not a meaningful bar here.  What is: the GPU step must
+    be as close to the exact (double) step as the fp32-storage oracle is, within a factor 3
+    per gradient tensor, plus 1e-3 (ten times the one-layer tolerance) for what fp32 MFMA
+    accumulation adds over 155 convolutions where the oracle accumulates in double; the loss
+    within 1e-4."""
+    net = S.resnet152()
+    k = 4
+    params = S.init_params(net)
+    img, lab = S.make_batch(net, k, 0)
+    chw = (net.in_c, net.in_h, net.in_w)
+    l32, _, g32 = O.train_step(net.as_array(), chw, params, img, lab, 0.1)
+    l64, _, g64 = O.train_step(net.as_array(), chw, [p.astype(np.float64) for p in params],
+                               img.astype(np.float64), lab, 0.1)
+    g = run_gpu(net, params, k, B().PLAN_NONE, 2048 * MiB)
+    close(g["losses"][0], l64, "loss against the exact step")
+    close(g["losses"][0], l32, "loss against the fp32-storage oracle")
+    worst = 0.0
+    for i, (a, r32, r64) in enumerate(zip(g["grads"], g32, g64)):
+        if not r64.size:
+            continue
+        n64 = np.linalg.norm(r64)
+        e_gpu = np.linalg.norm(np.asarray(a, np.float64) - r64) / n64
+        e_o32 = np.linalg.norm(r32.astype(np.float64) - r64) / n64
+        worst = max(worst, e_gpu / max(e_o32, 1e-6))
+        assert np.isfinite(e_gpu) and e_gpu <= 3.0 * e_o32 + 1e-3, \
+            f"layer {i} ({S.KIND_NAMES[net.layers[i].kind]}): gpu {e_gpu:.3e}, fp32 oracle {e_o32:.3e}"
+    print(f"worst gpu / fp32-oracle error ratio against the exact step: {worst:.2f}")
 
 
 def test_three_steps_follow_the_oracle():
@@ -192,3 +226,27 @@ def test_device_resident_input_and_error_paths():
     l_host = ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.1)
     assert l_dev == l_host
     ctx.close()
+
+
+def test_resnet152_at_the_benchmark_size_swapped_and_resident_agree_bit_for_bit():
+    """The benchmark's network and minibatch (ResNet-152, 224x224, k = 41): a planner-chosen
+    partial swap under 5 GiB against the resident run under 8 GiB, two steps, every bit of
+    loss and updated weights; and the loss of the first step is what 1000 classes at random
+    initialisation give (ln 1000 plus the spread of the logits)."""
+    GiB = 1 << 30
+    net = S.resnet152()
+    k = 41
+    params = S.init_params(net)
+    b = B()
+    ref = run_gpu(net, params, k, b.PLAN_NONE, 8 * GiB, steps=2, host=64 * MiB)
+    probe = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w))
+    need = probe.plan_swaps(k, 5 * GiB, b.PLAN_DYNAMIC)
+    probe.close()
+    assert need["n_swapped"] > 0
+    out = run_gpu(net, params, k, b.PLAN_DYNAMIC, 5 * GiB, steps=2, host=need["host_bytes"] + 64 * MiB)
+    assert out["summary"]["n_swapped"] > 0 and out["stats"]["bytes_out"] == out["summary"]["bytes_swapped"]
+    assert out["stats"]["peak_pool_bytes"] <= 5 * GiB
+    for a, r in zip(out["losses"], ref["losses"]):
+        assert np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
+    bit_equal(out["weights"], ref["weights"], "weights")
+    assert np.log(1000.0) < ref["losses"][0] < np.log(1000.0) + 3.0
