@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--budget-gib", type=float, default=8.0)
     ap.add_argument("--net", default="resnet152", choices=["resnet50", "resnet101", "resnet152"])
     ap.add_argument("--mode", default="dynamic", choices=["dynamic", "naive", "none"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage of activations / gradients / kernel-side weights (bf16: configs[4])")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-noswap-reference", action="store_true")
     ap.add_argument("--cpu-sample-k", type=int, default=12)
@@ -70,7 +72,8 @@ def main():
         sweep_ks = sorted(set(sweep_ks + [int(args.k)]))
 
     # ---- static analysis without the GPU: which minibatches are trainable, how much host memory
-    probe = B.Context(net.as_array(), chw)
+    dtype = B.BF16 if args.dtype == "bf16" else B.F32
+    probe = B.Context(net.as_array(), chw, dtype=dtype)
     trainable, host_need = [], 256
     for k in sweep_ks:
         try:
@@ -97,7 +100,7 @@ def main():
 
     torch.cuda.set_device(0)
     t0 = time.time()
-    ctx = B.Context(net.as_array(), chw, pool_bytes=budget, host_bytes=host_need + (64 << 20))
+    ctx = B.Context(net.as_array(), chw, pool_bytes=budget, host_bytes=host_need + (64 << 20), dtype=dtype)
     ctx.set_weights(S.init_params(net))
     log(f"context ready in {time.time() - t0:.1f}s: pool {budget / GiB:.2f} GiB, pinned host {host_need / GiB:.2f} GiB")
 
@@ -182,7 +185,7 @@ def main():
     sec0 = None
     if (not args.no_noswap_reference and summ["n_swapped"] > 0) or not timed_swaps:
         big = int(summ["noswap_peak_bytes"] * 1.02) + (64 << 20)
-        ctx2 = B.Context(net.as_array(), chw, pool_bytes=big, host_bytes=256)
+        ctx2 = B.Context(net.as_array(), chw, pool_bytes=big, host_bytes=256, dtype=dtype)
         ctx2.set_weights(S.init_params(net))
         ctx2.plan_swaps(k, big, B.PLAN_NONE)
         imgs = batch(k, 0)
@@ -205,9 +208,12 @@ def main():
     conv_flops = sum(r["flops"] for r in kp)
     conv_ms = sum(r["ms"] for r in kp)
     ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
-                    frac=ach / PEAK_FP32_MFMA_TFLOPS,
-                    traffic=MEASURED_TRAFFIC_BYTES.get((args.net, k, args.budget_gib)), launches_per_step=dom["launches"],
+    # bf16 mode: the forward / data-gradient kernel multiplies bf16 on the matrix cores (dense peak
+    # 2.5 PFLOP/s); the weight-gradient kernel widens its operands and uses the fp32 instruction
+    peak = 2500.0 if (args.dtype == "bf16" and dom["name"].startswith("igemm")) else PEAK_FP32_MFMA_TFLOPS
+    roofline = dict(bound="mfma", kernel=dom["name"], achieved=ach, peak=peak, unit="TFLOP/s",
+                    frac=ach / peak,
+                    traffic=MEASURED_TRAFFIC_BYTES.get((args.net, k, args.budget_gib)) if args.dtype == "f32" else None, launches_per_step=dom["launches"],
                     avg_launch_us=dom["ms"] * 1e3 / dom["launches"],
                     flop_per_launch=dom["flops"] / dom["launches"],
                     timed_in="the headline run" if timed_swaps else "the no-swap run of the same minibatch")
@@ -244,11 +250,12 @@ def main():
                    kind="oracle", sample=f"one {args.net} training step at minibatch {kc} ({dt:.1f} s)")
 
     out = dict(
-        metric="train images/s (ResNet-152 fp32, 8 GiB HBM budget) + conv MFMA utilisation",
+        metric="train images/s (ResNet-152 fp32, 8 GiB HBM budget) + conv MFMA utilisation" if (args.net, args.dtype, args.budget_gib) == ("resnet152", "f32", 8.0)
+        else f"train images/s ({args.net} {args.dtype}, {args.budget_gib} GiB HBM budget) + conv MFMA utilisation",
         value=value, unit="images/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
-        ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32",
+        ms_per_step=sec * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype=args.dtype,
         data="synthetic",
-        config=dict(workload=f"{args.net} fp32 training step, 224x224x3 N(0,1) images, 1000 classes, "
+        config=dict(workload=f"{args.net} {'fp32' if args.dtype == 'f32' else 'bf16 (fp32 master weights and statistics)'} training step, 224x224x3 N(0,1) images, 1000 classes, "
                              f"minibatch {k}, device-memory budget {args.budget_gib} GiB, planner mode {args.mode}",
                     minibatch=k, budget_gib=args.budget_gib, strides="v1", optimizer="plain SGD lr 0.1"),
         roofline=roofline, cpu_baseline=cpu, conv=conv, swap=swap, noswap_reference=noswap,

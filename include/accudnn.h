@@ -125,7 +125,11 @@ typedef struct acc_ctx acc_ctx;
 
 /* ---- context ---------------------------------------------------------------------- */
 /* Builds the fused step list and the tensor table (static information of Sec. 4.2).
- * With resources: places weights / gradients / statistics at the bottom of the pool. */
+ * With resources: places weights / gradients / statistics at the bottom of the pool.
+ * dtype: ACC_F32, or ACC_BF16 = activations, activation gradients and the copy of the
+ * weights that the kernels read are stored as bf16 (half the bytes to keep and to swap),
+ * products accumulate in fp32, master weights, weight gradients, batch-norm parameters and
+ * statistics and the loss stay fp32; images and weights cross the boundary as fp32 either way. */
 int acc_create(const acc_layer* layers, int n_layers, int in_c, int in_h, int in_w, int dtype,
                const acc_resources* res, acc_ctx** out);
 void acc_destroy(acc_ctx* ctx);
@@ -137,8 +141,6 @@ const char* acc_step_kind_name(int kind);
 int acc_set_weights(acc_ctx* ctx, int layer, const float* host_w, size_t n);
 int acc_get_weights(acc_ctx* ctx, int layer, float* host_w, size_t n);
 int acc_get_grads(acc_ctx* ctx, int layer, float* host_g, size_t n);
-/* forward output of a layer that the last plan keeps (a retained map), NCHW, host.
- * Valid after train_step only for maps that were not swapped; parity/debug hook. */
 int acc_param_count(const acc_ctx* ctx, int layer, size_t* n);
 
 /* ---- cost model (dynamic information, Sec. 4.2; Eq. 2 and Eq. 5) ------------------- */
@@ -247,30 +249,33 @@ int acc_get_kernel_profile(acc_ctx* ctx, acc_kernel_profile* out, int max_entrie
 int acc_get_step_times_ms(acc_ctx* ctx, double* ms, int n);
 
 /* ---- single operations on caller-owned device buffers (parity and roofline) ------- */
-/* All pointers device, fp32; x / y / dy / dx NHWC, w / dw O-H-W-I; stream is a
- * hipStream_t.  workspace may be NULL when workspace_bytes is 0; query the need with
- * acc_op_conv_workspace().  accumulate != 0 adds into dx instead of overwriting. */
+/* All pointers device; x / y / dy / dx / res / g_out NHWC and w (O-H-W-I) are stored as
+ * `dtype` says (ACC_F32, or ACC_BF16 = the upper half of an fp32, round to nearest even);
+ * dw (O-H-W-I), gamma, beta, mean, istd, dgamma, dbeta are always fp32.  Arithmetic is fp32
+ * (bf16 products accumulate in fp32).  stream is a hipStream_t.  workspace may be NULL when
+ * workspace_bytes is 0; query the need with acc_op_conv_workspace().  accumulate != 0 adds
+ * into dx instead of overwriting. */
 size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, int r, int s, int stride,
                              int pad);
-int acc_op_conv_fwd(const float* x, const float* w, float* y, int n, int h, int wd, int cin,
-                    int cout, int r, int s, int stride, int pad, void* stream);
-int acc_op_conv_dgrad(const float* dy, const float* w, float* dx, int n, int h, int wd, int cin,
+int acc_op_conv_fwd(const void* x, const void* w, void* y, int n, int h, int wd, int cin,
+                    int cout, int r, int s, int stride, int pad, int dtype, void* stream);
+int acc_op_conv_dgrad(const void* dy, const void* w, void* dx, int n, int h, int wd, int cin,
                       int cout, int r, int s, int stride, int pad, int accumulate,
-                      void* workspace, size_t workspace_bytes, void* stream);
-int acc_op_conv_wgrad(const float* x, const float* dy, float* dw, int n, int h, int wd, int cin,
+                      void* workspace, size_t workspace_bytes, int dtype, void* stream);
+int acc_op_conv_wgrad(const void* x, const void* dy, float* dw, int n, int h, int wd, int cin,
                       int cout, int r, int s, int stride, int pad, void* workspace,
-                      size_t workspace_bytes, void* stream);
+                      size_t workspace_bytes, int dtype, void* stream);
 /* y = relu?(gamma*(x-mean)*istd + beta (+ res)); saves mean / istd (c floats each).
  * workspace: acc_op_bn_workspace(c) bytes. */
 size_t acc_op_bn_workspace(int c);
-int acc_op_bn_fwd(const float* x, const float* gamma, const float* beta, const float* res,
-                  float* y, float* mean, float* istd, int rows, int c, int relu, float eps,
-                  void* workspace, void* stream);
+int acc_op_bn_fwd(const void* x, const float* gamma, const float* beta, const void* res,
+                  void* y, float* mean, float* istd, int rows, int c, int relu, float eps,
+                  void* workspace, int dtype, void* stream);
 /* dy is masked by (y > 0) when y != NULL (fused ReLU); when g_out != NULL the masked
  * gradient is also written there (it may alias dy). */
-int acc_op_bn_bwd(const float* x, const float* dy, const float* y, const float* gamma,
-                  const float* mean, const float* istd, float* dx, float* dgamma, float* dbeta,
-                  float* g_out, int rows, int c, void* workspace, void* stream);
+int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const float* gamma,
+                  const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
+                  void* g_out, int rows, int c, void* workspace, int dtype, void* stream);
 
 #ifdef __cplusplus
 }

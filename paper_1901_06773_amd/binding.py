@@ -130,12 +130,12 @@ _PROTOS = {
     "acc_get_step_times_ms": (_I, [_VP, C.POINTER(_D), _I]),
     "acc_get_kernel_profile": (_I, [_VP, C.POINTER(acc_kernel_profile), _I]),
     "acc_op_conv_workspace": (_SZ, [_I] * 9),
-    "acc_op_conv_fwd": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_VP]),
-    "acc_op_conv_dgrad": (_I, [_VP, _VP, _VP] + [_I] * 10 + [_VP, _SZ, _VP]),
-    "acc_op_conv_wgrad": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_VP, _SZ, _VP]),
+    "acc_op_conv_fwd": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_I, _VP]),
+    "acc_op_conv_dgrad": (_I, [_VP, _VP, _VP] + [_I] * 10 + [_VP, _SZ, _I, _VP]),
+    "acc_op_conv_wgrad": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_VP, _SZ, _I, _VP]),
     "acc_op_bn_workspace": (_SZ, [_I]),
-    "acc_op_bn_fwd": (_I, [_VP] * 7 + [_I, _I, _I, _F, _VP, _VP]),
-    "acc_op_bn_bwd": (_I, [_VP] * 10 + [_I, _I, _VP, _VP]),
+    "acc_op_bn_fwd": (_I, [_VP] * 7 + [_I, _I, _I, _F, _VP, _I, _VP]),
+    "acc_op_bn_bwd": (_I, [_VP] * 10 + [_I, _I, _VP, _I, _VP]),
 }
 for _name, (_res, _args) in _PROTOS.items():
     _fn = getattr(_lib, _name)
@@ -166,8 +166,9 @@ class Context:
     """One network on one GPU (or, with pool_bytes=None, a planning-only context)."""
 
     def __init__(self, spec_array: np.ndarray, in_chw: Sequence[int], pool_bytes: Optional[int] = None,
-                 host_bytes: int = 0, device: str = "cuda:0"):
+                 host_bytes: int = 0, device: str = "cuda:0", dtype: int = F32):
         self._h = _VP()
+        self.dtype = int(dtype)
         self._keep = []
         arr, n = _layers_array(spec_array)
         self.n_layers = n
@@ -185,7 +186,7 @@ class Context:
                                 self.streams[2].cuda_stream)
             res_ptr = C.byref(res)
             torch.cuda.synchronize(self.device)
-        rc = _lib.acc_create(arr, n, int(in_chw[0]), int(in_chw[1]), int(in_chw[2]), F32, res_ptr, C.byref(self._h))
+        rc = _lib.acc_create(arr, n, int(in_chw[0]), int(in_chw[1]), int(in_chw[2]), self.dtype, res_ptr, C.byref(self._h))
         if rc != ACC_OK:
             raise AccError(rc, _lib.acc_last_error(None).decode())
 
@@ -359,12 +360,22 @@ def op_conv_workspace(n, h, w, cin, cout, r, stride, pad) -> int:
     return int(_lib.acc_op_conv_workspace(n, h, w, cin, cout, r, r, stride, pad))
 
 
+def _dtype_of(t) -> int:
+    """Storage type of a torch tensor handed to an acc_op_* call."""
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported storage type {t.dtype}")
+
+
 def op_conv_fwd(x, w, y, stride, pad):
     import torch
     n, h, wd, cin = x.shape
     cout, r, s, _ = w.shape
     rc = _lib.acc_op_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), n, h, wd, cin, cout, r, s, stride, pad,
-                              _stream_ptr(torch))
+                              _dtype_of(x), _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_conv_fwd")
 
@@ -375,7 +386,7 @@ def op_conv_dgrad(dy, w, dx, stride, pad, ws, accumulate=False):
     cout, r, s, _ = w.shape
     rc = _lib.acc_op_conv_dgrad(dy.data_ptr(), w.data_ptr(), dx.data_ptr(), n, h, wd, cin, cout, r, s, stride, pad,
                                 1 if accumulate else 0, ws.data_ptr(), ws.numel() * ws.element_size(),
-                                _stream_ptr(torch))
+                                _dtype_of(dy), _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_conv_dgrad")
 
@@ -386,7 +397,8 @@ def op_conv_wgrad(x, dy, dw, stride, pad, ws):
     cout, r, s, _ = dw.shape
     rc = _lib.acc_op_conv_wgrad(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), n, h, wd, cin, cout, r, s, stride, pad,
                                 ws.data_ptr() if ws is not None else None,
-                                ws.numel() * ws.element_size() if ws is not None else 0, _stream_ptr(torch))
+                                ws.numel() * ws.element_size() if ws is not None else 0, _dtype_of(x),
+                                _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_conv_wgrad")
 
@@ -401,7 +413,8 @@ def op_bn_fwd(x, gamma, beta, res, y, mean, istd, relu, eps, ws):
     rows = x.numel() // c
     rc = _lib.acc_op_bn_fwd(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(),
                             res.data_ptr() if res is not None else None, y.data_ptr(), mean.data_ptr(),
-                            istd.data_ptr(), rows, c, 1 if relu else 0, float(eps), ws.data_ptr(), _stream_ptr(torch))
+                            istd.data_ptr(), rows, c, 1 if relu else 0, float(eps), ws.data_ptr(), _dtype_of(x),
+                            _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_bn_fwd")
 
@@ -413,6 +426,6 @@ def op_bn_bwd(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, ws):
     rc = _lib.acc_op_bn_bwd(x.data_ptr(), dy.data_ptr(), y.data_ptr() if y is not None else None, gamma.data_ptr(),
                             mean.data_ptr(), istd.data_ptr(), dx.data_ptr(), dgamma.data_ptr(), dbeta.data_ptr(),
                             g_out.data_ptr() if g_out is not None else None, rows, c, ws.data_ptr(),
-                            _stream_ptr(torch))
+                            _dtype_of(x), _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_bn_bwd")

@@ -9,6 +9,7 @@
 //
 // workspace layout (bn_workspace_bytes): double part[2][MAX_SLABS][c] | float coef[4][c]
 #include "kernels.h"
+#include "dtype.h"
 
 namespace acc {
 namespace {
@@ -36,10 +37,10 @@ __host__ __device__ inline ReduceShape reduce_shape(int c) {
 
 // Sums over the rows of one slab, per channel, of up to two quantities.
 // MODE 0: (x, x*x).   MODE 1: (g, g*xhat) with g = dy * [y > 0] (y optional).
-template <int MODE>
-__global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restrict__ x,
-                                                            const float* __restrict__ dy,
-                                                            const float* __restrict__ y,
+template <int MODE, class T>
+__global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const T* __restrict__ x,
+                                                            const T* __restrict__ dy,
+                                                            const T* __restrict__ y,
                                                             const float* __restrict__ mean,
                                                             const float* __restrict__ istd,
                                                             double* __restrict__ part, long rows,
@@ -63,8 +64,7 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
       mu[0] = m4.x; mu[1] = m4.y; mu[2] = m4.z; mu[3] = m4.w;
       is[0] = i4.x; is[1] = i4.y; is[2] = i4.z; is[3] = i4.w;
     }
-    auto add_row = [&](const float4& xv, const float4& gv, const float4& yv) {
-      const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
+    auto add_row = [&](const float (&xs)[4], const float (&gv)[4], const float (&ys)[4]) {
       if (MODE == 0) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -73,9 +73,8 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
           s1[j] += d * d;
         }
       } else {
-        float gs[4] = {gv.x, gv.y, gv.z, gv.w};
+        float gs[4] = {gv[0], gv[1], gv[2], gv[3]};
         if (y) {
-          const float ys[4] = {yv.x, yv.y, yv.z, yv.w};
 #pragma unroll
           for (int j = 0; j < 4; ++j) gs[j] = ys[j] > 0.f ? gs[j] : 0.f;
         }
@@ -89,25 +88,25 @@ __global__ __launch_bounds__(THREADS) void bn_reduce_kernel(const float* __restr
     };
     // four rows per trip: all their loads are issued before the first sum needs one
     constexpr int U = 4;
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
     long r = r_lo + lane_r;
     for (; r + (long)(U - 1) * rpi < r_hi; r += (long)U * rpi) {
-      float4 xv[U], gv[U], yv[U];
+      float xv[U][4], gv[U][4] = {}, yv[U][4] = {};
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const size_t off = (size_t)(r + (long)u * rpi) * c + (size_t)cg * 4;
-        xv[u] = *reinterpret_cast<const float4*>(x + off);
-        gv[u] = MODE == 1 ? *reinterpret_cast<const float4*>(dy + off) : zero4;
-        yv[u] = (MODE == 1 && y) ? *reinterpret_cast<const float4*>(y + off) : zero4;
+        Elem<T>::load4(x + off, xv[u]);
+        if (MODE == 1) Elem<T>::load4(dy + off, gv[u]);
+        if (MODE == 1 && y) Elem<T>::load4(y + off, yv[u]);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) add_row(xv[u], gv[u], yv[u]);
     }
     for (; r < r_hi; r += rpi) {
       const size_t off = (size_t)r * c + (size_t)cg * 4;
-      const float4 xv = *reinterpret_cast<const float4*>(x + off);
-      const float4 gv = MODE == 1 ? *reinterpret_cast<const float4*>(dy + off) : zero4;
-      const float4 yv = (MODE == 1 && y) ? *reinterpret_cast<const float4*>(y + off) : zero4;
+      float xv[4], gv[4] = {}, yv[4] = {};
+      Elem<T>::load4(x + off, xv);
+      if (MODE == 1) Elem<T>::load4(dy + off, gv);
+      if (MODE == 1 && y) Elem<T>::load4(y + off, yv);
       add_row(xv, gv, yv);
     }
   }
@@ -209,63 +208,67 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_finish_kernel(
 
 // y = relu?((x-mean)*scale + beta (+ res)), float4 per thread, grid-stride.  Subtracting the
 // mean first keeps the result exact where x equals the mean (a channel of constant values).
-__global__ __launch_bounds__(THREADS) void bn_apply_kernel(const float* __restrict__ x,
-                                                           const float* __restrict__ res,
+template <class T>
+__global__ __launch_bounds__(THREADS) void bn_apply_kernel(const T* __restrict__ x,
+                                                           const T* __restrict__ res,
                                                            const float* __restrict__ coef,
-                                                           float* __restrict__ y, size_t n4, int c,
+                                                           T* __restrict__ y, size_t n4, int c,
                                                            int relu) {
   const int cg = c >> 2;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < n4; i += (size_t)gridDim.x * THREADS) {
     const int g = (int)(i % cg);
-    const float4 xv = reinterpret_cast<const float4*>(x)[i];
+    float xv[4], o[4];
+    Elem<T>::load4(x + i * 4, xv);
     const float4 sc = reinterpret_cast<const float4*>(coef)[g];
     const float4 mu = reinterpret_cast<const float4*>(coef + c)[g];
     const float4 be = reinterpret_cast<const float4*>(coef + 2 * c)[g];
-    float4 o;
-    o.x = fmaf(xv.x - mu.x, sc.x, be.x);
-    o.y = fmaf(xv.y - mu.y, sc.y, be.y);
-    o.z = fmaf(xv.z - mu.z, sc.z, be.z);
-    o.w = fmaf(xv.w - mu.w, sc.w, be.w);
+    o[0] = fmaf(xv[0] - mu.x, sc.x, be.x);
+    o[1] = fmaf(xv[1] - mu.y, sc.y, be.y);
+    o[2] = fmaf(xv[2] - mu.z, sc.z, be.z);
+    o[3] = fmaf(xv[3] - mu.w, sc.w, be.w);
     if (res) {
-      const float4 rv = reinterpret_cast<const float4*>(res)[i];
-      o.x += rv.x; o.y += rv.y; o.z += rv.z; o.w += rv.w;
+      float rv[4];
+      Elem<T>::load4(res + i * 4, rv);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[j] += rv[j];
     }
     if (relu) {
-      o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) o[j] = fmaxf(o[j], 0.f);
     }
-    reinterpret_cast<float4*>(y)[i] = o;
+    Elem<T>::store4(y + i * 4, o);
   }
 }
 
 // dx = a*(g - dbeta/m - xhat*dgamma/m), g = dy*[y>0]; optionally stores g (may alias dy)
+template <class T>
 __global__ __launch_bounds__(THREADS) void bn_bwd_apply_kernel(
-    const float* __restrict__ x, const float* dy, const float* __restrict__ y,
+    const T* __restrict__ x, const T* dy, const T* __restrict__ y,
     const float* __restrict__ mean, const float* __restrict__ istd, const float* __restrict__ coef,
-    float* __restrict__ dx, float* g_out, size_t n4, int c) {
+    T* __restrict__ dx, T* g_out, size_t n4, int c) {
   const int cg = c >> 2;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < n4; i += (size_t)gridDim.x * THREADS) {
     const int g = (int)(i % cg);
-    const float4 xv = reinterpret_cast<const float4*>(x)[i];
-    float4 gv = reinterpret_cast<const float4*>(dy)[i];
+    float xv[4], gv[4], o[4];
+    Elem<T>::load4(x + i * 4, xv);
+    Elem<T>::load4(dy + i * 4, gv);
     if (y) {
-      const float4 yv = reinterpret_cast<const float4*>(y)[i];
-      gv.x = yv.x > 0.f ? gv.x : 0.f;
-      gv.y = yv.y > 0.f ? gv.y : 0.f;
-      gv.z = yv.z > 0.f ? gv.z : 0.f;
-      gv.w = yv.w > 0.f ? gv.w : 0.f;
+      float yv[4];
+      Elem<T>::load4(y + i * 4, yv);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) gv[j] = yv[j] > 0.f ? gv[j] : 0.f;
     }
     const float4 mu = reinterpret_cast<const float4*>(mean)[g];
     const float4 is = reinterpret_cast<const float4*>(istd)[g];
     const float4 a = reinterpret_cast<const float4*>(coef)[g];
     const float4 c1 = reinterpret_cast<const float4*>(coef + c)[g];
     const float4 c2 = reinterpret_cast<const float4*>(coef + 2 * c)[g];
-    float4 o;
-    o.x = a.x * (gv.x - c1.x - (xv.x - mu.x) * is.x * c2.x);
-    o.y = a.y * (gv.y - c1.y - (xv.y - mu.y) * is.y * c2.y);
-    o.z = a.z * (gv.z - c1.z - (xv.z - mu.z) * is.z * c2.z);
-    o.w = a.w * (gv.w - c1.w - (xv.w - mu.w) * is.w * c2.w);
-    reinterpret_cast<float4*>(dx)[i] = o;
-    if (g_out) reinterpret_cast<float4*>(g_out)[i] = gv;
+    o[0] = a.x * (gv[0] - c1.x - (xv[0] - mu.x) * is.x * c2.x);
+    o[1] = a.y * (gv[1] - c1.y - (xv[1] - mu.y) * is.y * c2.y);
+    o[2] = a.z * (gv[2] - c1.z - (xv[2] - mu.z) * is.z * c2.z);
+    o[3] = a.w * (gv[3] - c1.w - (xv[3] - mu.w) * is.w * c2.w);
+    Elem<T>::store4(dx + i * 4, o);
+    if (g_out) Elem<T>::store4(g_out + i * 4, gv);
   }
 }
 
@@ -292,43 +295,71 @@ size_t bn_workspace_bytes(int c) {
   return (size_t)2 * MAX_SLABS * c * sizeof(double) + (size_t)4 * c * sizeof(float);
 }
 
-hipError_t bn_forward(const float* x, const float* gamma, const float* beta, const float* res,
-                      float* y, float* mean, float* istd, long rows, int c, int relu, float eps,
-                      void* workspace, hipStream_t st) {
-  if (!x || !gamma || !beta || !y || !mean || !istd || !workspace) return hipErrorInvalidValue;
-  if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+namespace {
+
+template <class T>
+hipError_t bn_forward_t(const T* x, const float* gamma, const float* beta, const T* res, T* y, float* mean,
+                        float* istd, long rows, int c, int relu, float eps, void* workspace, hipStream_t st) {
   double* part = static_cast<double*>(workspace);
   float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
   const ReduceShape rs = reduce_shape(c);
   const int slabs = slab_count(rows, rs);
-  hipLaunchKernelGGL(bn_reduce_kernel<0>, dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, nullptr,
-                     nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
+  hipLaunchKernelGGL((bn_reduce_kernel<0, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, (const T*)nullptr,
+                     (const T*)nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
   hipLaunchKernelGGL(bn_fwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
                      gamma, beta, mean, istd, coef, rows, c, eps, slabs);
   const size_t n4 = (size_t)rows * c / 4;
-  hipLaunchKernelGGL(bn_apply_kernel, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, res, coef, y, n4, c,
-                     relu);
+  hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, res, coef, y, n4, c, relu);
   return hipGetLastError();
 }
 
-hipError_t bn_backward(const float* x, const float* dy, const float* y, const float* gamma,
-                       const float* mean, const float* istd, float* dx, float* dgamma, float* dbeta,
-                       float* g_out, long rows, int c, void* workspace, hipStream_t st) {
-  if (!x || !dy || !gamma || !mean || !istd || !dx || !dgamma || !dbeta || !workspace)
-    return hipErrorInvalidValue;
-  if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+template <class T>
+hipError_t bn_backward_t(const T* x, const T* dy, const T* y, const float* gamma, const float* mean,
+                         const float* istd, T* dx, float* dgamma, float* dbeta, T* g_out, long rows, int c,
+                         void* workspace, hipStream_t st) {
   double* part = static_cast<double*>(workspace);
   float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
   const ReduceShape rs = reduce_shape(c);
   const int slabs = slab_count(rows, rs);
-  hipLaunchKernelGGL(bn_reduce_kernel<1>, dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
+  hipLaunchKernelGGL((bn_reduce_kernel<1, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
                      istd, part, rows, c, rs.tpr, rs.rpi, slabs);
   hipLaunchKernelGGL(bn_bwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
                      gamma, istd, dgamma, dbeta, coef, rows, c, slabs);
   const size_t n4 = (size_t)rows * c / 4;
-  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, dy, y, mean, istd,
+  hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, dy, y, mean, istd,
                      coef, dx, g_out, n4, c);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t bn_forward(const void* x, const float* gamma, const float* beta, const void* res, void* y,
+                      float* mean, float* istd, long rows, int c, int relu, float eps, void* workspace,
+                      int dtype, hipStream_t st) {
+  if (!x || !gamma || !beta || !y || !mean || !istd || !workspace) return hipErrorInvalidValue;
+  if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  if (dtype == DT_F32)
+    return bn_forward_t((const float*)x, gamma, beta, (const float*)res, (float*)y, mean, istd, rows, c, relu, eps,
+                        workspace, st);
+  if (dtype == DT_BF16)
+    return bn_forward_t((const bf16_t*)x, gamma, beta, (const bf16_t*)res, (bf16_t*)y, mean, istd, rows, c, relu,
+                        eps, workspace, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t bn_backward(const void* x, const void* dy, const void* y, const float* gamma, const float* mean,
+                       const float* istd, void* dx, float* dgamma, float* dbeta, void* g_out, long rows, int c,
+                       void* workspace, int dtype, hipStream_t st) {
+  if (!x || !dy || !gamma || !mean || !istd || !dx || !dgamma || !dbeta || !workspace)
+    return hipErrorInvalidValue;
+  if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  if (dtype == DT_F32)
+    return bn_backward_t((const float*)x, (const float*)dy, (const float*)y, gamma, mean, istd, (float*)dx, dgamma,
+                         dbeta, (float*)g_out, rows, c, workspace, st);
+  if (dtype == DT_BF16)
+    return bn_backward_t((const bf16_t*)x, (const bf16_t*)dy, (const bf16_t*)y, gamma, mean, istd, (bf16_t*)dx,
+                         dgamma, dbeta, (bf16_t*)g_out, rows, c, workspace, st);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace acc

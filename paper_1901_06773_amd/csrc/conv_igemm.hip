@@ -17,6 +17,7 @@
 // 40 / 61 / 82): with M a multiple of 49 the larger tiles quantise badly over 256 CUs,
 // and four resident workgroups per CU hide the one barrier per chunk.
 #include "kernels.h"
+#include "dtype.h"
 
 namespace acc {
 namespace {
@@ -24,9 +25,21 @@ namespace {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));   // native vector: staging stays in registers
 
-constexpr int BK = 32;
-constexpr int LD = BK + 4;
+// A K-chunk is 128 bytes of a GEMM row: 32 fp32 or 64 bf16 elements.  The loaders and the
+// LDS layout work on bytes and are the same for both; only the matrix instruction differs
+// (16 x v_mfma_f32_32x32x2_f32 or 4 x v_mfma_f32_32x32x16_bf16 per chunk and wave).
+constexpr int CHUNK_BYTES = 128;
+constexpr int LD = CHUNK_BYTES / 4 + 4;      // LDS row pitch in 4-byte words (16 bytes of padding)
 constexpr int BM = 64, BN = 64;
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ v16f mfma32x32x16bf(const float4& a, const float4& b, v16f c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+#else
+  return c;  // the host pass never runs this
+#endif
+}
 
 __device__ __forceinline__ v16f mfma32x32x2(float a, float b, v16f c) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -73,11 +86,14 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
   return ((size_t)(img * g.out_h + p * g.out_stride) * g.out_w + q * g.out_stride) * g.n_out;
 }
 
-// FAST: c % 32 == 0, NHWC input, at most 32 filter taps.  Otherwise every element is
-// decoded on its own (any c, K tail); used for the 3-channel stem and for tiny layers.
-template <bool FAST>
+// FAST: c a multiple of the chunk (32 fp32 / 64 bf16 channels), NHWC input, at most 32 filter
+// taps.  Otherwise every element is decoded on its own (any c, K tail); used for the
+// 3-channel stem and for tiny layers.
+template <bool FAST, class T>
 __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
                                                      int main_grid) {
+  constexpr int ES = sizeof(T);
+  constexpr int BK = CHUNK_BYTES / ES;       // elements of K per chunk
   __shared__ __attribute__((aligned(16))) float As[2 * BM * LD];
   __shared__ __attribute__((aligned(16))) float Bs[2 * BN * LD];
 
@@ -143,10 +159,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
         af[nx] = *reinterpret_cast<const float4*>(as + (g8 + 1) * 8);
         bf[nx] = *reinterpret_cast<const float4*>(bs + (g8 + 1) * 8);
       }
-      acc = mfma32x32x2(af[c].x, bf[c].x, acc);
-      acc = mfma32x32x2(af[c].y, bf[c].y, acc);
-      acc = mfma32x32x2(af[c].z, bf[c].z, acc);
-      acc = mfma32x32x2(af[c].w, bf[c].w, acc);
+      if constexpr (ES == 4) {
+        acc = mfma32x32x2(af[c].x, bf[c].x, acc);
+        acc = mfma32x32x2(af[c].y, bf[c].y, acc);
+        acc = mfma32x32x2(af[c].z, bf[c].z, acc);
+        acc = mfma32x32x2(af[c].w, bf[c].w, acc);
+      } else {
+        acc = mfma32x32x16bf(af[c], bf[c], acc);   // 16 bytes per lane = 8 bf16 of K
+      }
     }
   };
   auto compute_chunk = [&](int cur) {
@@ -233,7 +253,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
       const RowPos rp = decode_row(g, m0 + row0 + 32 * i, M);
-      a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * 4) + col4 * 16;
+      a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * ES) + col4 * 16;
       uint32_t mask = 0;
       for (int kr = 0; kr < g.r; ++kr)
         for (int kt = 0; kt < g.s; ++kt) {
@@ -245,12 +265,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int n = n0 + row0 + 32 * i;
-      b_voff[i] = (uint32_t)(n < g.n_out ? n : 0) * (uint32_t)(K * 4) + col4 * 16;
+      b_voff[i] = (uint32_t)(n < g.n_out ? n : 0) * (uint32_t)(K * ES) + col4 * 16;
     }
     struct RegsA { v4f v[AI]; } ra0, ra1;        // two register sets
     struct RegsB { v4f v[BI]; } rb0, rb1;
     int kr = 0, kt = 0, c0 = 0;  // tap and channel offset of the chunk being loaded (uniform)
-    const uint32_t first_pixel = (uint32_t)margin * (uint32_t)(g.c * 4) + col4 * 16;   // always exists
+    const uint32_t first_pixel = (uint32_t)margin * (uint32_t)(g.c * ES) + col4 * 16;   // always exists
 
     // Loads are unconditional so that the number of loads in flight is known statically
     // (only then can the store of chunk kc+1 wait for its own loads and leave those of
@@ -260,9 +280,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     auto load_chunk = [&](RegsA& ra, RegsB& rb, int& set_tap, int kc) {
       const int tap = kr * g.s + kt;
       set_tap = tap;
-      const char* abase = reinterpret_cast<const char*>(g.in) + ((long)c0 - (long)margin * g.c) * 4;
-      const uint32_t tap_off = (uint32_t)(kr * g.wd + kt) * (uint32_t)(g.c * 4);
-      const char* bbase = reinterpret_cast<const char*>(g.w) + (long)kc * (BK * 4);
+      const char* abase = reinterpret_cast<const char*>(g.in) + ((long)c0 - (long)margin * g.c) * ES;
+      const uint32_t tap_off = (uint32_t)(kr * g.wd + kt) * (uint32_t)(g.c * ES);
+      const char* bbase = reinterpret_cast<const char*>(g.w) + (long)kc * CHUNK_BYTES;
 #pragma unroll
       for (int i = 0; i < AI; ++i) {
         const uint32_t off = ((a_mask[i] >> tap) & 1u) ? a_voff[i] + tap_off : first_pixel;
@@ -292,14 +312,20 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 
     main_loop(load_chunk, store_chunk, ra0, rb0, ra1, rb1);
   } else {
-    // one element per load: thread -> k column tid%32, rows tid/32 + 8*i
-    constexpr int AI = BM / 8, BI = BN / 8;
-    const int kcol = tid & 31, row0 = tid >> 5;
+    // one element per load: thread -> k column tid % BK, rows tid / BK + RP * i
+    constexpr int RP = 256 / BK;                 // rows per pass
+    constexpr int AI = BM / RP, BI = BN / RP;
+    constexpr int LDE = LD * 4 / ES;             // LDS row pitch in elements
+    const int kcol = tid & (BK - 1), row0 = tid / BK;
+    const T* in = static_cast<const T*>(g.in);
+    const T* wp = static_cast<const T*>(g.w);
+    T* AsE = reinterpret_cast<T*>(As);
+    T* BsE = reinterpret_cast<T*>(Bs);
     RowPos rp[AI];
 #pragma unroll
-    for (int i = 0; i < AI; ++i) rp[i] = decode_row(g, m0 + row0 + 8 * i, M);
-    struct RegsA { float v[AI]; } ra0, ra1;
-    struct RegsB { float v[BI]; } rb0, rb1;
+    for (int i = 0; i < AI; ++i) rp[i] = decode_row(g, m0 + row0 + RP * i, M);
+    struct RegsA { T v[AI]; } ra0, ra1;
+    struct RegsB { T v[BI]; } rb0, rb1;
     auto load_chunk = [&](RegsA& ra, RegsB& rb, int&, int kc) {
       const int k = kc * BK + kcol;
       const bool kok = k < K;
@@ -310,19 +336,19 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       for (int i = 0; i < AI; ++i) {
         const int iy = rp[i].iy0 + kr, ix = rp[i].ix0 + kt;
         const bool ok = kok && rp[i].ok && (unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd;
-        ra.v[i] = ok ? g.in[(size_t)(rp[i].pix + iy * g.wd + ix) * g.c + c] : 0.f;
+        ra.v[i] = ok ? in[(size_t)(rp[i].pix + iy * g.wd + ix) * g.c + c] : T(0);
       }
 #pragma unroll
       for (int i = 0; i < BI; ++i) {
-        const int n = n0 + row0 + 8 * i;
-        rb.v[i] = (kok && n < g.n_out) ? g.w[(size_t)n * K + k] : 0.f;
+        const int n = n0 + row0 + RP * i;
+        rb.v[i] = (kok && n < g.n_out) ? wp[(size_t)n * K + k] : T(0);
       }
     };
     auto store_chunk = [&](const RegsA& ra, const RegsB& rb, int, int buf) {
 #pragma unroll
-      for (int i = 0; i < AI; ++i) As[buf * (BM * LD) + (row0 + 8 * i) * LD + kcol] = ra.v[i];
+      for (int i = 0; i < AI; ++i) AsE[buf * (BM * LDE) + (row0 + RP * i) * LDE + kcol] = ra.v[i];
 #pragma unroll
-      for (int i = 0; i < BI; ++i) Bs[buf * (BN * LD) + (row0 + 8 * i) * LD + kcol] = rb.v[i];
+      for (int i = 0; i < BI; ++i) BsE[buf * (BN * LDE) + (row0 + RP * i) * LDE + kcol] = rb.v[i];
     };
     main_loop(load_chunk, store_chunk, ra0, rb0, ra1, rb1);
   }
@@ -335,14 +361,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   for (int v = 0; v < 16; ++v) {
     const int m = m0 + wm0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
     if (m >= M) continue;
-    const size_t o = out_row_offset(g, m) + n;
+    T* o = static_cast<T*>(g.out) + out_row_offset(g, m) + n;
     float val = acc[v];
-    if (g.accumulate) val += g.out[o];
-    g.out[o] = val;
+    if (g.accumulate) val += Elem<T>::load(o);
+    Elem<T>::store(o, val);
   }
 }
 
-template <bool FAST>
+template <bool FAST, class T>
 hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchProbe* probe) {
   const int tm = (M + BM - 1) / BM, tn = (g.n_out + BN - 1) / BN;
   const long tiles = (long)tm * tn;
@@ -355,7 +381,7 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   }
   if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
   if (probe->before) (void)hipEventRecord(probe->before, st);
-  hipLaunchKernelGGL((igemm_kernel<FAST>), dim3((unsigned)(main_grid + side_blocks)), dim3(256), 0, st, g, M, K, tn,
+  hipLaunchKernelGGL((igemm_kernel<FAST, T>), dim3((unsigned)(main_grid + side_blocks)), dim3(256), 0, st, g, M, K, tn,
                      (int)tiles, main_grid);
   if (probe->after) (void)hipEventRecord(probe->after, st);
   return hipGetLastError();
@@ -384,14 +410,18 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   const long K = (long)g.r * g.s * g.c;
   if (M >= (1L << 31) || K >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31))
     return hipErrorInvalidValue;
-  // The fast loader needs 32-channel chunks, at most 32 filter taps (one validity bit
-  // each) and every per-lane byte offset below 2^32.  The choice depends on the shape
-  // only, never on addresses or on the swap plan.
-  const bool fast = (g.c % BK == 0) && g.r * g.s <= 32 &&
-                    ((long)g.n_img * g.h * g.wd + 2L * g.pad * (g.wd + 1)) * g.c * 4 < (1L << 32) &&
-                    (long)g.n_out * K * 4 < (1L << 32);
+  // The fast loader needs whole 128-byte chunks of channels (32 fp32 / 64 bf16), at most 32
+  // filter taps (one validity bit each) and every per-lane byte offset below 2^32.  The
+  // choice depends on the shape only, never on addresses or on the swap plan.
+  if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
+  const long es = (long)dt_size(g.dtype);
+  const bool fast = (g.c % (CHUNK_BYTES / es) == 0) && g.r * g.s <= 32 &&
+                    ((long)g.n_img * g.h * g.wd + 2L * g.pad * (g.wd + 1)) * g.c * es < (1L << 32) &&
+                    (long)g.n_out * K * es < (1L << 32);
   probe->variant = fast ? V_IGEMM_FAST : V_IGEMM_GENERIC;
-  return fast ? launch<true>(g, (int)M, (int)K, st, probe) : launch<false>(g, (int)M, (int)K, st, probe);
+  if (g.dtype == DT_F32)
+    return fast ? launch<true, float>(g, (int)M, (int)K, st, probe) : launch<false, float>(g, (int)M, (int)K, st, probe);
+  return fast ? launch<true, bf16_t>(g, (int)M, (int)K, st, probe) : launch<false, bf16_t>(g, (int)M, (int)K, st, probe);
 }
 
 }  // namespace acc

@@ -15,12 +15,30 @@
 // 64x64 tiles measured best on MI355X (ResNet shapes, minibatch 32 / 256: 66 / 91
 // TFLOP/s against 48 / 86 with 128-wide tiles).
 #include "kernels.h"
+#include "dtype.h"
 
 namespace acc {
 namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+// four consecutive elements as they come from memory, and as the fp32 values the MFMA takes
+// (bf16 operands are widened on the way into LDS: their products are exact in fp32, so the
+// result is that of a bf16 product accumulated in fp32)
+template <class T> struct Quad;
+template <> struct Quad<float> {
+  typedef v4f raw;
+  static __device__ __forceinline__ v4f widen(const raw& r) { return r; }
+};
+template <> struct Quad<bf16_t> {
+  typedef v2u raw;
+  static __device__ __forceinline__ v4f widen(const raw& r) {
+    return v4f{__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u), __uint_as_float(r.y << 16),
+               __uint_as_float(r.y & 0xffff0000u)};
+  }
+};
 constexpr int BKM = 32;          // rows of m per chunk
 constexpr int BM = 64, BN = 64;  // tile of dw: output channels x filter columns
 constexpr int LDT = 64 + 32;     // LDS pitch: lanes 32-63 read the next row on other banks
@@ -53,7 +71,7 @@ __device__ __forceinline__ int gather_pixel(const WgradGeom& g, int m, int kr, i
 
 // FAST: cin % 64 == 0 (a tile's columns lie inside one tap), cout % 4 == 0, byte offsets
 // below 2^32.
-template <bool FAST>
+template <bool FAST, class T>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int J, int tiles_j, int tiles,
                                                      int splits, int chunks_per_split, float* out,
                                                      size_t split_stride, int main_grid) {
@@ -68,16 +86,18 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
     const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
     const int kr = g.r - 1 - tap / g.s, kt = g.s - 1 - tap % g.s;
     const int src_tap = kr * g.s + kt;
-    float (*tile)[33] = reinterpret_cast<float (*)[33]>(As);
+    T (*tile)[33] = reinterpret_cast<T (*)[33]>(As);
+    const T* fw = static_cast<const T*>(g.flip_w);
+    T* fwt = static_cast<T*>(g.flip_wt);
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int i = ty; i < 32; i += 8) {
       const int co = co0f + i, ci = ci0f + tx;
-      tile[i][tx] = (co < g.cout && ci < g.cin) ? g.flip_w[((size_t)co * g.r * g.s + src_tap) * g.cin + ci] : 0.f;
+      tile[i][tx] = (co < g.cout && ci < g.cin) ? fw[((size_t)co * g.r * g.s + src_tap) * g.cin + ci] : T(0);
     }
     __syncthreads();
     for (int i = ty; i < 32; i += 8) {
       const int ci = ci0f + i, co = co0f + tx;
-      if (ci < g.cin && co < g.cout) g.flip_wt[((size_t)ci * g.r * g.s + tap) * g.cout + co] = tile[tx][i];
+      if (ci < g.cin && co < g.cout) fwt[((size_t)ci * g.r * g.s + tap) * g.cout + co] = tile[tx][i];
     }
     return;
   }
@@ -186,10 +206,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
     const int kr = tap / g.s, kt = tap - kr * g.s;
     const bool direct = g.r == 1 && g.s == 1 && g.stride == 1 && g.pad == 0;
     const bool a_col_ok = co0 + col4 * 4 < g.cout;
-    const uint32_t a_lane = (uint32_t)(a_col_ok ? co0 + col4 * 4 : 0) * 4;
-    const uint32_t b_lane = (uint32_t)(ci0 + col4 * 4) * 4;
+    constexpr int ES = sizeof(T);
+    typedef typename Quad<T>::raw raw;
+    const uint32_t a_lane = (uint32_t)(a_col_ok ? co0 + col4 * 4 : 0) * ES;
+    const uint32_t b_lane = (uint32_t)(ci0 + col4 * 4) * ES;
     struct Regs {
-      v4f a[2], b[2];
+      raw a[2], b[2];
       uint32_t ok;   // bit i: a[i] valid, bit 2+i: b[i] valid
     } r0, r1;
     // position of each gathered row; chunks are visited in order, so the position advances
@@ -219,7 +241,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
         const bool mok = m < Mrows;
         const uint32_t mm = mok ? (uint32_t)m : 0u;
         ok |= (mok && a_col_ok ? 1u : 0u) << i;
-        r.a[i] = *reinterpret_cast<const v4f*>(abase + (mm * (uint32_t)(g.cout * 4) + a_lane));
+        r.a[i] = *reinterpret_cast<const raw*>(abase + (mm * (uint32_t)(g.cout * ES) + a_lane));
         int pix = (int)mm;
         if (!direct) {
           const int iy = r_p[i] * g.stride + kr - g.pad, ix = r_q[i] * g.stride + kt - g.pad;
@@ -232,7 +254,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
         }
         const bool bok = mok && pix >= 0;
         ok |= (bok ? 1u : 0u) << (2 + i);
-        r.b[i] = *reinterpret_cast<const v4f*>(bbase + ((uint32_t)(bok ? pix : 0) * (uint32_t)(g.cin * 4) + b_lane));
+        r.b[i] = *reinterpret_cast<const raw*>(bbase + ((uint32_t)(bok ? pix : 0) * (uint32_t)(g.cin * ES) + b_lane));
       }
       r.ok = ok;
     };
@@ -241,7 +263,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
       float* bs = Bs + buf * (BKM * LDT);
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        v4f a = r.a[i], b = r.b[i];
+        v4f a = Quad<T>::widen(r.a[i]), b = Quad<T>::widen(r.b[i]);
         if (!((r.ok >> i) & 1u)) a = v4f{0.f, 0.f, 0.f, 0.f};
         if (!((r.ok >> (2 + i)) & 1u)) b = v4f{0.f, 0.f, 0.f, 0.f};
         *reinterpret_cast<v4f*>(&as[(row + 16 * i) * LDT + col4 * 4]) = a;
@@ -265,11 +287,11 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
       for (int i = 0; i < AI; ++i) {
         const int m = (chunk_lo + kc) * BKM + row0 + 4 * i;
         const bool mok = m < Mrows;
-        r.a[i] = (mok && co < g.cout) ? g.dy[(size_t)m * g.cout + co] : 0.f;
+        r.a[i] = (mok && co < g.cout) ? Elem<T>::load(static_cast<const T*>(g.dy) + (size_t)m * g.cout + co) : 0.f;
         float v = 0.f;
         if (mok && jok) {
           const int pix = gather_pixel(g, m, kr, kt);
-          if (pix >= 0) v = g.x[(size_t)pix * g.cin + ci];
+          if (pix >= 0) v = Elem<T>::load(static_cast<const T*>(g.x) + (size_t)pix * g.cin + ci);
         }
         r.b[i] = v;
       }
@@ -370,8 +392,10 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   if (c.splits > 1 && !g.workspace) return hipErrorInvalidValue;
   const long work = (long)c.tiles_co * c.tiles_j * c.splits;
   if (work > (1L << 30)) return hipErrorInvalidValue;
-  const bool fast = (g.cout % 4 == 0) && (g.cin % 64 == 0) && Mrows * g.cout * 4 < (1L << 32) &&
-                    (long)g.n_img * g.h * g.wd * g.cin * 4 < (1L << 32);
+  if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
+  const long es = (long)dt_size(g.dtype);
+  const bool fast = (g.cout % 4 == 0) && (g.cin % 64 == 0) && Mrows * g.cout * es < (1L << 32) &&
+                    (long)g.n_img * g.h * g.wd * g.cin * es < (1L << 32);
   float* out = c.splits > 1 ? g.workspace : g.dw;
   const size_t count = (size_t)g.cout * J;
   const int main_grid = (int)((work + 7) / 8 * 8);
@@ -380,12 +404,15 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   const dim3 grid((unsigned)(main_grid + flip_blocks));
   const int tiles = c.tiles_co * c.tiles_j;
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
-  if (fast)
-    hipLaunchKernelGGL((wgrad_kernel<true>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j,
-                       tiles, c.splits, c.chunks_per_split, out, count, main_grid);
-  else
-    hipLaunchKernelGGL((wgrad_kernel<false>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j,
-                       tiles, c.splits, c.chunks_per_split, out, count, main_grid);
+#define ACC_WGRAD_LAUNCH(F, T)                                                                             \
+  hipLaunchKernelGGL((wgrad_kernel<F, T>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j, tiles, \
+                     c.splits, c.chunks_per_split, out, count, main_grid)
+  if (g.dtype == DT_F32) {
+    if (fast) ACC_WGRAD_LAUNCH(true, float); else ACC_WGRAD_LAUNCH(false, float);
+  } else {
+    if (fast) ACC_WGRAD_LAUNCH(true, bf16_t); else ACC_WGRAD_LAUNCH(false, bf16_t);
+  }
+#undef ACC_WGRAD_LAUNCH
   if (probe && probe->after) (void)hipEventRecord(probe->after, st);
   if (probe) probe->variant = fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
   hipError_t e = hipGetLastError();

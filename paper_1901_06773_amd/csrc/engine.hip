@@ -17,6 +17,7 @@
 #include "../../include/accudnn.h"
 #include "graph.h"
 #include "kernels.h"
+#include "dtype.h"
 #include <cmath>
 #include "plan.h"
 
@@ -41,6 +42,7 @@ struct acc_ctx {
   // static part of the pool
   float* d_params = nullptr;
   float* d_grads = nullptr;
+  uint16_t* d_params16 = nullptr;      // bf16 mode: the rounded copy of the weights the kernels read
   float* d_stats = nullptr;
   float* d_loss = nullptr;
   char* dyn = nullptr;
@@ -145,6 +147,12 @@ int param_io(acc_ctx* c, int layer, float* host, size_t n, bool to_device, bool 
     else std::memcpy(tmp.data(), host, n * sizeof(float));
     HIPCHK(c, hipMemcpyAsync(dev, tmp.data(), n * sizeof(float), hipMemcpyHostToDevice, c->s_c));
     HIPCHK(c, hipStreamSynchronize(c->s_c));
+    if (!grads && c->d_params16) {   // bf16 mode: the kernels read the rounded copy
+      std::vector<uint16_t> h16(n);
+      for (size_t i = 0; i < n; ++i) h16[i] = float_to_bf16(tmp[i]);
+      HIPCHK(c, hipMemcpyAsync(c->d_params16 + ps.offset, h16.data(), n * 2, hipMemcpyHostToDevice, c->s_c));
+      HIPCHK(c, hipStreamSynchronize(c->s_c));
+    }
   } else {
     HIPCHK(c, hipMemcpyAsync(tmp.data(), dev, n * sizeof(float), hipMemcpyDeviceToHost, c->s_c));
     HIPCHK(c, hipStreamSynchronize(c->s_c));
@@ -161,11 +169,11 @@ extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int i
                           const acc_resources* res, acc_ctx** out) {
   if (!out) { g_create_error = "out is null"; return ACC_EINVAL; }
   *out = nullptr;
-  if (dtype != ACC_F32) { g_create_error = "only fp32 is implemented"; return ACC_EINVAL; }
+  if (dtype != ACC_F32 && dtype != ACC_BF16) { g_create_error = "dtype must be ACC_F32 or ACC_BF16"; return ACC_EINVAL; }
   acc_ctx* c = new (std::nothrow) acc_ctx();
   if (!c) { g_create_error = "out of host memory"; return ACC_EHOSTMEM; }
   std::string err;
-  if (!c->g.build(layers, n_layers, in_c, in_h, in_w, &err)) {
+  if (!c->g.build(layers, n_layers, in_c, in_h, in_w, dtype, &err)) {
     g_create_error = err;
     delete c;
     return ACC_EINVAL;
@@ -197,6 +205,7 @@ extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int i
     const size_t pb = al256(c->g.param_elems * sizeof(float));
     c->d_params = (float*)p; p += pb;
     c->d_grads = (float*)p; p += pb;
+    if (dtype == ACC_BF16) { c->d_params16 = (uint16_t*)p; p += al256(c->g.param_elems * 2); }
     c->d_stats = (float*)p; p += al256(c->g.stat_elems * sizeof(float));
     c->d_loss = (float*)p; p += 256;
     c->dyn = p;
@@ -511,11 +520,16 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
   const Step& s = g.steps[j];
   const int k = c->plan.k;
   auto ptr = [&](int t) -> float* { return t < 0 ? nullptr : (float*)(c->dyn + c->cur_off[t]); };
+  const int dt = g.dtype;
+  const size_t es = dt_size(dt);
   auto T = [&](int t) -> const Tensor& { return g.tensors[t]; };
   hipStream_t st = c->s_c;
   const acc_layer* l = s.layer >= 0 ? &g.layers[s.layer] : nullptr;
   float* w = s.layer >= 0 ? c->d_params + g.params[s.layer].offset : nullptr;
   float* dw = s.layer >= 0 ? c->d_grads + g.params[s.layer].offset : nullptr;
+  // the filter copy the convolution kernels read: the fp32 weights themselves, or their bf16 copy
+  const void* wk = s.layer < 0 ? nullptr
+                   : dt == ACC_BF16 ? (const void*)(c->d_params16 + g.params[s.layer].offset) : (const void*)w;
   auto igemm = [&](const ConvGeom& cg, double flops) {
     LaunchProbe lp;
     LaunchProbe* pp = c->next_probe(&lp, flops);
@@ -534,10 +548,10 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
   const double conv_flops = s.flops_per_image * k / (s.phase == 1 && s.dx >= 0 ? 2.0 : 1.0);
   switch (s.kind) {
     case K_INPUT_F:
-      return nchw_to_nhwc(ptr(s.x), ptr(s.y), k, g.in_c, g.in_h * g.in_w, st);
+      return nchw_to_nhwc(ptr(s.x), ptr(s.y), k, g.in_c, g.in_h * g.in_w, dt, st);
     case K_CONV_F: {
       ConvGeom cg{};
-      cg.in = ptr(s.x); cg.w = w; cg.out = ptr(s.y);
+      cg.in = ptr(s.x); cg.w = wk; cg.out = ptr(s.y); cg.dtype = dt;
       cg.n_img = k; cg.h = T(s.x).h; cg.wd = T(s.x).w; cg.c = l->cin;
       cg.p = T(s.y).h; cg.q = T(s.y).w; cg.n_out = l->cout;
       cg.r = l->r; cg.s = l->s; cg.stride = l->stride; cg.pad = l->pad;
@@ -547,72 +561,72 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
     case K_BN_F: {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
       return bn_forward(ptr(s.x), w, w + l->cin, ptr(s.res), ptr(s.y), stat, stat + l->cin,
-                        (long)k * T(s.x).h * T(s.x).w, l->cin, s.relu, 1e-5f, ptr(s.ws), st);
+                        (long)k * T(s.x).h * T(s.x).w, l->cin, s.relu, 1e-5f, ptr(s.ws), dt, st);
     }
     case K_MAXPOOL_F:
-      return maxpool_forward(ptr(s.x), ptr(s.y), k, T(s.x).h, T(s.x).w, T(s.x).c, l->r, l->s, l->stride, l->pad, st);
+      return maxpool_forward(ptr(s.x), ptr(s.y), k, T(s.x).h, T(s.x).w, T(s.x).c, l->r, l->s, l->stride, l->pad, dt, st);
     case K_GAP_F:
-      return gap_forward(ptr(s.x), ptr(s.y), k, T(s.x).h * T(s.x).w, T(s.x).c, st);
+      return gap_forward(ptr(s.x), ptr(s.y), k, T(s.x).h * T(s.x).w, T(s.x).c, dt, st);
     case K_FC_F: {
       ConvGeom cg{};
-      cg.in = ptr(s.x); cg.w = w; cg.out = ptr(s.y);
+      cg.in = ptr(s.x); cg.w = wk; cg.out = ptr(s.y); cg.dtype = dt;
       cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cin; cg.p = 1; cg.q = 1; cg.n_out = l->cout;
       cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
       hipError_t e = igemm(cg, conv_flops);
       if (e != hipSuccess) return e;
-      return bias_add(ptr(s.y), w + (size_t)l->cout * l->cin, k, l->cout, st);
+      return bias_add(ptr(s.y), w + (size_t)l->cout * l->cin, k, l->cout, dt, st);
     }
     case K_LOSS_F:
-      return softmax_ce_forward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.ws), c->d_loss, k, g.classes, st);
+      return softmax_ce_forward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.ws), c->d_loss, k, g.classes, dt, st);
     case K_LOSS_B:
-      return softmax_ce_backward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.dx), k, g.classes, st);
+      return softmax_ce_backward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.dx), k, g.classes, dt, st);
     case K_FC_B: {
       WgradGeom wg{};
-      wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw;
+      wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw; wg.dtype = dt;
       wg.n_img = k; wg.h = 1; wg.wd = 1; wg.cin = l->cin; wg.p = 1; wg.q = 1; wg.cout = l->cout;
       wg.r = 1; wg.s = 1; wg.stride = 1; wg.pad = 0; wg.workspace = ptr(s.ws2);
       // the transposed filter for the data gradient is written by extra workgroups of the
       // weight-gradient launch; the parts of the weight gradient are added up by extra
       // workgroups of the data-gradient launch
-      wg.flip_w = w; wg.flip_wt = ptr(s.ws);
+      wg.flip_w = wk; wg.flip_wt = ptr(s.ws);
       ReduceJob job;
       hipError_t e = wgrad(wg, conv_flops, &job);
       if (e != hipSuccess) return e;
-      e = column_sum(ptr(s.dy), dw + (size_t)l->cout * l->cin, k, l->cout, st);
+      e = column_sum(ptr(s.dy), dw + (size_t)l->cout * l->cin, k, l->cout, dt, st);
       if (e != hipSuccess) return e;
       ConvGeom cg{};
       cg.side = job;
-      cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx);
+      cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx); cg.dtype = dt;
       cg.n_img = k; cg.h = 1; cg.wd = 1; cg.c = l->cout; cg.p = 1; cg.q = 1; cg.n_out = l->cin;
       cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
       cg.accumulate = s.dx_accumulate;
       return igemm(cg, conv_flops);
     }
     case K_GAP_B:
-      return gap_backward(ptr(s.dy), ptr(s.dx), k, T(s.dx).h * T(s.dx).w, T(s.dx).c, s.dx_accumulate, st);
+      return gap_backward(ptr(s.dy), ptr(s.dx), k, T(s.dx).h * T(s.dx).w, T(s.dx).c, s.dx_accumulate, dt, st);
     case K_MAXPOOL_B:
       return maxpool_backward(ptr(s.x), ptr(s.dy), ptr(s.dx), k, T(s.x).h, T(s.x).w, T(s.x).c, l->r, l->s,
-                              l->stride, l->pad, s.dx_accumulate, st);
+                              l->stride, l->pad, s.dx_accumulate, dt, st);
     case K_BN_B: {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
       return bn_backward(ptr(s.x), ptr(s.dy), ptr(s.y), w, stat, stat + l->cin, ptr(s.dx), dw, dw + l->cin,
-                         s.g_inplace ? ptr(s.dy) : nullptr, (long)k * T(s.x).h * T(s.x).w, l->cin, ptr(s.ws), st);
+                         s.g_inplace ? ptr(s.dy) : nullptr, (long)k * T(s.x).h * T(s.x).w, l->cin, ptr(s.ws), dt, st);
     }
     case K_CONV_B: {
       const int h = T(s.x).h, wd = T(s.x).w, ho = T(s.dy).h, wo = T(s.dy).w;
       WgradGeom wg{};
-      wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw;
+      wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw; wg.dtype = dt;
       wg.n_img = k; wg.h = h; wg.wd = wd; wg.cin = l->cin; wg.p = ho; wg.q = wo; wg.cout = l->cout;
       wg.r = l->r; wg.s = l->s; wg.stride = l->stride; wg.pad = l->pad;
       wg.workspace = ptr(s.ws2);
       if (s.dx < 0) return wgrad(wg, conv_flops, nullptr);   // first layer: no data gradient
-      wg.flip_w = w; wg.flip_wt = ptr(s.ws);                 // side jobs as in the fc step
+      wg.flip_w = wk; wg.flip_wt = ptr(s.ws);                // side jobs as in the fc step
       ReduceJob job;
       hipError_t e = wgrad(wg, conv_flops, &job);
       if (e != hipSuccess) return e;
       ConvGeom cg{};
       cg.side = job;
-      cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx);
+      cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx); cg.dtype = dt;
       cg.n_img = k; cg.h = ho; cg.wd = wo; cg.c = l->cout; cg.n_out = l->cin;
       cg.r = l->r; cg.s = l->s; cg.stride = 1; cg.accumulate = s.dx_accumulate;
       cg.out_h = h; cg.out_w = wd;
@@ -621,14 +635,14 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       } else {  // 1x1, pad 0: dense product on the strided positions, zeros elsewhere
         cg.p = ho; cg.q = wo; cg.pad = 0; cg.out_stride = l->stride;
         if (!s.dx_accumulate) {
-          e = fill_zero(ptr(s.dx), (size_t)k * h * wd * l->cin, st);
+          e = fill_zero(ptr(s.dx), (size_t)k * h * wd * l->cin * es / 4, st);   // whole words: cin is even
           if (e != hipSuccess) return e;
         }
       }
       return igemm(cg, conv_flops);
     }
     case K_SGD:
-      return sgd_update(c->d_params, c->d_grads, lr, g.param_elems, st);
+      return sgd_update(c->d_params, c->d_grads, lr, g.param_elems, c->d_params16, st);
   }
   return hipErrorInvalidValue;
 }

@@ -58,11 +58,15 @@ size_t Graph::bytes(int t, int k) const {
 
 size_t Graph::static_bytes() const {
   auto al = [](size_t b) { return (b + 255) & ~(size_t)255; };
-  return 2 * al(param_elems * sizeof(float)) + al(stat_elems * sizeof(float)) + 256;
+  // weights, gradients (fp32), in bf16 mode the rounded copy of the weights, statistics, loss
+  return 2 * al(param_elems * sizeof(float)) + (dtype == ACC_BF16 ? al(param_elems * 2) : 0) +
+         al(stat_elems * sizeof(float)) + 256;
 }
 
-bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::string* err) {
+bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, std::string* err) {
   *this = Graph();
+  dtype = dt;
+  const size_t es = dt == ACC_BF16 ? 2 : 4;   // bytes per stored activation element
   if (!recs || n <= 0 || ic <= 0 || ih <= 0 || iw <= 0) { *err = "empty network or input"; return false; }
   layers.assign(recs, recs + n);
   in_c = ic; in_h = ih; in_w = iw;
@@ -150,11 +154,11 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
   };
   auto new_act = [&](int layer) {
     return new_tensor(T_ACT, shape_c[layer], shape_h[layer], shape_w[layer],
-                      (size_t)shape_c[layer] * shape_h[layer] * shape_w[layer] * 4, 0, layer);
+                      (size_t)shape_c[layer] * shape_h[layer] * shape_w[layer] * es, 0, layer);
   };
   t_stage = new_tensor(T_INPUT, in_c, in_h, in_w, (size_t)in_c * in_h * in_w * 4, 0, -1);
   t_labels = new_tensor(T_INPUT, 1, 1, 1, 4, 0, -1);
-  t_image = new_tensor(T_ACT, in_c, in_h, in_w, (size_t)in_c * in_h * in_w * 4, 0, -1);
+  t_image = new_tensor(T_ACT, in_c, in_h, in_w, (size_t)in_c * in_h * in_w * es, 0, -1);
   auto act_in = [&](int id) { return id < 0 ? t_image : act_of_layer[id]; };
   auto elems = [&](int t) { return (double)tensors[t].c * tensors[t].h * tensors[t].w; };
 
@@ -163,7 +167,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
     Step s;
     s.kind = K_INPUT_F;
     s.x = t_stage; s.y = t_image;
-    s.bytes_per_image = 8.0 * in_c * in_h * in_w;
+    s.bytes_per_image = (4.0 + es) * in_c * in_h * in_w;
     s.reads = {t_stage};
     s.writes = {t_image};
     steps.push_back(s);
@@ -186,7 +190,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
         s.x_is_image = l.in0 < 0;
         s.y = act_of_layer[i] = new_act(i);
         s.flops_per_image = 2.0 * shape_h[i] * shape_w[i] * l.cout * l.cin * l.r * l.s;
-        s.bytes_per_image = 4.0 * (elems(s.x) + elems(s.y));
+        s.bytes_per_image = (double)es * (elems(s.x) + elems(s.y));
         s.bytes_fixed = 4.0 * params[i].count;
         break;
       }
@@ -210,7 +214,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
         s.y = new_act(out_layer);
         act_of_layer[out_layer] = s.y;
         s.ws = new_tensor(T_WORK, 0, 0, 0, 0, bn_workspace_bytes(l.cin), i);
-        s.bytes_per_image = 4.0 * elems(s.x) * (s.res >= 0 ? 4 : 3);
+        s.bytes_per_image = (double)es * elems(s.x) * (s.res >= 0 ? 4 : 3);
         break;
       }
       case ACC_RELU:
@@ -220,24 +224,24 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
       case ACC_MAXPOOL:
         s.kind = K_MAXPOOL_F;
         s.y = act_of_layer[i] = new_act(i);
-        s.bytes_per_image = 4.0 * (elems(s.x) + elems(s.y));
+        s.bytes_per_image = (double)es * (elems(s.x) + elems(s.y));
         break;
       case ACC_GAP:
         s.kind = K_GAP_F;
         s.y = act_of_layer[i] = new_act(i);
-        s.bytes_per_image = 4.0 * (elems(s.x) + elems(s.y));
+        s.bytes_per_image = (double)es * (elems(s.x) + elems(s.y));
         break;
       case ACC_FC:
         s.kind = K_FC_F;
         s.y = act_of_layer[i] = new_act(i);
         s.flops_per_image = 2.0 * l.cin * l.cout;
-        s.bytes_per_image = 4.0 * (elems(s.x) + elems(s.y));
+        s.bytes_per_image = (double)es * (elems(s.x) + elems(s.y));
         s.bytes_fixed = 4.0 * params[i].count;
         break;
       case ACC_SOFTMAX_CE:
         s.kind = K_LOSS_F;
         s.ws = new_tensor(T_WORK, 0, 0, 0, 4, 0, i);   // per-sample losses
-        s.bytes_per_image = 4.0 * elems(s.x);
+        s.bytes_per_image = (double)es * elems(s.x);
         break;
     }
     s.reads.push_back(s.x);
@@ -288,11 +292,11 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
       case K_FC_F:
         b.kind = K_FC_B;
         b.dx = grad_for_write(f.x, &b.dx_accumulate);
-        b.ws = new_tensor(T_WORK, 0, 0, 0, 0, (size_t)l.cin * l.cout * 4, f.layer);
+        b.ws = new_tensor(T_WORK, 0, 0, 0, 0, (size_t)l.cin * l.cout * es, f.layer);
         b.ws2 = new_tensor(T_WORK, 0, 0, 0, 0, 0, f.layer);
         tensors[b.ws2].wgrad_layer = f.layer;
         b.flops_per_image = 4.0 * l.cin * l.cout;
-        b.bytes_per_image = 4.0 * (2 * elems(f.x) + elems(f.y));
+        b.bytes_per_image = (double)es * (2 * elems(f.x) + elems(f.y));
         b.bytes_fixed = 12.0 * params[f.layer].count;
         b.reads = {f.x, b.dy};
         if (b.dx_accumulate) b.reads.push_back(b.dx);
@@ -304,7 +308,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
         b.reads = {b.dy};
         if (b.dx_accumulate) b.reads.push_back(b.dx);
         b.writes = {b.dx};
-        b.bytes_per_image = 4.0 * (elems(f.x) + elems(f.y));
+        b.bytes_per_image = (double)es * (elems(f.x) + elems(f.y));
         break;
       case K_MAXPOOL_F:
         b.kind = K_MAXPOOL_B;
@@ -312,7 +316,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
         b.reads = {f.x, b.dy};
         if (b.dx_accumulate) b.reads.push_back(b.dx);
         b.writes = {b.dx};
-        b.bytes_per_image = 4.0 * (2 * elems(f.x) + elems(f.y));
+        b.bytes_per_image = (double)es * (2 * elems(f.x) + elems(f.y));
         break;
       case K_BN_F: {
         b.kind = K_BN_B;
@@ -337,7 +341,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
           b.g_inplace = true;
           b.writes.push_back(b.dy);
         }
-        b.bytes_per_image = 4.0 * elems(f.x) * (2 * (f.relu ? 3 : 2) + 1 + (f.res >= 0 ? 1 : 0));
+        b.bytes_per_image = (double)es * elems(f.x) * (2 * (f.relu ? 3 : 2) + 1 + (f.res >= 0 ? 1 : 0));
         break;
       }
       case K_CONV_F: {
@@ -350,12 +354,12 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, std::str
             return false;
           }
           b.dx = grad_for_write(f.x, &b.dx_accumulate);
-          b.ws = new_tensor(T_WORK, 0, 0, 0, 0, params[f.layer].count * 4, f.layer);
+          b.ws = new_tensor(T_WORK, 0, 0, 0, 0, params[f.layer].count * es, f.layer);
         }
         b.ws2 = new_tensor(T_WORK, 0, 0, 0, 0, 0, f.layer);
         tensors[b.ws2].wgrad_layer = f.layer;
         b.flops_per_image = f.flops_per_image * (need_dx ? 2 : 1);
-        b.bytes_per_image = 4.0 * (elems(f.x) * (need_dx ? 2 : 1) + 2 * elems(f.y));
+        b.bytes_per_image = (double)es * (elems(f.x) * (need_dx ? 2 : 1) + 2 * elems(f.y));
         b.bytes_fixed = 4.0 * params[f.layer].count * (need_dx ? 4 : 1);
         b.reads = {f.x, b.dy};
         if (need_dx && b.dx_accumulate) b.reads.push_back(b.dx);

@@ -67,7 +67,8 @@ struct Graph {
   std::vector<int> act_of_layer;      // tensor holding a layer's output, -1 if fused away
 
   // Builds everything from the layer records; on failure returns false and sets err.
-  bool build(const acc_layer* recs, int n, int in_c, int in_h, int in_w, std::string* err);
+  int dtype = 0;                      // ACC_F32 / ACC_BF16: storage of activations and their gradients
+  bool build(const acc_layer* recs, int n, int in_c, int in_h, int in_w, int dtype, std::string* err);
   size_t static_bytes() const;        // params + grads + statistics + scalars, 256-aligned parts
   size_t bytes(int tensor, int k) const;   // 256-aligned size of a memory object at minibatch k
   void conv_dims(int layer, int* h, int* w, int* ho, int* wo) const;  // input / output size

@@ -1,6 +1,10 @@
 // Launchers of the gfx950 kernels.  Every launcher checks that its operand shapes
 // fit what the kernel and its grid assume and returns hipErrorInvalidValue otherwise;
-// nothing here allocates.  All activations NHWC fp32, filters O-H-W-I (K-contiguous rows).
+// nothing here allocates.  Activations NHWC, filters O-H-W-I (K-contiguous rows); `dtype`
+// (DT_F32 / DT_BF16 of dtype.h, the values of ACC_F32 / ACC_BF16) is the storage type of
+// activations, activation gradients and of the filter copy the kernels read; arithmetic is
+// fp32 (bf16 products on the matrix cores accumulate in fp32), weight gradients, batch-norm
+// parameters and statistics, biases and the loss are always fp32.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <cstddef>
@@ -22,9 +26,10 @@ struct ReduceJob {
 };
 
 struct ConvGeom {
-  const float* in;
-  const float* w;
-  float* out;
+  const void* in;           // dtype
+  const void* w;            // dtype
+  void* out;                // dtype
+  int dtype;
   int n_img, h, wd, c;      // input image size and channels
   int p, q;                 // rows enumerate n_img x p x q positions
   int n_out;                // GEMM N (output channels)
@@ -48,9 +53,10 @@ const char* conv_variant_name(int v);
 
 // dw[co][(r,t,ci)] = sum_{img,p,q} dy[img,p,q,co] * x[img, p*stride+r-pad, q*stride+t-pad, ci]
 struct WgradGeom {
-  const float* x;
-  const float* dy;
-  float* dw;
+  const void* x;            // dtype
+  const void* dy;           // dtype
+  float* dw;                // fp32
+  int dtype;
   int n_img, h, wd, cin;
   int p, q, cout;
   int r, s, stride, pad;
@@ -58,8 +64,8 @@ struct WgradGeom {
   // Optional side job: extra workgroups appended to the launch write the flipped and
   // transposed filter wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci] of this layer (the data
   // gradient that follows needs it).  Both null: no side job.
-  const float* flip_w;
-  float* flip_wt;
+  const void* flip_w;       // dtype
+  void* flip_wt;            // dtype
 };
 size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s);
 // If `deferred` is given and the gradient is split over the minibatch, the reduction of the
@@ -70,35 +76,37 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe = n
 hipError_t reduce_parts(const ReduceJob& job, hipStream_t st);
 
 // wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci]  (filter of the transposed convolution)
-hipError_t filter_flip_transpose(const float* w, float* wt, int cout, int cin, int r, int s,
+hipError_t filter_flip_transpose(const void* w, void* wt, int cout, int cin, int r, int s, int dtype,
                                  hipStream_t st);
 
 // Batch norm over rows x c (NHWC flattened).  workspace: bn_workspace_bytes(c).
+// x, res, y, dy, dx, g_out: dtype; gamma, beta, mean, istd, dgamma, dbeta: fp32.
 size_t bn_workspace_bytes(int c);
-hipError_t bn_forward(const float* x, const float* gamma, const float* beta, const float* res,
-                      float* y, float* mean, float* istd, long rows, int c, int relu, float eps,
-                      void* workspace, hipStream_t st);
-hipError_t bn_backward(const float* x, const float* dy, const float* y, const float* gamma,
-                       const float* mean, const float* istd, float* dx, float* dgamma, float* dbeta,
-                       float* g_out, long rows, int c, void* workspace, hipStream_t st);
+hipError_t bn_forward(const void* x, const float* gamma, const float* beta, const void* res,
+                      void* y, float* mean, float* istd, long rows, int c, int relu, float eps,
+                      void* workspace, int dtype, hipStream_t st);
+hipError_t bn_backward(const void* x, const void* dy, const void* y, const float* gamma,
+                       const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
+                       void* g_out, long rows, int c, void* workspace, int dtype, hipStream_t st);
 
-hipError_t maxpool_forward(const float* x, float* y, int n, int h, int wd, int c, int r, int s,
-                           int stride, int pad, hipStream_t st);
-hipError_t maxpool_backward(const float* x, const float* dy, float* dx, int n, int h, int wd, int c,
-                            int r, int s, int stride, int pad, int accumulate, hipStream_t st);
-hipError_t gap_forward(const float* x, float* y, int n, int hw, int c, hipStream_t st);
-hipError_t gap_backward(const float* dy, float* dx, int n, int hw, int c, int accumulate,
+hipError_t maxpool_forward(const void* x, void* y, int n, int h, int wd, int c, int r, int s,
+                           int stride, int pad, int dtype, hipStream_t st);
+hipError_t maxpool_backward(const void* x, const void* dy, void* dx, int n, int h, int wd, int c,
+                            int r, int s, int stride, int pad, int accumulate, int dtype, hipStream_t st);
+hipError_t gap_forward(const void* x, void* y, int n, int hw, int c, int dtype, hipStream_t st);
+hipError_t gap_backward(const void* dy, void* dx, int n, int hw, int c, int accumulate, int dtype,
                         hipStream_t st);
-hipError_t bias_add(float* y, const float* b, long rows, int c, hipStream_t st);
-hipError_t column_sum(const float* dy, float* db, long rows, int c, hipStream_t st);
+hipError_t bias_add(void* y, const float* b, long rows, int c, int dtype, hipStream_t st);
+hipError_t column_sum(const void* dy, float* db, long rows, int c, int dtype, hipStream_t st);
 // loss_rows: n floats of scratch; loss: one float
-hipError_t softmax_ce_forward(const float* z, const int32_t* labels, float* loss_rows, float* loss,
-                              int n, int classes, hipStream_t st);
-hipError_t softmax_ce_backward(const float* z, const int32_t* labels, float* dz, int n, int classes,
-                               hipStream_t st);
-hipError_t sgd_update(float* w, const float* g, float lr, size_t count, hipStream_t st);
+hipError_t softmax_ce_forward(const void* z, const int32_t* labels, float* loss_rows, float* loss,
+                              int n, int classes, int dtype, hipStream_t st);
+hipError_t softmax_ce_backward(const void* z, const int32_t* labels, void* dz, int n, int classes,
+                               int dtype, hipStream_t st);
+// w <- w - lr * g (fp32); w_bf16 (may be null): rounded copy of the updated weights
+hipError_t sgd_update(float* w, const float* g, float lr, size_t count, void* w_bf16, hipStream_t st);
 hipError_t fill_zero(float* p, size_t count, hipStream_t st);
-// y[n][hw][c] = x[n][c][hw]
-hipError_t nchw_to_nhwc(const float* x, float* y, int n, int c, int hw, hipStream_t st);
+// y[n][hw][c] (dtype) = x[n][c][hw] (fp32)
+hipError_t nchw_to_nhwc(const float* x, void* y, int n, int c, int hw, int dtype, hipStream_t st);
 
 }  // namespace acc

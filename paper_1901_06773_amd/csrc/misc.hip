@@ -3,6 +3,7 @@
 // None of them is on the roofline-critical path; all are coalesced along the channel
 // axis of NHWC and use fixed-order reductions.
 #include "kernels.h"
+#include "dtype.h"
 
 namespace acc {
 namespace {
@@ -17,10 +18,11 @@ inline unsigned grid_for(size_t work, size_t cap = 256 * 32) {
 
 // wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci]; a 32x32 LDS tile transposes (co, ci)
 // so that both the read (ci fastest) and the write (co fastest) are coalesced.
-__global__ __launch_bounds__(256) void flip_transpose_kernel(const float* __restrict__ w,
-                                                             float* __restrict__ wt, int cout, int cin,
+template <class T>
+__global__ __launch_bounds__(256) void flip_transpose_kernel(const T* __restrict__ w,
+                                                             T* __restrict__ wt, int cout, int cin,
                                                              int r, int s) {
-  __shared__ float tile[32][33];
+  __shared__ T tile[32][33];
   const int tap = blockIdx.z;                       // r'*s + t' of the output
   const int kr = r - 1 - tap / s, kt = s - 1 - tap % s;
   const int src_tap = kr * s + kt;
@@ -28,7 +30,7 @@ __global__ __launch_bounds__(256) void flip_transpose_kernel(const float* __rest
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
   for (int i = ty; i < 32; i += 8) {
     const int co = co0 + i, ci = ci0 + tx;
-    tile[i][tx] = (co < cout && ci < cin) ? w[((size_t)co * r * s + src_tap) * cin + ci] : 0.f;
+    tile[i][tx] = (co < cout && ci < cin) ? w[((size_t)co * r * s + src_tap) * cin + ci] : T(0);
   }
   __syncthreads();
   for (int i = ty; i < 32; i += 8) {
@@ -38,8 +40,9 @@ __global__ __launch_bounds__(256) void flip_transpose_kernel(const float* __rest
 }
 
 // one thread per (n, p, q, 4 channels); the first maximum in (r, t) scan order wins
-__global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __restrict__ x,
-                                                              float* __restrict__ y, int n, int h, int wd,
+template <class T>
+__global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const T* __restrict__ x,
+                                                              T* __restrict__ y, int n, int h, int wd,
                                                               int c, int r, int s, int stride, int pad,
                                                               int ho, int wo) {
   const int cg = c >> 2;
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __res
     const int q = (int)(rest % wo); rest /= wo;
     const int p = (int)(rest % ho);
     const int img = (int)(rest / ho);
-    float4 best = make_float4(0.f, 0.f, 0.f, 0.f);
+    float best[4] = {0.f, 0.f, 0.f, 0.f};
     bool have = false;
     for (int kr = 0; kr < r; ++kr) {
       const int iy = p * stride + kr - pad;
@@ -58,17 +61,14 @@ __global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __res
       for (int kt = 0; kt < s; ++kt) {
         const int ix = q * stride + kt - pad;
         if ((unsigned)ix >= (unsigned)wd) continue;
-        const float4 v = *reinterpret_cast<const float4*>(x + ((size_t)(img * h + iy) * wd + ix) * c + g * 4);
-        if (!have) { best = v; have = true; }
-        else {
-          best.x = v.x > best.x ? v.x : best.x;
-          best.y = v.y > best.y ? v.y : best.y;
-          best.z = v.z > best.z ? v.z : best.z;
-          best.w = v.w > best.w ? v.w : best.w;
-        }
+        float v[4];
+        Elem<T>::load4(x + ((size_t)(img * h + iy) * wd + ix) * c + g * 4, v);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) best[j] = (!have || v[j] > best[j]) ? v[j] : best[j];
+        have = true;
       }
     }
-    *reinterpret_cast<float4*>(y + i * 4) = best;
+    Elem<T>::store4(y + i * 4, best);
   }
 }
 
@@ -76,13 +76,15 @@ __global__ __launch_bounds__(THREADS) void maxpool_fwd_kernel(const float* __res
 // channels (V = 4 as float4 when c % 4 == 0, else 1); for every window that covers the
 // position, find the window's first maximum again and take the window's dy where this
 // position is the winner.  Windows are visited in (p, q) order, so the sum has a fixed order.
-template <int V>
-__global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __restrict__ x,
-                                                              const float* __restrict__ dy, float* dx,
+template <class T, int V>
+__global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const T* __restrict__ x,
+                                                              const T* __restrict__ dy, T* dx,
                                                               int n, int h, int wd, int c, int r, int s,
                                                               int stride, int pad, int ho, int wo,
                                                               int accumulate) {
-  struct alignas(4 * V) Vec { float v[V]; };
+  struct Vec { float v[V]; };
+  auto ld = [](const T* p) { Vec r; if constexpr (V == 4) Elem<T>::load4(p, r.v); else r.v[0] = Elem<T>::load(p); return r; };
+  auto st = [](T* p, const Vec& r) { if constexpr (V == 4) Elem<T>::store4(p, r.v); else Elem<T>::store(p, r.v[0]); };
   const int cg = c / V;
   const size_t total = (size_t)n * h * wd * cg;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
@@ -114,65 +116,69 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const float* __res
           for (int kt = 0; kt < s; ++kt) {
             const int xx = q * stride + kt - pad;
             if ((unsigned)xx >= (unsigned)wd) continue;
-            const Vec v = *reinterpret_cast<const Vec*>(x + ((size_t)(img * h + yy) * wd + xx) * c + g * V);
+            const Vec v = ld(x + ((size_t)(img * h + yy) * wd + xx) * c + g * V);
 #pragma unroll
             for (int j = 0; j < V; ++j)
               if (at[j] < 0 || v.v[j] > best.v[j]) { best.v[j] = v.v[j]; at[j] = yy * wd + xx; }
           }
         }
-        const Vec d = *reinterpret_cast<const Vec*>(dy + ((size_t)(img * ho + p) * wo + q) * c + g * V);
+        const Vec d = ld(dy + ((size_t)(img * ho + p) * wo + q) * c + g * V);
 #pragma unroll
         for (int j = 0; j < V; ++j)
           if (at[j] == me) acc.v[j] += d.v[j];
       }
-    Vec* out = reinterpret_cast<Vec*>(dx + i * V);
+    T* out = dx + i * V;
     if (accumulate) {
-      const Vec o = *out;
+      const Vec o = ld(out);
 #pragma unroll
       for (int j = 0; j < V; ++j) acc.v[j] = o.v[j] + acc.v[j];
     }
-    *out = acc;
+    st(out, acc);
   }
 }
 
 // y[n][c] = mean over hw of x[n][hw][c]
-__global__ __launch_bounds__(THREADS) void gap_fwd_kernel(const float* __restrict__ x, float* __restrict__ y,
+template <class T>
+__global__ __launch_bounds__(THREADS) void gap_fwd_kernel(const T* __restrict__ x, T* __restrict__ y,
                                                           int n, int hw, int c) {
   const size_t total = (size_t)n * c;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
     const int ch = (int)(i % c);
     const int img = (int)(i / c);
     float sum = 0.f;
-    for (int k = 0; k < hw; ++k) sum += x[((size_t)img * hw + k) * c + ch];
-    y[i] = sum / (float)hw;
+    for (int k = 0; k < hw; ++k) sum += Elem<T>::load(x + ((size_t)img * hw + k) * c + ch);
+    Elem<T>::store(y + i, sum / (float)hw);
   }
 }
 
-__global__ __launch_bounds__(THREADS) void gap_bwd_kernel(const float* __restrict__ dy, float* dx, int n,
+template <class T>
+__global__ __launch_bounds__(THREADS) void gap_bwd_kernel(const T* __restrict__ dy, T* dx, int n,
                                                           int hw, int c, int accumulate) {
   const size_t total = (size_t)n * hw * c;
   const float inv = 1.f / (float)hw;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
     const int ch = (int)(i % c);
     const int img = (int)(i / ((size_t)hw * c));
-    const float v = dy[(size_t)img * c + ch] * inv;
-    dx[i] = accumulate ? dx[i] + v : v;
+    const float v = Elem<T>::load(dy + (size_t)img * c + ch) * inv;
+    Elem<T>::store(dx + i, accumulate ? Elem<T>::load(dx + i) + v : v);
   }
 }
 
-__global__ __launch_bounds__(THREADS) void bias_add_kernel(float* y, const float* __restrict__ b, size_t total,
+template <class T>
+__global__ __launch_bounds__(THREADS) void bias_add_kernel(T* y, const float* __restrict__ b, size_t total,
                                                            int c) {
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS)
-    y[i] += b[i % c];
+    Elem<T>::store(y + i, Elem<T>::load(y + i) + b[i % c]);
 }
 
 // db[ch] = sum over rows, one thread per channel, rows in order
-__global__ __launch_bounds__(THREADS) void column_sum_kernel(const float* __restrict__ dy,
+template <class T>
+__global__ __launch_bounds__(THREADS) void column_sum_kernel(const T* __restrict__ dy,
                                                              float* __restrict__ db, long rows, int c) {
   const int ch = blockIdx.x * THREADS + threadIdx.x;
   if (ch >= c) return;
   float sum = 0.f;
-  for (long r = 0; r < rows; ++r) sum += dy[(size_t)r * c + ch];
+  for (long r = 0; r < rows; ++r) sum += Elem<T>::load(dy + (size_t)r * c + ch);
   db[ch] = sum;
 }
 
@@ -202,26 +208,27 @@ __device__ __forceinline__ float block_sum(float v, float* sh) {
 
 // one workgroup per sample: loss_rows[i] = logsumexp(z_i) - z_i[label]; optionally
 // dz = (softmax - onehot) / n
-__global__ __launch_bounds__(THREADS) void softmax_ce_kernel(const float* __restrict__ z,
+template <class T>
+__global__ __launch_bounds__(THREADS) void softmax_ce_kernel(const T* __restrict__ z,
                                                              const int32_t* __restrict__ labels,
                                                              float* __restrict__ loss_rows,
-                                                             float* __restrict__ dz, int n, int classes) {
+                                                             T* __restrict__ dz, int n, int classes) {
   __shared__ float sh[THREADS];
   const int i = blockIdx.x;
-  const float* zi = z + (size_t)i * classes;
+  const T* zi = z + (size_t)i * classes;
   float mx = -INFINITY;
-  for (int j = threadIdx.x; j < classes; j += THREADS) mx = fmaxf(mx, zi[j]);
+  for (int j = threadIdx.x; j < classes; j += THREADS) mx = fmaxf(mx, Elem<T>::load(zi + j));
   mx = block_max(mx, sh);
   float se = 0.f;
-  for (int j = threadIdx.x; j < classes; j += THREADS) se += expf(zi[j] - mx);
+  for (int j = threadIdx.x; j < classes; j += THREADS) se += expf(Elem<T>::load(zi + j) - mx);
   se = block_sum(se, sh);
   const float lse = mx + logf(se);
   const int lab = labels[i];
-  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lse - zi[lab];
+  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lse - Elem<T>::load(zi + lab);
   if (dz) {
     const float inv_n = 1.f / (float)n;
     for (int j = threadIdx.x; j < classes; j += THREADS)
-      dz[(size_t)i * classes + j] = (expf(zi[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_n;
+      Elem<T>::store(dz + (size_t)i * classes + j, (expf(Elem<T>::load(zi + j) - lse) - (j == lab ? 1.f : 0.f)) * inv_n);
   }
 }
 
@@ -234,10 +241,15 @@ __global__ void loss_mean_kernel(const float* __restrict__ loss_rows, float* __r
   }
 }
 
+// w <- w - lr * g on the fp32 master weights; in bf16 mode the rounded copy the kernels read is
+// refreshed in the same pass
 __global__ __launch_bounds__(THREADS) void sgd_kernel(float* __restrict__ w, const float* __restrict__ g,
-                                                      float lr, size_t count) {
-  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < count; i += (size_t)gridDim.x * THREADS)
-    w[i] = fmaf(-lr, g[i], w[i]);
+                                                      float lr, size_t count, bf16_t* __restrict__ w16) {
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < count; i += (size_t)gridDim.x * THREADS) {
+    const float v = fmaf(-lr, g[i], w[i]);
+    w[i] = v;
+    if (w16) w16[i] = float_to_bf16(v);
+  }
 }
 
 __global__ __launch_bounds__(THREADS) void fill_zero_kernel(float* __restrict__ p, size_t count) {
@@ -246,49 +258,60 @@ __global__ __launch_bounds__(THREADS) void fill_zero_kernel(float* __restrict__ 
 }
 
 // y[n][hw][c] = x[n][c][hw]: reads coalesced along hw for each channel, one pixel per thread
-__global__ __launch_bounds__(THREADS) void nchw_to_nhwc_kernel(const float* __restrict__ x, float* __restrict__ y,
+template <class T>
+__global__ __launch_bounds__(THREADS) void nchw_to_nhwc_kernel(const float* __restrict__ x, T* __restrict__ y,
                                                                int n, int c, int hw) {
   const size_t total = (size_t)n * hw;
   for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
     const size_t img = i / hw, pos = i - img * hw;
     const float* src = x + img * (size_t)c * hw + pos;
-    float* dst = y + i * c;
-    for (int ch = 0; ch < c; ++ch) dst[ch] = src[(size_t)ch * hw];
+    T* dst = y + i * c;
+    for (int ch = 0; ch < c; ++ch) Elem<T>::store(dst + ch, src[(size_t)ch * hw]);
   }
 }
 
 }  // namespace
 
-hipError_t nchw_to_nhwc(const float* x, float* y, int n, int c, int hw, hipStream_t st) {
+// runs `call` with T = float or bf16_t according to dtype
+#define ACC_DISPATCH(dtype, call)                                   \
+  do {                                                              \
+    if ((dtype) == DT_F32) { using T = float; call; }               \
+    else if ((dtype) == DT_BF16) { using T = bf16_t; call; }        \
+    else return hipErrorInvalidValue;                               \
+  } while (0)
+
+hipError_t nchw_to_nhwc(const float* x, void* y, int n, int c, int hw, int dtype, hipStream_t st) {
   if (!x || !y || n <= 0 || c <= 0 || hw <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(nchw_to_nhwc_kernel, dim3(grid_for((size_t)n * hw)), dim3(THREADS), 0, st, x, y, n, c, hw);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(nchw_to_nhwc_kernel<T>, dim3(grid_for((size_t)n * hw)), dim3(THREADS), 0, st,
+                                         x, (T*)y, n, c, hw));
   return hipGetLastError();
 }
 
-hipError_t filter_flip_transpose(const float* w, float* wt, int cout, int cin, int r, int s,
+hipError_t filter_flip_transpose(const void* w, void* wt, int cout, int cin, int r, int s, int dtype,
                                  hipStream_t st) {
   if (!w || !wt || cout <= 0 || cin <= 0 || r <= 0 || s <= 0 || r * s > 65535) return hipErrorInvalidValue;
   const dim3 grid((cin + 31) / 32, (cout + 31) / 32, r * s);
   if (grid.y > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(flip_transpose_kernel, grid, dim3(256), 0, st, w, wt, cout, cin, r, s);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(flip_transpose_kernel<T>, grid, dim3(256), 0, st, (const T*)w, (T*)wt, cout,
+                                         cin, r, s));
   return hipGetLastError();
 }
 
-hipError_t maxpool_forward(const float* x, float* y, int n, int h, int wd, int c, int r, int s,
-                           int stride, int pad, hipStream_t st) {
+hipError_t maxpool_forward(const void* x, void* y, int n, int h, int wd, int c, int r, int s,
+                           int stride, int pad, int dtype, hipStream_t st) {
   if (!x || !y || n <= 0 || h <= 0 || wd <= 0 || c <= 0 || (c & 3) || r <= 0 || s <= 0 || stride <= 0 ||
       pad < 0 || pad >= r || pad >= s)
     return hipErrorInvalidValue;
   const int ho = (h + 2 * pad - r) / stride + 1, wo = (wd + 2 * pad - s) / stride + 1;
   if (ho <= 0 || wo <= 0) return hipErrorInvalidValue;
   const size_t total = (size_t)n * ho * wo * (c / 4);
-  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for(total)), dim3(THREADS), 0, st, x, y, n, h, wd, c, r, s,
-                     stride, pad, ho, wo);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(grid_for(total)), dim3(THREADS), 0, st,
+                                         (const T*)x, (T*)y, n, h, wd, c, r, s, stride, pad, ho, wo));
   return hipGetLastError();
 }
 
-hipError_t maxpool_backward(const float* x, const float* dy, float* dx, int n, int h, int wd, int c,
-                            int r, int s, int stride, int pad, int accumulate, hipStream_t st) {
+hipError_t maxpool_backward(const void* x, const void* dy, void* dx, int n, int h, int wd, int c,
+                            int r, int s, int stride, int pad, int accumulate, int dtype, hipStream_t st) {
   if (!x || !dy || !dx || n <= 0 || h <= 0 || wd <= 0 || c <= 0 || r <= 0 || s <= 0 || stride <= 0 ||
       pad < 0 || pad >= r || pad >= s)
     return hipErrorInvalidValue;
@@ -296,64 +319,68 @@ hipError_t maxpool_backward(const float* x, const float* dy, float* dx, int n, i
   if (ho <= 0 || wo <= 0) return hipErrorInvalidValue;
   if (c % 4 == 0) {
     const size_t total = (size_t)n * h * wd * (c / 4);
-    hipLaunchKernelGGL(maxpool_bwd_kernel<4>, dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0, st, x, dy, dx, n, h,
-                       wd, c, r, s, stride, pad, ho, wo, accumulate);
+    ACC_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_kernel<T, 4>), dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0,
+                                           st, (const T*)x, (const T*)dy, (T*)dx, n, h, wd, c, r, s, stride, pad, ho,
+                                           wo, accumulate));
   } else {
     const size_t total = (size_t)n * h * wd * c;
-    hipLaunchKernelGGL(maxpool_bwd_kernel<1>, dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0, st, x, dy, dx, n, h,
-                       wd, c, r, s, stride, pad, ho, wo, accumulate);
+    ACC_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_kernel<T, 1>), dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0,
+                                           st, (const T*)x, (const T*)dy, (T*)dx, n, h, wd, c, r, s, stride, pad, ho,
+                                           wo, accumulate));
   }
   return hipGetLastError();
 }
 
-hipError_t gap_forward(const float* x, float* y, int n, int hw, int c, hipStream_t st) {
+hipError_t gap_forward(const void* x, void* y, int n, int hw, int c, int dtype, hipStream_t st) {
   if (!x || !y || n <= 0 || hw <= 0 || c <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gap_fwd_kernel, dim3(grid_for((size_t)n * c)), dim3(THREADS), 0, st, x, y, n, hw, c);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(gap_fwd_kernel<T>, dim3(grid_for((size_t)n * c)), dim3(THREADS), 0, st,
+                                         (const T*)x, (T*)y, n, hw, c));
   return hipGetLastError();
 }
 
-hipError_t gap_backward(const float* dy, float* dx, int n, int hw, int c, int accumulate, hipStream_t st) {
+hipError_t gap_backward(const void* dy, void* dx, int n, int hw, int c, int accumulate, int dtype, hipStream_t st) {
   if (!dy || !dx || n <= 0 || hw <= 0 || c <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gap_bwd_kernel, dim3(grid_for((size_t)n * hw * c)), dim3(THREADS), 0, st, dy, dx, n, hw,
-                     c, accumulate);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(gap_bwd_kernel<T>, dim3(grid_for((size_t)n * hw * c)), dim3(THREADS), 0, st,
+                                         (const T*)dy, (T*)dx, n, hw, c, accumulate));
   return hipGetLastError();
 }
 
-hipError_t bias_add(float* y, const float* b, long rows, int c, hipStream_t st) {
+hipError_t bias_add(void* y, const float* b, long rows, int c, int dtype, hipStream_t st) {
   if (!y || !b || rows <= 0 || c <= 0) return hipErrorInvalidValue;
   const size_t total = (size_t)rows * c;
-  hipLaunchKernelGGL(bias_add_kernel, dim3(grid_for(total)), dim3(THREADS), 0, st, y, b, total, c);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(bias_add_kernel<T>, dim3(grid_for(total)), dim3(THREADS), 0, st, (T*)y, b,
+                                         total, c));
   return hipGetLastError();
 }
 
-hipError_t column_sum(const float* dy, float* db, long rows, int c, hipStream_t st) {
+hipError_t column_sum(const void* dy, float* db, long rows, int c, int dtype, hipStream_t st) {
   if (!dy || !db || rows <= 0 || c <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(column_sum_kernel, dim3((c + THREADS - 1) / THREADS), dim3(THREADS), 0, st, dy, db, rows,
-                     c);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(column_sum_kernel<T>, dim3((c + THREADS - 1) / THREADS), dim3(THREADS), 0, st,
+                                         (const T*)dy, db, rows, c));
   return hipGetLastError();
 }
 
-hipError_t softmax_ce_forward(const float* z, const int32_t* labels, float* loss_rows, float* loss,
-                              int n, int classes, hipStream_t st) {
+hipError_t softmax_ce_forward(const void* z, const int32_t* labels, float* loss_rows, float* loss,
+                              int n, int classes, int dtype, hipStream_t st) {
   if (!z || !labels || !loss_rows || !loss || n <= 0 || classes <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(softmax_ce_kernel, dim3(n), dim3(THREADS), 0, st, z, labels, loss_rows,
-                     (float*)nullptr, n, classes);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(softmax_ce_kernel<T>, dim3(n), dim3(THREADS), 0, st, (const T*)z, labels,
+                                         loss_rows, (T*)nullptr, n, classes));
   hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(64), 0, st, loss_rows, loss, n);
   return hipGetLastError();
 }
 
-hipError_t softmax_ce_backward(const float* z, const int32_t* labels, float* dz, int n, int classes,
+hipError_t softmax_ce_backward(const void* z, const int32_t* labels, void* dz, int n, int classes, int dtype,
                                hipStream_t st) {
   if (!z || !labels || !dz || n <= 0 || classes <= 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(softmax_ce_kernel, dim3(n), dim3(THREADS), 0, st, z, labels, (float*)nullptr, dz, n,
-                     classes);
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(softmax_ce_kernel<T>, dim3(n), dim3(THREADS), 0, st, (const T*)z, labels,
+                                         (float*)nullptr, (T*)dz, n, classes));
   return hipGetLastError();
 }
 
-hipError_t sgd_update(float* w, const float* g, float lr, size_t count, hipStream_t st) {
+hipError_t sgd_update(float* w, const float* g, float lr, size_t count, void* w_bf16, hipStream_t st) {
   if (!w || !g) return hipErrorInvalidValue;
   if (count == 0) return hipSuccess;
-  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(count)), dim3(THREADS), 0, st, w, g, lr, count);
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(count)), dim3(THREADS), 0, st, w, g, lr, count, (bf16_t*)w_bf16);
   return hipGetLastError();
 }
 

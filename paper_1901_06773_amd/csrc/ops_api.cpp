@@ -4,6 +4,7 @@
 
 #include "../../include/accudnn.h"
 #include "kernels.h"
+#include "dtype.h"
 
 using namespace acc;
 
@@ -14,6 +15,7 @@ inline bool conv_ok(int n, int h, int w, int cin, int cout, int r, int s, int st
   return n > 0 && h > 0 && w > 0 && cin > 0 && cout > 0 && r > 0 && s == r && stride > 0 && pad >= 0 && pad < r &&
          h + 2 * pad >= r && w + 2 * pad >= s;
 }
+inline bool dtype_ok(int dt) { return dt == ACC_F32 || dt == ACC_BF16; }
 inline int status(hipError_t e) { return e == hipSuccess ? ACC_OK : (e == hipErrorInvalidValue ? ACC_EINVAL : ACC_EHIP); }
 }  // namespace
 
@@ -23,11 +25,11 @@ extern "C" size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, 
   return al256(wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s)) + al256((size_t)cout * cin * r * s * sizeof(float));
 }
 
-extern "C" int acc_op_conv_fwd(const float* x, const float* w, float* y, int n, int h, int wd, int cin, int cout,
-                               int r, int s, int stride, int pad, void* stream) {
-  if (!x || !w || !y || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+extern "C" int acc_op_conv_fwd(const void* x, const void* w, void* y, int n, int h, int wd, int cin, int cout,
+                               int r, int s, int stride, int pad, int dtype, void* stream) {
+  if (!x || !w || !y || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
   ConvGeom g{};
-  g.in = x; g.w = w; g.out = y;
+  g.in = x; g.w = w; g.out = y; g.dtype = dtype;
   g.n_img = n; g.h = h; g.wd = wd; g.c = cin;
   g.p = out_dim(h, r, stride, pad); g.q = out_dim(wd, s, stride, pad); g.n_out = cout;
   g.r = r; g.s = s; g.stride = stride; g.pad = pad;
@@ -35,20 +37,20 @@ extern "C" int acc_op_conv_fwd(const float* x, const float* w, float* y, int n, 
   return status(conv_igemm(g, (hipStream_t)stream));
 }
 
-extern "C" int acc_op_conv_dgrad(const float* dy, const float* w, float* dx, int n, int h, int wd, int cin, int cout,
+extern "C" int acc_op_conv_dgrad(const void* dy, const void* w, void* dx, int n, int h, int wd, int cin, int cout,
                                  int r, int s, int stride, int pad, int accumulate, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
-  if (!dy || !w || !dx || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+                                 size_t workspace_bytes, int dtype, void* stream) {
+  if (!dy || !w || !dx || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
   if (stride > 1 && (r > 1 || pad > 0)) return ACC_EINVAL;   // strided data gradient: 1x1 only
   const size_t filt = al256((size_t)cout * cin * r * s * sizeof(float));
   if (!workspace || workspace_bytes < filt) return ACC_EINVAL;
   hipStream_t st = (hipStream_t)stream;
-  float* wt = (float*)workspace;
-  hipError_t e = filter_flip_transpose(w, wt, cout, cin, r, s, st);
+  void* wt = workspace;
+  hipError_t e = filter_flip_transpose(w, wt, cout, cin, r, s, dtype, st);
   if (e != hipSuccess) return status(e);
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
   ConvGeom g{};
-  g.in = dy; g.w = wt; g.out = dx;
+  g.in = dy; g.w = wt; g.out = dx; g.dtype = dtype;
   g.n_img = n; g.h = ho; g.wd = wo; g.c = cout; g.n_out = cin;
   g.r = r; g.s = s; g.stride = 1; g.accumulate = accumulate;
   g.out_h = h; g.out_w = wd;
@@ -57,22 +59,24 @@ extern "C" int acc_op_conv_dgrad(const float* dy, const float* w, float* dx, int
   } else {
     g.p = ho; g.q = wo; g.pad = 0; g.out_stride = stride;
     if (!accumulate) {
-      e = fill_zero(dx, (size_t)n * h * wd * cin, st);
+      const size_t bytes = (size_t)n * h * wd * cin * dt_size(dtype);
+      if (bytes % 4) return ACC_EINVAL;
+      e = fill_zero((float*)dx, bytes / 4, st);
       if (e != hipSuccess) return status(e);
     }
   }
   return status(conv_igemm(g, st));
 }
 
-extern "C" int acc_op_conv_wgrad(const float* x, const float* dy, float* dw, int n, int h, int wd, int cin, int cout,
+extern "C" int acc_op_conv_wgrad(const void* x, const void* dy, float* dw, int n, int h, int wd, int cin, int cout,
                                  int r, int s, int stride, int pad, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
-  if (!x || !dy || !dw || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+                                 int dtype, void* stream) {
+  if (!x || !dy || !dw || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
   const size_t need = wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s);
   if (need && (!workspace || workspace_bytes < need)) return ACC_EINVAL;
   WgradGeom g{};
-  g.x = x; g.dy = dy; g.dw = dw;
+  g.x = x; g.dy = dy; g.dw = dw; g.dtype = dtype;
   g.n_img = n; g.h = h; g.wd = wd; g.cin = cin; g.p = ho; g.q = wo; g.cout = cout;
   g.r = r; g.s = s; g.stride = stride; g.pad = pad; g.workspace = (float*)workspace;
   return status(conv_wgrad(g, (hipStream_t)stream));
@@ -80,15 +84,18 @@ extern "C" int acc_op_conv_wgrad(const float* x, const float* dy, float* dw, int
 
 extern "C" size_t acc_op_bn_workspace(int c) { return c > 0 ? al256(bn_workspace_bytes(c)) : 0; }
 
-extern "C" int acc_op_bn_fwd(const float* x, const float* gamma, const float* beta, const float* res, float* y,
+extern "C" int acc_op_bn_fwd(const void* x, const float* gamma, const float* beta, const void* res, void* y,
                              float* mean, float* istd, int rows, int c, int relu, float eps, void* workspace,
-                             void* stream) {
-  return status(bn_forward(x, gamma, beta, res, y, mean, istd, rows, c, relu, eps, workspace, (hipStream_t)stream));
+                             int dtype, void* stream) {
+  if (!dtype_ok(dtype)) return ACC_EINVAL;
+  return status(bn_forward(x, gamma, beta, res, y, mean, istd, rows, c, relu, eps, workspace, dtype,
+                           (hipStream_t)stream));
 }
 
-extern "C" int acc_op_bn_bwd(const float* x, const float* dy, const float* y, const float* gamma, const float* mean,
-                             const float* istd, float* dx, float* dgamma, float* dbeta, float* g_out, int rows, int c,
-                             void* workspace, void* stream) {
-  return status(bn_backward(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, rows, c, workspace,
+extern "C" int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const float* gamma, const float* mean,
+                             const float* istd, void* dx, float* dgamma, float* dbeta, void* g_out, int rows, int c,
+                             void* workspace, int dtype, void* stream) {
+  if (!dtype_ok(dtype)) return ACC_EINVAL;
+  return status(bn_backward(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, rows, c, workspace, dtype,
                             (hipStream_t)stream));
 }

@@ -257,3 +257,96 @@ def test_conv_full_size_sampled(case):
                     if 0 <= py < ho and 0 <= px < wo:
                         ref += np.dot(DY[i, py, px, :], W_[:, kr, kt, ci])
             assert abs(DX[i, iy, ix, ci] - ref) <= TOL * scale_dx, ("dgrad", case, (i, iy, ix, ci))
+
+
+# ------------------------------------------------------------------ bf16 storage
+BF16_CASES = [
+    (2, 14, 14, 64, 96, 3, 1, 1),      # fast path (channels a multiple of 64), N tail
+    (3, 9, 9, 128, 256, 1, 1, 0),
+    (2, 16, 16, 64, 128, 1, 2, 0),     # strided 1x1
+    (5, 28, 28, 64, 64, 3, 1, 1),      # several tiles
+    (2, 16, 16, 32, 16, 3, 1, 1),      # 32 channels: per-element path in bf16
+    (2, 12, 10, 20, 24, 3, 1, 1),      # ragged channels
+    (2, 23, 23, 8, 16, 7, 2, 3),       # stem-like
+]
+
+
+def bf(a: np.ndarray) -> torch.Tensor:
+    """numpy fp32 -> device bf16 (round to nearest even)"""
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(torch.bfloat16)
+
+
+def f32(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("case", BF16_CASES)
+def test_conv_bf16(case):
+    """bf16 operands, fp32 accumulation: against the oracle run on the same bf16-rounded
+    operands the only differences are the accumulation order and the final rounding of a
+    bf16 output (relative 2^-9 per element); the weight gradient is fp32 and held to 1e-4."""
+    n, h, w, cin, cout, r, stride, pad = case
+    b = B()
+    xb = bf(nhwc(rnd(1, n, cin, h, w)))
+    wb = bf(ohwi(rnd(2, cout, cin, r, r) * np.float32(np.sqrt(2.0 / (cin * r * r)))))
+    x, wt = nchw(f32(xb)), oihw(f32(wb))                         # what the kernels really see
+    ho, wo = O.out_dim(h, r, stride, pad), O.out_dim(w, r, stride, pad)
+    dyb = bf(nhwc(rnd(3, n, cout, ho, wo)))
+    dy = nchw(f32(dyb))
+    y = torch.full((n, ho, wo, cout), float("nan"), device="cuda", dtype=torch.bfloat16)
+    b.op_conv_fwd(xb, wb, y, stride, pad)
+    ws = torch.empty(max(b.op_conv_workspace(n, h, w, cin, cout, r, stride, pad), 256), dtype=torch.uint8, device="cuda")
+    dw = torch.full((cout, r, r, cin), float("nan"), device="cuda")
+    b.op_conv_wgrad(xb, dyb, dw, stride, pad, ws)
+    torch.cuda.synchronize()
+    close(nchw(f32(y)), O.conv_fwd(x, wt, stride, pad), f"bf16 conv_fwd {case}", 8e-3)
+    close(oihw(dw.cpu().numpy()), O.conv_wgrad(x, dy, (cout, cin, r, r), stride, pad), f"bf16 conv_wgrad {case}")
+    if stride == 1 or r == 1:
+        for accumulate in (False, True):
+            base = bf(nhwc(rnd(4, n, cin, h, w)))
+            dx = base.clone() if accumulate else torch.full((n, h, w, cin), float("nan"), device="cuda", dtype=torch.bfloat16)
+            b.op_conv_dgrad(dyb, wb, dx, stride, pad, ws, accumulate)
+            torch.cuda.synchronize()
+            ref = O.conv_dgrad(dy, wt, (n, cin, h, w), stride, pad)
+            if accumulate:
+                ref = ref + nchw(f32(base))
+            close(nchw(f32(dx)), ref, f"bf16 conv_dgrad {case} acc={accumulate}", 8e-3)
+
+
+@pytest.mark.parametrize("case", [(3, 64, 7, 9), (2, 256, 14, 14), (37, 64, 11, 13)])
+@pytest.mark.parametrize("variant", ["plain", "add_relu"])
+def test_bn_bf16(case, variant):
+    n, c, h, w = case
+    b = B()
+    xb = bf(nhwc(rnd(5, n, c, h, w) * np.float32(1.7) + np.float32(0.3)))
+    x = nchw(f32(xb))
+    gamma = (1.0 + 0.2 * rnd(6, c)).astype(np.float32)
+    beta = (0.1 * rnd(7, c)).astype(np.float32)
+    relu = variant != "plain"
+    resb = bf(nhwc(rnd(8, n, c, h, w))) if relu else None
+    bn, mean, istd = O.bn_fwd(x, gamma, beta, O.BN_EPS)
+    pre = bn if resb is None else bn + nchw(f32(resb))
+    ref_y = O.relu_fwd(pre) if relu else pre
+    ws = torch.empty(b.op_bn_workspace(c), dtype=torch.uint8, device="cuda")
+    y = torch.full_like(xb, float("nan"))
+    m_d = torch.empty(c, device="cuda"); i_d = torch.empty(c, device="cuda")
+    b.op_bn_fwd(xb, dev(gamma), dev(beta), resb, y, m_d, i_d, relu, O.BN_EPS, ws)
+    torch.cuda.synchronize()
+    close(nchw(f32(y)), ref_y, f"bf16 bn_fwd {case} {variant}", 8e-3)
+    close(m_d.cpu().numpy(), mean, "bn mean", 1e-5)       # statistics are fp32 sums of the bf16 values
+    close(i_d.cpu().numpy(), istd, "bn istd", 1e-5)
+    # backward on the stored (bf16) output, so that both sides take the same ReLU decisions
+    y_used = nchw(f32(y))
+    dyb = bf(nhwc(rnd(9, n, c, h, w)))
+    dy = nchw(f32(dyb))
+    g = O.relu_bwd(y_used, dy) if relu else dy
+    ref_dx, ref_dg, ref_db = O.bn_bwd(x, g, gamma, mean, istd)
+    dxd = torch.full_like(xb, float("nan"))
+    dg_d = torch.empty(c, device="cuda"); db_d = torch.empty(c, device="cuda")
+    b.op_bn_bwd(xb, dyb, y if relu else None, dev(gamma), m_d, i_d, dxd, dg_d, db_d, dyb if relu else None, ws)
+    torch.cuda.synchronize()
+    close(nchw(f32(dxd)), ref_dx, f"bf16 bn_bwd dx {case} {variant}", 8e-3)
+    close(dg_d.cpu().numpy(), ref_dg, "bn dgamma", 1e-4)
+    close(db_d.cpu().numpy(), ref_db, "bn dbeta", 1e-4)
+    if relu:
+        np.testing.assert_array_equal(nchw(f32(dyb)), g)      # masking is exact

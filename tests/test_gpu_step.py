@@ -53,9 +53,10 @@ NETS = {
 
 
 
-def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=64 * MiB, lr=0.1, explicit=None):
+def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=64 * MiB, lr=0.1, explicit=None, dtype=0):
     b = B()
-    ctx = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w), pool_bytes=pool or budget, host_bytes=host)
+    ctx = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w), pool_bytes=pool or budget, host_bytes=host,
+                    dtype=dtype)
     ctx.set_weights(params)
     summ = ctx.plan_explicit(k, budget, explicit) if explicit is not None else ctx.plan_swaps(k, budget, mode)
     losses = []
@@ -250,3 +251,136 @@ def test_resnet152_at_the_benchmark_size_swapped_and_resident_agree_bit_for_bit(
         assert np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
     bit_equal(out["weights"], ref["weights"], "weights")
     assert np.log(1000.0) < ref["losses"][0] < np.log(1000.0) + 3.0
+
+
+# ------------------------------------------------------------------ bf16 storage (configs[4]'s arithmetic)
+def l2_close(gpu, ref, what, tol):
+    gpu = np.asarray(gpu, np.float64); ref = np.asarray(ref, np.float64)
+    assert np.isfinite(gpu).all(), f"{what}: non-finite values"
+    err = np.linalg.norm(gpu - ref) / max(np.linalg.norm(ref), 1e-30)
+    assert err <= tol, f"{what}: rel l2 {err:.3e}"
+
+
+def _bf(a):
+    """round an fp32 array to bf16 (nearest even) and back"""
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(torch.bfloat16).float().numpy()
+
+
+def bf16_chain_step(net, params, img, lab):
+    """The step of a conv-BN-ReLU chain (+ GAP, FC, loss) put together from the oracle's layer
+    functions, with every stored tensor rounded to bf16 where the GPU path stores one: conv
+    outputs, BN+ReLU outputs, pooled features, logits (before and after the bias), and the
+    gradient of each of them; weights rounded for the kernels; statistics, weight gradients
+    and the loss in fp32.  -> (loss, grads per layer)"""
+    L = net.layers
+    grads = [np.zeros(0, np.float32)] * len(L)
+    acts = {-1: _bf(img)}
+    saved = {}
+    i = 0
+    while L[i].kind == S.CONV:
+        cv, bn = L[i], L[i + 1]
+        assert bn.kind == S.BN and L[i + 2].kind == S.RELU
+        w16 = _bf(params[i].reshape(cv.cout, cv.cin, cv.r, cv.s))
+        x = acts[cv.in0]
+        z = _bf(O.conv_fwd(x, w16, cv.stride, cv.pad))
+        gamma, beta = params[i + 1][:bn.cin], params[i + 1][bn.cin:]
+        y, mean, istd = O.bn_fwd(z, gamma, beta, O.BN_EPS)
+        a = _bf(O.relu_fwd(y))
+        saved[i] = (x, w16, z, gamma, mean, istd, a)
+        acts[i + 2] = a
+        i += 3
+    gap_l, fc_l = L[i], L[i + 1]
+    assert gap_l.kind == S.GAP and fc_l.kind == S.FC and L[i + 2].kind == S.SOFTMAX_CE
+    feat_in = acts[gap_l.in0]
+    feat = _bf(O.gap_fwd(feat_in))
+    W, bias = params[i + 1][:fc_l.cout * fc_l.cin], params[i + 1][fc_l.cout * fc_l.cin:]
+    p16 = np.concatenate([_bf(W), np.zeros_like(bias)])
+    logits = _bf(_bf(O.fc_fwd(feat, p16, fc_l.cout)) + bias)
+    loss, dz = O.softmax_ce(logits, lab)
+    dz = _bf(dz)
+    dfeat, dparam = O.fc_bwd(feat, p16, dz)
+    grads[i + 1] = dparam
+    g = _bf(O.gap_bwd(_bf(dfeat), feat_in.shape))
+    i -= 3
+    while i >= 0:
+        cv = L[i]
+        x, w16, z, gamma, mean, istd, a = saved[i]
+        gm = O.relu_bwd(a, g)
+        dz_, dgamma, dbeta = O.bn_bwd(z, gm, gamma, mean, istd)
+        grads[i + 1] = np.concatenate([dgamma, dbeta])
+        dz_ = _bf(dz_)
+        grads[i] = O.conv_wgrad(x, dz_, w16.shape, cv.stride, cv.pad).ravel()
+        if i > 0:
+            g = _bf(O.conv_dgrad(dz_, w16, x.shape, cv.stride, cv.pad))
+        i -= 3
+    return loss, grads
+
+
+def test_bf16_step_equals_its_layers_put_together():
+    """At random initialisation batch-norm backward cancels most of the incoming gradient,
+    which amplifies bf16 rounding of the stored tensors to 10-50 % in the weight gradients:
+    against the fp32 oracle only the loss can be held to 2e-2 (next test).  What pins the
+    bf16 path is this: the GPU step against the same layers taken from the oracle one by
+    one with bf16 rounding at exactly the tensors the GPU stores.  Then only the accumulation
+    order and rare rounding ties differ: 2e-2 per gradient tensor holds with a wide margin."""
+    net = wide_chain()
+    k = 6
+    params = S.init_params(net)
+    img, lab = S.make_batch(net, k, 0)
+    e_loss, e_g = bf16_chain_step(net, params, img, lab)
+    b = B()
+    g = run_gpu(net, params, k, b.PLAN_NONE, 512 * MiB, dtype=b.BF16, lr=0.0)
+    l2_close(g["losses"][0], e_loss, "loss", 1e-4)
+    worst = 0.0
+    for i, (a, r) in enumerate(zip(g["grads"], e_g)):
+        if r.size:
+            worst = max(worst, np.linalg.norm(np.asarray(a, np.float64) - r) / np.linalg.norm(r))
+            l2_close(a, r, f"grad of layer {i} ({S.KIND_NAMES[net.layers[i].kind]})", 2e-2)
+    print(f"worst relative l2 distance of a gradient tensor: {worst:.2e}")
+
+
+@pytest.mark.parametrize("name", ["config1_unit", "mini_resnet_w8", "mini_resnet_w32", "wide_chain"])
+def test_bf16_loss_is_within_two_percent_of_the_fp32_oracle(name):
+    """Activations, their gradients and the weights the kernels read stored as bf16, fp32
+    accumulation, fp32 master weights and statistics: the loss within 2e-2 of the fp32
+    oracle's, every gradient finite and pointing the oracle's way (cosine above 0.8 per
+    tensor: the rounding noise explained above is large but not dominant)."""
+    make, k = NETS[name]
+    net = make()
+    params = S.init_params(net)
+    img, lab = S.make_batch(net, k, 0)
+    o_loss, o_w, o_g = O.train_step(net.as_array(), (net.in_c, net.in_h, net.in_w), params, img, lab, 0.1)
+    b = B()
+    g = run_gpu(net, params, k, b.PLAN_NONE, 512 * MiB, dtype=b.BF16)
+    l2_close(g["losses"][0], o_loss, f"{name} loss", 2e-2)
+    for i, (a, r) in enumerate(zip(g["grads"], o_g)):
+        if r.size:
+            a = np.asarray(a, np.float64)
+            assert np.isfinite(a).all()
+            cos = float(np.dot(a, r) / (np.linalg.norm(a) * np.linalg.norm(r)))
+            assert cos > 0.8, f"{name} grad of layer {i} ({S.KIND_NAMES[net.layers[i].kind]}): cosine {cos:.3f}"
+
+
+def test_bf16_maps_take_half_the_memory_and_swap_bit_exactly():
+    b = B()
+    make, k = NETS["mini_resnet_w32"]
+    net = make()
+    params = S.init_params(net)
+    chw = (net.in_c, net.in_h, net.in_w)
+    p32 = b.Context(net.as_array(), chw)
+    p16 = b.Context(net.as_array(), chw, dtype=b.BF16)
+    s32 = p32.plan_swaps(k, 1 << 40, b.PLAN_NAIVE_ALL)
+    s16 = p16.plan_swaps(k, 1 << 40, b.PLAN_NAIVE_ALL)
+    p32.close(); p16.close()
+    assert s16["n_maps"] == s32["n_maps"]
+    assert abs(s16["bytes_maps"] * 2 - s32["bytes_maps"]) <= 512 * s32["n_maps"]      # halves, up to 256-byte rounding
+    ref = run_gpu(net, params, k, b.PLAN_NONE, 512 * MiB, steps=2, dtype=b.BF16)
+    stat = s16["static_bytes"]
+    tight = stat + int((s16["layer_peak_bytes"] - stat) * 1.10) + 64 * 1024
+    out = run_gpu(net, params, k, b.PLAN_NAIVE_ALL, tight, steps=2, dtype=b.BF16)
+    assert out["summary"]["n_swapped"] == out["summary"]["n_maps"] > 0
+    assert out["stats"]["bytes_out"] == out["stats"]["bytes_in"] == s16["bytes_swapped"]
+    for a, r in zip(out["losses"], ref["losses"]):
+        assert np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
+    bit_equal(out["grads"], ref["grads"], "gradients")
+    bit_equal(out["weights"], ref["weights"], "weights")
