@@ -384,3 +384,64 @@ def test_bf16_maps_take_half_the_memory_and_swap_bit_exactly():
         assert np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
     bit_equal(out["grads"], ref["grads"], "gradients")
     bit_equal(out["weights"], ref["weights"], "weights")
+
+
+# ------------------------------------------------------------------ the baseline's configurations
+GiB = 1 << 30
+
+
+def _budgeted_vs_resident(net, k, budget, expect_swaps, dtype=0, steps=2):
+    b = B()
+    params = S.init_params(net)
+    chw = (net.in_c, net.in_h, net.in_w)
+    probe = b.Context(net.as_array(), chw, dtype=dtype)
+    plan = probe.plan_swaps(k, budget, b.PLAN_DYNAMIC)
+    resident = probe.plan_swaps(k, 1 << 40, b.PLAN_NONE)
+    probe.close()
+    assert plan["peak_bytes"] <= budget
+    assert (plan["n_swapped"] > 0) == expect_swaps, plan["n_swapped"]
+    out = run_gpu(net, params, k, b.PLAN_DYNAMIC, budget, steps=steps, host=plan["host_bytes"] + 64 * MiB, dtype=dtype)
+    assert out["stats"]["peak_pool_bytes"] <= budget
+    assert all(np.isfinite(l) for l in out["losses"])
+    if expect_swaps:
+        ref = run_gpu(net, params, k, b.PLAN_NONE, resident["peak_bytes"] + 64 * MiB, steps=steps, dtype=dtype)
+        for a, r in zip(out["losses"], ref["losses"]):
+            assert np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
+        bit_equal(out["weights"], ref["weights"], "weights")
+    return plan, out
+
+
+def test_config_resnet50_uncapped_needs_no_swap():
+    """configs[1]: ResNet-50, minibatch 32, no memory cap: the planner must choose zero swaps."""
+    plan, out = _budgeted_vs_resident(S.resnet50(), 32, 64 * GiB, expect_swaps=False)
+    assert plan["n_swapped"] == 0 and out["stats"]["bytes_out"] == 0
+
+
+def test_config_resnet101_under_12_gib():
+    """configs[2]: ResNet-101, minibatch 64, 12 GiB: planner-chosen swaps, same bits as the
+    resident run."""
+    net = S.resnet101()
+    plan, out = _budgeted_vs_resident(net, 64, 12 * GiB, expect_swaps=_needs_swap(net, 64, 12 * GiB))
+    assert out["stats"]["bytes_out"] == plan["bytes_swapped"]
+
+
+def _needs_swap(net, k, budget, dtype=0):
+    b = B()
+    probe = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w), dtype=dtype)
+    need = probe.plan_swaps(k, 1 << 40, b.PLAN_NONE)["peak_bytes"] > budget
+    probe.close()
+    return need
+
+
+def test_config_resnet152_under_8_gib_at_twice_the_resident_minibatch():
+    """configs[3]: ResNet-152 under 8 GiB at minibatch 64 (the resident maximum is 46)."""
+    plan, out = _budgeted_vs_resident(S.resnet152(), 64, 8 * GiB, expect_swaps=True)
+    assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 2 * GiB
+
+
+def test_config_resnet152_bf16_under_24_gib():
+    """configs[4]: ResNet-152 with bf16 storage, 24 GiB; at minibatch 320 (the resident maximum
+    is 291) so that the resident reference run stays small."""
+    b = B()
+    plan, out = _budgeted_vs_resident(S.resnet152(), 320, 24 * GiB, expect_swaps=True, dtype=b.BF16, steps=1)
+    assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 0
