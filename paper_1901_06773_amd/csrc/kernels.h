@@ -12,10 +12,6 @@
 
 namespace acc {
 
-// Implicit-GEMM view of a convolution-like gather:
-//   out[m][n] (+)= sum_{r,t,c} in[img, p*stride+r-pad, q*stride+t-pad, c] * w[n][(r,t,c)]
-// with row m = (img, p, q) over a P x Q grid.  The result row is written to pixel
-// (p*out_stride, q*out_stride) of an out_h x out_w image with `n_out` channels.
 // A weight-gradient reduction that has not been launched yet: dw[i] = part[0][i] + part[1][i]
 // + ... (count elements, `splits` parts, in that order).  count == 0: nothing to do.
 struct ReduceJob {
@@ -25,6 +21,10 @@ struct ReduceJob {
   int splits;
 };
 
+// Implicit-GEMM view of a convolution-like gather:
+//   out[m][n] (+)= sum_{r,t,c} in[img, p*stride+r-pad, q*stride+t-pad, c] * w[n][(r,t,c)]
+// with row m = (img, p, q) over a P x Q grid.  The result row is written to pixel
+// (p*out_stride, q*out_stride) of an out_h x out_w image with `n_out` channels.
 struct ConvGeom {
   const void* in;           // dtype
   const void* w;            // dtype
