@@ -40,21 +40,31 @@ class Arena {
  public:
   explicit Arena(size_t cap) { free_.push_back({0, cap, -1, -1}); }
 
+  // First fit; blocks whose offload has a sequence number above `ready_d2h` (still being
+  // copied out) are used only if nothing else fits.
+  bool alloc(size_t need, bool top, int ready_d2h, size_t* off, int* dstep, int* dd2h) {
+    if (try_alloc(need, top, ready_d2h, off, dstep, dd2h)) return true;
+    return try_alloc(need, top, 1 << 30, off, dstep, dd2h);
+  }
+
   // First fit over runs of adjacent free segments; bottom-up, or top-down for long-lived
   // objects so that they do not fragment the space the short-lived ones cycle through.
-  bool alloc(size_t need, bool top, size_t* off, int* dstep, int* dd2h) {
+  // Segments with tag_d2h > limit do not count as free.
+  bool try_alloc(size_t need, bool top, int limit, size_t* off, int* dstep, int* dd2h) {
     const int n = (int)free_.size();
+    auto usable = [&](int q) { return free_[q].tag_d2h <= limit; };
     *dstep = -1;
     *dd2h = -1;
     if (!top) {
       int i = 0;
       while (i < n) {
+        if (!usable(i)) { ++i; continue; }
         size_t total = 0;
         int j = i;
         for (;;) {
           total += free_[j].size;
           if (total >= need) break;
-          if (j + 1 < n && free_[j + 1].off == free_[j].off + free_[j].size) ++j;
+          if (j + 1 < n && free_[j + 1].off == free_[j].off + free_[j].size && usable(j + 1)) ++j;
           else { total = 0; break; }
         }
         if (total >= need && need > 0) {
@@ -79,12 +89,13 @@ class Arena {
     }
     int i = n - 1;
     while (i >= 0) {
+      if (!usable(i)) { --i; continue; }
       size_t total = 0;
       int j = i;
       for (;;) {
         total += free_[j].size;
         if (total >= need) break;
-        if (j - 1 >= 0 && free_[j - 1].off + free_[j - 1].size == free_[j].off) --j;
+        if (j - 1 >= 0 && free_[j - 1].off + free_[j - 1].size == free_[j].off && usable(j - 1)) --j;
         else { total = 0; break; }
       }
       if (total >= need && need > 0) {
@@ -164,10 +175,19 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
     if (P.swapped[t]) offload_after[T.last_fwd].push_back(t);
     free_after[T.last].push_back(t);
   }
+  // the model's clock (stalls ignored, so it runs early and errs towards "still copying")
+  double clk = 0.0, link_out = 0.0;
+  std::vector<double> d2h_done;                 // per offload sequence number
+  auto ready_d2h = [&]() {
+    if (!opt.clock) return 1 << 30;
+    int r = -1;
+    while (r + 1 < (int)d2h_done.size() && d2h_done[r + 1] <= clk) ++r;
+    return r;
+  };
   size_t live = 0;
   auto take = [&](int t, bool top, int* dstep, int* dd2h) {
     size_t off = 0;
-    if (!arena.alloc(P.tbytes[t], top, &off, dstep, dd2h)) return false;
+    if (!arena.alloc(P.tbytes[t], top, ready_d2h(), &off, dstep, dd2h)) return false;
     cur_off[t] = off;
     live += P.tbytes[t];
     if (live > P.dyn_peak) P.dyn_peak = live;
@@ -276,6 +296,7 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
     for (int t : g.steps[j].reads) need_h2d = std::max(need_h2d, h2d_of[t]);
     if (need_h2d > seen_c_h2d) { c.wait_h2d = need_h2d; seen_c_h2d = need_h2d; }
     P.instrs.push_back(c);
+    if (opt.clock) clk += opt.clock->step_time(g, j, k);
 
     for (int t : offload_after[j]) {
       Instr o;
@@ -287,6 +308,10 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
       P.bytes_swapped += P.tbytes[t];
       ++P.n_swapped;
       P.instrs.push_back(o);
+      if (opt.clock) {
+        link_out = std::max(link_out, clk) + opt.clock->d2h_time(P.tbytes[t]);
+        d2h_done.push_back(link_out);
+      }
       arena.release(cur_off[t], P.tbytes[t], -1, o.seq);
       live -= P.tbytes[t];
       st[t] = TS_OFFLOADED;
@@ -409,9 +434,24 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
     out->mode = mode;
     return ACC_OK;
   }
+  // A swap set is laid out twice, with plain first fit and with first fit that passes over
+  // blocks still being copied out (by the model's clock), and the layout with the shorter
+  // predicted iteration is kept.
+  auto build_sim = [&](const std::vector<uint8_t>& sw, Plan* p, std::string* w) -> bool {
+    Plan pa, pb;
+    std::string wa, wb;
+    const bool oka = build_plan(g, k, budget, sw, opt, &pa, &wa);
+    if (oka) simulate(g, cm, &pa);
+    PlanOptions timed = opt;
+    timed.clock = &cm;
+    const bool okb = build_plan(g, k, budget, sw, timed, &pb, &wb);
+    if (okb) simulate(g, cm, &pb);
+    if (!oka && !okb) { *w = wa; return false; }
+    if (okb && (!oka || pb.t_iter < pa.t_iter)) *p = std::move(pb); else *p = std::move(pa);
+    return true;
+  };
   if (mode == ACC_PLAN_NAIVE_ALL) {
-    if (!build_plan(g, k, budget, all, opt, out, why)) return ACC_EUNTRAINABLE;
-    simulate(g, cm, out);
+    if (!build_sim(all, out, why)) return ACC_EUNTRAINABLE;
     out->mode = mode;
     return ACC_OK;
   }
@@ -425,8 +465,7 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
   }
   // Trainability: the layer-wise peak with every map swapped must fit (k <= k_max).
   Plan best;
-  if (!build_plan(g, k, budget, all, opt, &best, why)) return ACC_EUNTRAINABLE;
-  simulate(g, cm, &best);
+  if (!build_sim(all, &best, why)) return ACC_EUNTRAINABLE;
   // Pin maps back into the memory the active area leaves free, starting with the maps
   // produced last (needed first in backward: the ones whose prefetch cannot hide), and keep
   // a pin whenever the predicted iteration does not get slower.
@@ -439,8 +478,7 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
       cur[t] = 0;
       Plan trial;
       std::string w2;
-      if (build_plan(g, k, budget, cur, opt, &trial, &w2)) {
-        simulate(g, cm, &trial);
+      if (build_sim(cur, &trial, &w2)) {
         if (trial.t_iter <= best.t_iter * (1.0 + 1e-9)) {
           best = std::move(trial);
           changed = true;
@@ -467,10 +505,7 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
         Plan trial;
         std::string w2;
         bool better = false;
-        if (build_plan(g, k, budget, cur, opt, &trial, &w2)) {
-          simulate(g, cm, &trial);
-          better = trial.t_iter < best.t_iter * (1.0 - 1e-6);
-        }
+        if (build_sim(cur, &trial, &w2)) better = trial.t_iter < best.t_iter * (1.0 - 1e-6);
         if (better) {
           best = std::move(trial);
           changed = true;

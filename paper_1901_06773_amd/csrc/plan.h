@@ -67,6 +67,10 @@ struct Plan {
 struct PlanOptions {
   bool lookahead = true;       // run allocations / prefetches ahead of the compute stream
   bool unlimited = false;      // ignore the budget (only to measure peaks)
+  // With a cost model: a block that an offload is still copying out (by the model's clock)
+  // is passed over while any other free block fits, so that an allocation does not wait for
+  // a copy when untouched memory is at hand.  Without: plain first fit.
+  const CostModel* clock = nullptr;
 };
 
 // Builds instruction list and placement for a fixed swap set.  Returns false (and why)
