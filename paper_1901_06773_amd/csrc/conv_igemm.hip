@@ -72,7 +72,7 @@ __device__ __forceinline__ RowPos decode_row(const ConvGeom& g, int m, int M) {
   const int q = rem - p * g.q;
   rp.pix = img * g.h * g.wd;
   rp.iy0 = p * g.stride - g.pad;
-  rp.ix0 = q * g.stride - g.pad;
+  rp.ix0 = q * g.stride - g.pad - g.pad_dx;
   return rp;
 }
 
@@ -83,7 +83,7 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
   const int rem = m - img * pq;
   const int p = rem / g.q;
   const int q = rem - p * g.q;
-  return ((size_t)(img * g.out_h + p * g.out_stride) * g.out_w + q * g.out_stride) * g.n_out;
+  return ((size_t)(img * g.out_h + g.out_y0 + p * g.out_stride) * g.out_w + g.out_x0 + q * g.out_stride) * g.n_out;
 }
 
 // FAST: c a multiple of the chunk (32 fp32 / 64 bf16 channels), NHWC input, at most 32 filter
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     // a per-row mask built once.
     constexpr int AI = BM / 32, BI = BN / 32;
     const int col4 = tid & 7, row0 = tid >> 3;
-    const int margin = g.pad * g.wd + g.pad;               // pixels
+    const int margin = g.pad * g.wd + g.pad + g.pad_dx;    // pixels
     uint32_t a_voff[AI], a_mask[AI], b_voff[BI];
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
@@ -400,11 +400,12 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   if (!probe) probe = &local;
   if (!g.in || !g.w || !g.out) return hipErrorInvalidValue;
   if (g.n_img <= 0 || g.h <= 0 || g.wd <= 0 || g.c <= 0 || g.p <= 0 || g.q <= 0 || g.n_out <= 0 ||
-      g.r <= 0 || g.s <= 0 || g.stride <= 0 || g.pad < 0 || g.out_stride <= 0)
+      g.r <= 0 || g.s <= 0 || g.stride <= 0 || g.pad < 0 || g.pad + g.pad_dx < 0 || g.out_stride <= 0 ||
+      g.out_y0 < 0 || g.out_x0 < 0)
     return hipErrorInvalidValue;
   // every gathered coordinate p*stride+r-pad is range-checked in the kernel; the output
-  // pixel (p*out_stride, q*out_stride) must exist
-  if ((g.p - 1) * g.out_stride >= g.out_h || (g.q - 1) * g.out_stride >= g.out_w)
+  // pixel (out_y0 + p*out_stride, out_x0 + q*out_stride) must exist
+  if (g.out_y0 + (long)(g.p - 1) * g.out_stride >= g.out_h || g.out_x0 + (long)(g.q - 1) * g.out_stride >= g.out_w)
     return hipErrorInvalidValue;
   const long M = (long)g.n_img * g.p * g.q;
   const long K = (long)g.r * g.s * g.c;
@@ -416,7 +417,7 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
   const long es = (long)dt_size(g.dtype);
   const bool fast = (g.c % (CHUNK_BYTES / es) == 0) && g.r * g.s <= 32 &&
-                    ((long)g.n_img * g.h * g.wd + 2L * g.pad * (g.wd + 1)) * g.c * es < (1L << 32) &&
+                    ((long)g.n_img * g.h * g.wd + 2L * (g.pad + (g.pad_dx > 0 ? g.pad_dx : 0)) * (g.wd + 1)) * g.c * es < (1L << 32) &&
                     (long)g.n_out * K * es < (1L << 32);
   probe->variant = fast ? V_IGEMM_FAST : V_IGEMM_GENERIC;
   if (g.dtype == DT_F32)

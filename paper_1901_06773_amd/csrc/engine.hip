@@ -620,7 +620,8 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       wg.r = l->r; wg.s = l->s; wg.stride = l->stride; wg.pad = l->pad;
       wg.workspace = ptr(s.ws2);
       if (s.dx < 0) return wgrad(wg, conv_flops, nullptr);   // first layer: no data gradient
-      wg.flip_w = wk; wg.flip_wt = ptr(s.ws);                // side jobs as in the fc step
+      const bool split = l->stride > 1 && (l->r > 1 || l->s > 1 || l->pad > 0);
+      if (!split) { wg.flip_w = wk; wg.flip_wt = ptr(s.ws); }   // side jobs as in the fc step
       ReduceJob job;
       hipError_t e = wgrad(wg, conv_flops, &job);
       if (e != hipSuccess) return e;
@@ -630,6 +631,35 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.n_img = k; cg.h = ho; cg.wd = wo; cg.c = l->cout; cg.n_out = l->cin;
       cg.r = l->r; cg.s = l->s; cg.stride = 1; cg.accumulate = s.dx_accumulate;
       cg.out_h = h; cg.out_w = wd;
+      if (split) {
+        // strided and larger than 1x1: one stride-1 convolution per residue class of the dx
+        // position, each with its own sub-filter; the first launch carries the reduction
+        DgradPart parts[kMaxDgradParts];
+        bool covers_all = false;
+        size_t wt_bytes = 0;
+        const int np = dgrad_split(h, wd, l->cin, l->cout, l->r, l->s, l->stride, l->pad, (int)es, parts, &covers_all,
+                                   &wt_bytes);
+        if (np <= 0 || wt_bytes > T(s.ws).bytes_fixed) return hipErrorInvalidValue;
+        if (!covers_all && !s.dx_accumulate) {
+          e = fill_zero(ptr(s.dx), (size_t)k * h * wd * l->cin * es / 4, st);
+          if (e != hipSuccess) return e;
+        }
+        double work = 0;
+        for (int i = 0; i < np; ++i) work += (double)parts[i].p * parts[i].q * parts[i].nr * parts[i].ns;
+        for (int i = 0; i < np; ++i) {
+          const DgradPart& pt = parts[i];
+          e = filter_gather_transpose(wk, ptr(s.ws), l->cout, l->cin, l->r, l->s, l->stride, pt, dt, st);
+          if (e != hipSuccess) return e;
+          cg.w = (const char*)ptr(s.ws) + pt.wt_offset;
+          cg.p = pt.p; cg.q = pt.q; cg.r = pt.nr; cg.s = pt.ns;
+          cg.pad = pt.pad_y; cg.pad_dx = pt.pad_x - pt.pad_y;
+          cg.out_stride = l->stride; cg.out_y0 = pt.y0; cg.out_x0 = pt.x0;
+          e = igemm(cg, conv_flops * ((double)pt.p * pt.q * pt.nr * pt.ns / work));
+          if (e != hipSuccess) return e;
+          cg.side = ReduceJob{};
+        }
+        return hipSuccess;
+      }
       if (l->stride == 1) {
         cg.p = h; cg.q = wd; cg.pad = l->r - 1 - l->pad; cg.out_stride = 1;
       } else {  // 1x1, pad 0: dense product on the strided positions, zeros elsewhere

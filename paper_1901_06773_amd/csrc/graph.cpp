@@ -349,12 +349,18 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
         b.x_is_image = f.x_is_image;
         const bool need_dx = !f.x_is_image;
         if (need_dx) {
+          size_t filter_bytes = params[f.layer].count * es;
           if (l.stride > 1 && (l.r > 1 || l.s > 1 || l.pad > 0)) {
-            *err = fmt("layer %d: %s", f.layer, "data gradient of a strided convolution larger than 1x1 is not supported");
-            return false;
+            // cut by the residue of the dx position: one sub-filter per class, aligned one by one
+            DgradPart parts[kMaxDgradParts];
+            if (dgrad_split(tensors[f.x].h, tensors[f.x].w, l.cin, l.cout, l.r, l.s, l.stride, l.pad, (int)es, parts,
+                            nullptr, &filter_bytes) < 0) {
+              *err = fmt("layer %d: %s", f.layer, "data gradient of this strided convolution is not supported");
+              return false;
+            }
           }
           b.dx = grad_for_write(f.x, &b.dx_accumulate);
-          b.ws = new_tensor(T_WORK, 0, 0, 0, 0, params[f.layer].count * es, f.layer);
+          b.ws = new_tensor(T_WORK, 0, 0, 0, 0, filter_bytes, f.layer);
         }
         b.ws2 = new_tensor(T_WORK, 0, 0, 0, 0, 0, f.layer);
         tensors[b.ws2].wgrad_layer = f.layer;

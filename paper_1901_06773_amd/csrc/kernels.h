@@ -10,6 +10,8 @@
 #include <cstddef>
 #include <cstdint>
 
+#include "dgrad_split.h"
+
 namespace acc {
 
 // A weight-gradient reduction that has not been launched yet: dw[i] = part[0][i] + part[1][i]
@@ -23,8 +25,9 @@ struct ReduceJob {
 
 // Implicit-GEMM view of a convolution-like gather:
 //   out[m][n] (+)= sum_{r,t,c} in[img, p*stride+r-pad, q*stride+t-pad, c] * w[n][(r,t,c)]
-// with row m = (img, p, q) over a P x Q grid.  The result row is written to pixel
-// (p*out_stride, q*out_stride) of an out_h x out_w image with `n_out` channels.
+// with row m = (img, p, q) over a P x Q grid (columns use pad + pad_dx).  The result row is
+// written to pixel (out_y0 + p*out_stride, out_x0 + q*out_stride) of an out_h x out_w image
+// with `n_out` channels.
 struct ConvGeom {
   const void* in;           // dtype
   const void* w;            // dtype
@@ -34,7 +37,9 @@ struct ConvGeom {
   int p, q;                 // rows enumerate n_img x p x q positions
   int n_out;                // GEMM N (output channels)
   int r, s, stride, pad;
+  int pad_dx;               // column padding is pad + pad_dx (>= 0)
   int out_h, out_w, out_stride;
+  int out_y0, out_x0;       // first output pixel
   int accumulate;           // out += result
   // Optional side job: extra workgroups appended to the launch add up the parts of a weight
   // gradient (independent data; saves a launch of its own).
@@ -78,6 +83,11 @@ hipError_t reduce_parts(const ReduceJob& job, hipStream_t st);
 // wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci]  (filter of the transposed convolution)
 hipError_t filter_flip_transpose(const void* w, void* wt, int cout, int cin, int r, int s, int dtype,
                                  hipStream_t st);
+
+// Sub-filter of one residue class of a strided data gradient (see dgrad_split.h), written at
+// wt + part.wt_offset.
+hipError_t filter_gather_transpose(const void* w, void* wt, int cout, int cin, int r, int s, int stride,
+                                   const DgradPart& part, int dtype, hipStream_t st);
 
 // Batch norm over rows x c (NHWC flattened).  workspace: bn_workspace_bytes(c).
 // x, res, y, dy, dx, g_out: dtype; gamma, beta, mean, istd, dgamma, dbeta: fp32.

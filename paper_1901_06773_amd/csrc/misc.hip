@@ -4,6 +4,7 @@
 // axis of NHWC and use fixed-order reductions.
 #include "kernels.h"
 #include "dtype.h"
+#include "dgrad_split.h"
 
 namespace acc {
 namespace {
@@ -36,6 +37,30 @@ __global__ __launch_bounds__(256) void flip_transpose_kernel(const T* __restrict
   for (int i = ty; i < 32; i += 8) {
     const int ci = ci0 + i, co = co0 + tx;
     if (ci < cin && co < cout) wt[((size_t)ci * r * s + tap) * cout + co] = tile[tx][i];
+  }
+}
+
+// wt[ci][r'][t'][co] = w[co][r0 + (nr-1-r')*step][t0 + (ns-1-t')*step][ci]: the sub-filter of one
+// residue class of a strided data gradient; same tiling as above.
+template <class T>
+__global__ __launch_bounds__(256) void gather_transpose_kernel(const T* __restrict__ w,
+                                                               T* __restrict__ wt, int cout, int cin,
+                                                               int r, int s, int nr, int ns, int r0,
+                                                               int t0, int step) {
+  __shared__ T tile[32][33];
+  const int tap = blockIdx.z;                       // r'*ns + t' of the output
+  const int kr = r0 + (nr - 1 - tap / ns) * step, kt = t0 + (ns - 1 - tap % ns) * step;
+  const int src_tap = kr * s + kt;
+  const int co0 = blockIdx.y * 32, ci0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    const int co = co0 + i, ci = ci0 + tx;
+    tile[i][tx] = (co < cout && ci < cin) ? w[((size_t)co * r * s + src_tap) * cin + ci] : T(0);
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int ci = ci0 + i, co = co0 + tx;
+    if (ci < cin && co < cout) wt[((size_t)ci * nr * ns + tap) * cout + co] = tile[tx][i];
   }
 }
 
@@ -294,6 +319,20 @@ hipError_t filter_flip_transpose(const void* w, void* wt, int cout, int cin, int
   if (grid.y > 65535) return hipErrorInvalidValue;
   ACC_DISPATCH(dtype, hipLaunchKernelGGL(flip_transpose_kernel<T>, grid, dim3(256), 0, st, (const T*)w, (T*)wt, cout,
                                          cin, r, s));
+  return hipGetLastError();
+}
+
+hipError_t filter_gather_transpose(const void* w, void* wt, int cout, int cin, int r, int s, int stride,
+                                   const DgradPart& pt, int dtype, hipStream_t st) {
+  if (!w || !wt || cout <= 0 || cin <= 0 || r <= 0 || s <= 0 || stride <= 0 || pt.nr <= 0 || pt.ns <= 0 ||
+      pt.r0 < 0 || pt.t0 < 0 || pt.r0 + (pt.nr - 1) * stride >= r || pt.t0 + (pt.ns - 1) * stride >= s ||
+      pt.nr * pt.ns > 65535)
+    return hipErrorInvalidValue;
+  const dim3 grid((cin + 31) / 32, (cout + 31) / 32, pt.nr * pt.ns);
+  if (grid.y > 65535) return hipErrorInvalidValue;
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(gather_transpose_kernel<T>, grid, dim3(256), 0, st, (const T*)w,
+                                         (T*)((char*)wt + pt.wt_offset), cout, cin, r, s, pt.nr, pt.ns, pt.r0,
+                                         pt.t0, stride));
   return hipGetLastError();
 }
 

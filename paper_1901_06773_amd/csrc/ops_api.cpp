@@ -22,7 +22,9 @@ inline int status(hipError_t e) { return e == hipSuccess ? ACC_OK : (e == hipErr
 extern "C" size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, int r, int s, int stride, int pad) {
   if (!conv_ok(n, h, w, cin, cout, r, s, stride, pad)) return 0;
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(w, s, stride, pad);
-  return al256(wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s)) + al256((size_t)cout * cin * r * s * sizeof(float));
+  // the sub-filters of a strided data gradient are aligned one by one
+  return al256(wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s)) + al256((size_t)cout * cin * r * s * sizeof(float)) +
+         (stride > 1 ? kMaxDgradParts * 256 : 0);
 }
 
 extern "C" int acc_op_conv_fwd(const void* x, const void* w, void* y, int n, int h, int wd, int cin, int cout,
@@ -41,14 +43,39 @@ extern "C" int acc_op_conv_dgrad(const void* dy, const void* w, void* dx, int n,
                                  int r, int s, int stride, int pad, int accumulate, void* workspace,
                                  size_t workspace_bytes, int dtype, void* stream) {
   if (!dy || !w || !dx || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
-  if (stride > 1 && (r > 1 || pad > 0)) return ACC_EINVAL;   // strided data gradient: 1x1 only
+  hipStream_t st = (hipStream_t)stream;
+  const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
+  hipError_t e;
+  if (stride > 1 && (r > 1 || pad > 0)) {
+    // one stride-1 convolution per residue class of the dx position
+    DgradPart parts[kMaxDgradParts];
+    bool covers_all = false;
+    size_t wt_bytes = 0;
+    const int np = dgrad_split(h, wd, cin, cout, r, s, stride, pad, (int)dt_size(dtype), parts, &covers_all, &wt_bytes);
+    if (np < 0 || !workspace || workspace_bytes < wt_bytes) return ACC_EINVAL;
+    if (!covers_all && !accumulate) {
+      const size_t bytes = (size_t)n * h * wd * cin * dt_size(dtype);
+      if (bytes % 4) return ACC_EINVAL;
+      if ((e = fill_zero((float*)dx, bytes / 4, st)) != hipSuccess) return status(e);
+    }
+    for (int i = 0; i < np; ++i) {
+      const DgradPart& pt = parts[i];
+      if ((e = filter_gather_transpose(w, workspace, cout, cin, r, s, stride, pt, dtype, st)) != hipSuccess) return status(e);
+      ConvGeom g{};
+      g.in = dy; g.w = (const char*)workspace + pt.wt_offset; g.out = dx; g.dtype = dtype;
+      g.n_img = n; g.h = ho; g.wd = wo; g.c = cout; g.n_out = cin;
+      g.p = pt.p; g.q = pt.q; g.r = pt.nr; g.s = pt.ns; g.stride = 1; g.pad = pt.pad_y; g.pad_dx = pt.pad_x - pt.pad_y;
+      g.out_h = h; g.out_w = wd; g.out_stride = stride; g.out_y0 = pt.y0; g.out_x0 = pt.x0;
+      g.accumulate = accumulate;
+      if ((e = conv_igemm(g, st)) != hipSuccess) return status(e);
+    }
+    return ACC_OK;
+  }
   const size_t filt = al256((size_t)cout * cin * r * s * sizeof(float));
   if (!workspace || workspace_bytes < filt) return ACC_EINVAL;
-  hipStream_t st = (hipStream_t)stream;
   void* wt = workspace;
-  hipError_t e = filter_flip_transpose(w, wt, cout, cin, r, s, dtype, st);
+  e = filter_flip_transpose(w, wt, cout, cin, r, s, dtype, st);
   if (e != hipSuccess) return status(e);
-  const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
   ConvGeom g{};
   g.in = dy; g.w = wt; g.out = dx; g.dtype = dtype;
   g.n_img = n; g.h = ho; g.wd = wo; g.c = cout; g.n_out = cin;

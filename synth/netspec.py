@@ -88,6 +88,17 @@ def _bottleneck(net: NetSpec, src: int, cin: int, planes: int, stride: int,
     return net.add(Layer(RELU, in0=d, cin=cout, cout=cout))
 
 
+def _basic_block(net: NetSpec, src: int, cin: int, planes: int, stride: int, project: bool) -> int:
+    """Two 3x3 convolutions (the first carries the stride), identity or 1x1 projection shortcut."""
+    shortcut = src
+    if project:
+        shortcut = _conv_bn(net, src, cin, planes, 1, stride, 0, relu=False)
+    a = _conv_bn(net, src, cin, planes, 3, stride, 1, relu=True)
+    b = _conv_bn(net, a, planes, planes, 3, 1, 1, relu=False)
+    d = net.add(Layer(ADD, in0=b, in1=shortcut, cin=planes, cout=planes))
+    return net.add(Layer(RELU, in0=d, cin=planes, cout=planes))
+
+
 def _head(net: NetSpec, src: int, cin: int, classes: int) -> None:
     g = net.add(Layer(GAP, in0=src, cin=cin, cout=cin))
     f = net.add(Layer(FC, in0=g, cin=cin, cout=classes))
@@ -105,12 +116,14 @@ def bottleneck_unit(cin: int = 64, planes: int = 16, hw: int = 16, classes: int 
 
 
 def resnet(blocks=(3, 4, 6, 3), in_c: int = 3, in_hw: int = 224, classes: int = 1000,
-           width: int = 64, variant: str = "v1", name: str = "") -> NetSpec:
-    """ImageNet-style bottleneck ResNet: 7x7/2 stem, 3x3/2 max-pool, four stages of
-    bottleneck blocks (projection shortcut on the first block of every stage),
-    global average pooling, FC, softmax cross-entropy.  variant "v1" puts the
-    stride of a down-sampling block on its first 1x1 convolution, "v1.5" on the 3x3."""
-    assert variant in ("v1", "v1.5")
+           width: int = 64, variant: str = "v1", name: str = "", block: str = "bottleneck") -> NetSpec:
+    """ImageNet-style ResNet: 7x7/2 stem, 3x3/2 max-pool, four stages of blocks, global
+    average pooling, FC, softmax cross-entropy.  block "bottleneck": 1x1-3x3-1x1 blocks with
+    four times wider output, projection shortcut on the first block of every stage; variant
+    "v1" puts the stride of a down-sampling block on its first 1x1 convolution, "v1.5" on the
+    3x3.  block "basic" (the 18- and 34-layer networks): two 3x3 convolutions per block,
+    projection shortcut only where the shape changes."""
+    assert variant in ("v1", "v1.5") and block in ("bottleneck", "basic")
     net = NetSpec(name or f"resnet_{'-'.join(map(str, blocks))}_w{width}", in_c, in_hw, in_hw, classes)
     x = _conv_bn(net, -1, in_c, width, 7, 2, 3, relu=True)
     x = net.add(Layer(MAXPOOL, in0=x, cin=width, cout=width, r=3, s=3, stride=2, pad=1))
@@ -119,10 +132,22 @@ def resnet(blocks=(3, 4, 6, 3), in_c: int = 3, in_hw: int = 224, classes: int = 
         planes = width << stage
         for b in range(nblk):
             stride = 2 if (stage > 0 and b == 0) else 1
-            x = _bottleneck(net, x, cin, planes, stride, project=(b == 0), variant=variant)
-            cin = planes * 4
+            if block == "basic":
+                x = _basic_block(net, x, cin, planes, stride, project=(stride != 1 or cin != planes))
+                cin = planes
+            else:
+                x = _bottleneck(net, x, cin, planes, stride, project=(b == 0), variant=variant)
+                cin = planes * 4
     _head(net, x, cin, classes)
     return net
+
+
+def resnet18(**kw) -> NetSpec:
+    return resnet((2, 2, 2, 2), name="resnet18", block="basic", **kw)
+
+
+def resnet34(**kw) -> NetSpec:
+    return resnet((3, 4, 6, 3), name="resnet34", block="basic", **kw)
 
 
 def resnet50(**kw) -> NetSpec:

@@ -82,7 +82,18 @@ def test_conv_fwd(case):
     close(nchw(y.cpu().numpy()), ref, f"conv_fwd {case}")
 
 
-@pytest.mark.parametrize("case", [c for c in CONV_CASES if c[6] == 1 or c[5] == 1])
+STRIDED_DGRAD_CASES = [  # data gradient cut by the residue of the dx position
+    (2, 16, 16, 64, 64, 3, 2, 1),      # the down-sampling 3x3 of the basic-block / v1.5 networks
+    (3, 15, 13, 32, 64, 3, 2, 1),      # odd sizes: the residue classes differ in size
+    (2, 14, 14, 64, 32, 3, 2, 0),      # no padding: row and column paddings of the parts differ
+    (2, 12, 12, 32, 32, 2, 2, 0),      # 2x2 stride 2: every part is a 1x1
+    (2, 17, 17, 32, 32, 5, 3, 2),      # stride 3, nine parts
+    (2, 16, 16, 20, 24, 3, 2, 1),      # per-element loader
+    (2, 13, 13, 32, 32, 1, 3, 0),      # 1x1 stride 3 through the same split (most classes empty)
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES + STRIDED_DGRAD_CASES)
 @pytest.mark.parametrize("accumulate", [False, True])
 def test_conv_dgrad(case, accumulate):
     n, h, w, cin, cout, r, stride, pad = case
@@ -187,7 +198,7 @@ def test_bad_arguments_are_rejected():
         b.op_conv_fwd(x, w, y, 1, 3)        # pad >= r
     ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(b.AccError):
-        b.op_conv_dgrad(y, w, x, 2, 1, ws)  # strided 3x3 data gradient is not supported
+        b.op_conv_dgrad(y, w, torch.zeros(1, 14, 14, 8, device="cuda"), 4, 2, ws)  # 3x3 stride 4 pad 2: not supported
 
 
 # ------------------------------------------------------------------ full-size layers, sampled

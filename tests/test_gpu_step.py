@@ -49,6 +49,9 @@ NETS = {
     "mini_resnet_w8": (lambda: S.resnet((1, 2), in_hw=32, classes=10, width=8), 3),
     "mini_resnet_w32": (lambda: S.resnet((1, 1, 2, 1), in_hw=64, classes=100, width=32), 5),
     "wide_chain": (wide_chain, 6),
+    # strided 3x3 convolutions with a data gradient: basic blocks (18/34-layer style) and v1.5 strides
+    "mini_resnet_basic": (lambda: S.resnet((2, 1, 1), in_hw=48, classes=10, width=32, block="basic"), 3),
+    "mini_resnet_v15": (lambda: S.resnet((1, 2), in_hw=32, classes=10, width=8, variant="v1.5"), 3),
 }
 
 
@@ -437,6 +440,14 @@ def test_config_resnet152_under_8_gib_at_twice_the_resident_minibatch():
     """configs[3]: ResNet-152 under 8 GiB at minibatch 64 (the resident maximum is 46)."""
     plan, out = _budgeted_vs_resident(S.resnet152(), 64, 8 * GiB, expect_swaps=True)
     assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 2 * GiB
+
+
+def test_resnet34_under_4_gib_swaps_and_keeps_the_bits():
+    """The basic-block network of the paper's Table 1 (strided 3x3 data gradients) at its full
+    input size: minibatch 192 needs 5.7 GiB resident; under 4 GiB the planner swaps, and the
+    weights after two steps are those of the resident run, bit for bit."""
+    plan, out = _budgeted_vs_resident(S.resnet34(), 192, 4 * GiB, expect_swaps=True)
+    assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 0
 
 
 def test_config_resnet152_bf16_under_24_gib():

@@ -16,6 +16,7 @@ NETS = {
     "config1_unit": lambda: S.bottleneck_unit(),                      # BASELINE configs[0]
     "mini_resnet_v1": lambda: S.resnet((1, 2), in_hw=20, classes=7, width=4),
     "mini_resnet_v15": lambda: S.resnet((2, 1), in_hw=18, classes=5, width=4, variant="v1.5"),
+    "mini_resnet_basic": lambda: S.resnet((2, 1), in_hw=20, classes=6, width=4, block="basic"),
 }
 
 
@@ -190,6 +191,9 @@ def test_resnet_specs_match_published_parameter_counts():
     assert S.param_count(S.resnet50()) == 25_557_032
     assert S.param_count(S.resnet101()) == 44_549_160
     assert S.param_count(S.resnet152()) == 60_192_808
+    # the basic-block networks (two 3x3 convolutions per block): 11.69 M / 21.80 M
+    assert S.param_count(S.resnet18()) == 11_689_512
+    assert S.param_count(S.resnet34()) == 21_797_672
     net = S.bottleneck_unit()
     assert [l.kind for l in net.layers][:11] == [S.CONV, S.BN, S.RELU, S.CONV, S.BN, S.RELU,
                                                   S.CONV, S.BN, S.ADD, S.RELU, S.GAP]

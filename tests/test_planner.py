@@ -78,9 +78,20 @@ def test_malformed_networks_are_rejected():
     arr[-1, 0] = S.GAP                                 # no loss at the end
     with pytest.raises(b.AccError):
         b.Context(arr, (64, 16, 16))
-    v15 = S.resnet((1, 1), in_hw=32, width=8, variant="v1.5")   # strided 3x3 needs a data gradient
+    ctx_of(S.resnet((1, 1), in_hw=32, width=8, variant="v1.5"))      # strided 3x3 with a data gradient: fine
+    # a 3x3 convolution with stride 4 and padding 2 would need a negatively padded part
+    net = S.NetSpec("odd_stride", 8, 16, 16, 10)
+    a = net.add(S.Layer(S.CONV, in0=-1, cin=8, cout=8, r=1, s=1, stride=1, pad=0))
+    a = net.add(S.Layer(S.BN, in0=a, cin=8, cout=8))
+    a = net.add(S.Layer(S.RELU, in0=a, cin=8, cout=8))
+    a = net.add(S.Layer(S.CONV, in0=a, cin=8, cout=8, r=3, s=3, stride=4, pad=2))
+    a = net.add(S.Layer(S.BN, in0=a, cin=8, cout=8))
+    a = net.add(S.Layer(S.RELU, in0=a, cin=8, cout=8))
+    a = net.add(S.Layer(S.GAP, in0=a, cin=8, cout=8))
+    a = net.add(S.Layer(S.FC, in0=a, cin=8, cout=10))
+    net.add(S.Layer(S.SOFTMAX_CE, in0=a, cin=10, cout=1))
     with pytest.raises(b.AccError) as e:
-        ctx_of(v15)
+        ctx_of(net)
     assert "strided" in str(e.value)
 
 
@@ -130,7 +141,8 @@ def test_memory_stays_under_the_figures_the_paper_prints_for_caffe():
     assert s["bytes_maps"] == 32 * per_image == 32 * 171_614_112
 
 
-@pytest.mark.parametrize("name,gmacs", [("resnet50", PUB["resnet50_gmacs"]), ("resnet101", PUB["resnet101_gmacs"]),
+@pytest.mark.parametrize("name,gmacs", [("resnet18", PUB["resnet18_gmacs"]), ("resnet34", PUB["resnet34_gmacs"]),
+                                        ("resnet50", PUB["resnet50_gmacs"]), ("resnet101", PUB["resnet101_gmacs"]),
                                         ("resnet152", PUB["resnet152_gmacs"])])
 def test_flops_match_the_published_multiply_adds(name, gmacs):
     """Forward multiply-adds per 224x224 image (convolutions and the FC layer)."""
