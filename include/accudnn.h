@@ -224,6 +224,20 @@ typedef struct {
 int acc_get_instr_count(const acc_ctx* ctx);
 int acc_get_instr(const acc_ctx* ctx, int index, acc_instr* out);
 
+/* One entry per instruction of the current plan, in issue order: when it runs on its own
+ * stream, in seconds after the start of the iteration.  which = 0: as Algorithm 1's
+ * simulation predicts with the current cost model; which = 1: as observed in the last
+ * train_step that ran with profiling level 1 or 3 (events around every step and copy, read
+ * against the first event of the iteration on the compute stream; input loads are not timed
+ * and report -1 / -1).  Returns the number of entries, ACC_EINVAL if max_entries is too small,
+ * ACC_ESTATE if there is no plan resp. no profiled step. */
+typedef struct {
+  int32_t op, arg;          /* as in acc_instr                                            */
+  uint64_t bytes;           /* copies: bytes moved; compute steps: 0                      */
+  double t_start, t_end;
+} acc_timeline_entry;
+int acc_get_timeline(acc_ctx* ctx, int which, acc_timeline_entry* out, int max_entries);
+
 /* ---- execution --------------------------------------------------------------------- */
 /* One forward / backward / SGD step at the planned minibatch.  images: fp32 NCHW,
  * pinned host (ACC_LOC_HOST) or device (ACC_LOC_DEVICE); labels: int32, host.  Blocks

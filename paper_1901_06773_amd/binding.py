@@ -92,6 +92,11 @@ class acc_instr(C.Structure):
                                           "reserved")]
 
 
+class acc_timeline_entry(C.Structure):
+    _fields_ = [("op", C.c_int32), ("arg", C.c_int32), ("bytes", C.c_uint64), ("t_start", C.c_double),
+                ("t_end", C.c_double)]
+
+
 class acc_kernel_profile(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("reserved", C.c_int32),
                 ("ms", C.c_double), ("flops", C.c_double)]
@@ -124,6 +129,7 @@ _PROTOS = {
     "acc_get_step_io": (_I, [_VP, _I, C.POINTER(C.c_int32), _I, C.POINTER(C.c_int32), _I]),
     "acc_get_instr_count": (_I, [_VP]),
     "acc_get_instr": (_I, [_VP, _I, C.POINTER(acc_instr)]),
+    "acc_get_timeline": (_I, [_VP, _I, C.POINTER(acc_timeline_entry), _I]),
     "acc_train_step": (_I, [_VP, _VP, _I, _VP, _F, C.POINTER(_F)]),
     "acc_get_stats": (_I, [_VP, C.POINTER(acc_stats)]),
     "acc_set_profiling": (_I, [_VP, _I]),
@@ -318,6 +324,16 @@ class Context:
             self._check(_lib.acc_get_instr(self._h, i, C.byref(ins)))
             out.append({n: getattr(ins, n) for n, _ in ins._fields_ if n != "reserved"})
         return out
+
+    def timeline(self, observed: bool = False) -> list:
+        """One dict per instruction of the plan (op, arg, bytes, t_start, t_end in seconds after the
+        start of the iteration): predicted by the planner's simulation, or observed in the last
+        train_step that ran with profiling level 1 or 3."""
+        n = self._check(_lib.acc_get_instr_count(self._h))
+        arr = (acc_timeline_entry * max(n, 1))()
+        n = self._check(_lib.acc_get_timeline(self._h, 1 if observed else 0, arr, n))
+        return [dict(op=arr[i].op, arg=arr[i].arg, bytes=arr[i].bytes, t_start=arr[i].t_start, t_end=arr[i].t_end)
+                for i in range(n)]
 
     # ---- execution
     def train_step(self, images, labels: np.ndarray, lr: float) -> float:

@@ -51,6 +51,7 @@ struct acc_ctx {
   std::vector<hipEvent_t> ev_step, ev_d2h, ev_h2d;
   std::vector<hipEvent_t> ev_window;   // one per kStepWindow compute steps: bounds the host's run-ahead
   std::vector<hipEvent_t> prof_a, prof_b, prof_copy_a, prof_copy_b;
+  std::vector<double> obs_start, obs_end;   // per instruction of the plan that ran, seconds
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
   bool profiling = false;
   bool kernel_profiling = false;
@@ -336,6 +337,7 @@ int install_plan(acc_ctx* c, Plan&& p, acc_plan_summary* out, double t0) {
     for (auto& e : c->ev_window) HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
   }
   c->plan = std::move(p);
+  c->obs_start.clear(); c->obs_end.clear();   // observations belong to the plan they ran under
   c->stats = acc_stats{};
   if (out) {
     const Plan& P = c->plan;
@@ -830,8 +832,43 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
       HIPCHK(c, hipEventElapsedTime(&ms, c->prof_copy_a[idx], c->prof_copy_b[idx]));
       (in.op == I_OFFLOAD ? c->stats.d2h_ms : c->stats.h2d_ms) += ms;
     }
+    // observed timeline: every timed instruction against the first event of the iteration
+    c->obs_start.assign(P.instrs.size(), -1.0);
+    c->obs_end.assign(P.instrs.size(), -1.0);
+    for (size_t i = 0; i < P.instrs.size(); ++i) {
+      const Instr& in = P.instrs[i];
+      hipEvent_t a = nullptr, b = nullptr;
+      if (in.op == I_COMPUTE) { a = c->prof_a[in.arg]; b = c->prof_b[in.arg]; }
+      else if (in.op == I_OFFLOAD) { a = c->prof_copy_a[in.seq]; b = c->prof_copy_b[in.seq]; }
+      else if (in.op == I_PREFETCH) { a = c->prof_copy_a[P.n_d2h + in.seq]; b = c->prof_copy_b[P.n_d2h + in.seq]; }
+      if (!a) continue;
+      float ms0 = 0, ms1 = 0;
+      HIPCHK(c, hipEventElapsedTime(&ms0, c->ev_begin, a));
+      HIPCHK(c, hipEventElapsedTime(&ms1, c->ev_begin, b));
+      c->obs_start[i] = ms0 * 1e-3;
+      c->obs_end[i] = ms1 * 1e-3;
+    }
   }
   return ACC_OK;
+}
+
+extern "C" int acc_get_timeline(acc_ctx* c, int which, acc_timeline_entry* out, int max_entries) {
+  if (!c || !out || (which != 0 && which != 1)) return ACC_EINVAL;
+  const Plan& P = c->plan;
+  if (!P.valid) return c->fail(ACC_ESTATE, "call acc_plan_swaps first");
+  const size_t n = P.instrs.size();
+  if ((size_t)(max_entries < 0 ? 0 : max_entries) < n) return c->fail(ACC_EINVAL, "max_entries is smaller than the instruction count");
+  const std::vector<double>& t0 = which == 0 ? P.i_start : c->obs_start;
+  const std::vector<double>& t1 = which == 0 ? P.i_end : c->obs_end;
+  if (t0.size() != n || t1.size() != n)
+    return c->fail(ACC_ESTATE, which == 0 ? "the plan has not been simulated" : "no profiled step of this plan yet");
+  for (size_t i = 0; i < n; ++i) {
+    const Instr& in = P.instrs[i];
+    out[i].op = in.op; out[i].arg = in.arg;
+    out[i].bytes = in.op == I_COMPUTE ? 0 : P.tbytes[in.arg];
+    out[i].t_start = t0[i]; out[i].t_end = t1[i];
+  }
+  return (int)n;
 }
 
 extern "C" int acc_get_stats(acc_ctx* c, acc_stats* out) {

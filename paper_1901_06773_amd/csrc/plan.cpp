@@ -361,10 +361,16 @@ void simulate(const Graph& g, const CostModel& cm, Plan* plan) {
   double t_c = 0, t_o = 0, t_i = 0, stall = 0, comp = 0;
   // waits already passed still bound a stream from below: keep the running maximum
   double c_floor = 0, i_floor = 0;
+  P.i_start.assign(P.instrs.size(), 0); P.i_end.assign(P.instrs.size(), 0);
+  size_t ii = 0;
   for (const Instr& in : P.instrs) {
+    double& i_start = P.i_start[ii];
+    double& i_end = P.i_end[ii];
+    ++ii;
     switch (in.op) {
       case I_LOAD_INPUT: {
         const double end = t_i + cm.h2d_time(P.tbytes[in.arg]);
+        i_start = t_i; i_end = end;
         h2d_t[in.seq] = end;
         t_i = end;
         break;
@@ -380,6 +386,7 @@ void simulate(const Graph& g, const CostModel& cm, Plan* plan) {
         stall += start - t_c;
         P.t_start[j] = start;
         P.t_end[j] = start + cost;
+        i_start = start; i_end = start + cost;
         t_c = start + cost;
         comp += cost;
         break;
@@ -387,6 +394,7 @@ void simulate(const Graph& g, const CostModel& cm, Plan* plan) {
       case I_OFFLOAD: {
         const double start = std::max(t_o, P.t_end[in.wait_step]);
         const double end = start + cm.d2h_time(P.tbytes[in.arg]);
+        i_start = start; i_end = end;
         d2h_t[in.seq] = end;
         t_o = end;
         break;
@@ -396,6 +404,7 @@ void simulate(const Graph& g, const CostModel& cm, Plan* plan) {
         if (in.wait_d2h >= 0) i_floor = std::max(i_floor, d2h_t[in.wait_d2h]);
         const double start = std::max(t_i, i_floor);
         const double end = start + cm.h2d_time(P.tbytes[in.arg]);
+        i_start = start; i_end = end;
         h2d_t[in.seq] = end;
         t_i = end;
         break;

@@ -61,6 +61,7 @@ struct Plan {
   int n_swapped = 0;
   // simulation results
   std::vector<double> t_cost, t_ready, t_start, t_end;
+  std::vector<double> i_start, i_end;      // per instruction, on its own stream
   double t_iter = 0, t_stall = 0, t_compute = 0;
 };
 

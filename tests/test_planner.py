@@ -511,3 +511,37 @@ def test_adaptive_learning_rate_closed_forms():
     q = 4.2
     assert (1 - a * c) ** q == pytest.approx(1 - b.adaptive_lr(a, c, q) * c, rel=1e-13)
     assert np.isnan(b.adaptive_lr(2.0, 0.7, 2.0)) and np.isnan(b.adaptive_lr(0.1, 0.0, 2.0))
+
+
+# ------------------------------------------------------------ timeline of the simulation
+@pytest.mark.parametrize("budget_gib", [64, 3, 2])
+def test_simulated_timeline_is_consistent_with_the_plan(budget_gib):
+    """The per-instruction times of Algorithm 1's simulation: every instruction starts after
+    what it waits for and after its predecessor on its stream; compute entries are the
+    t_start / t_end of the steps; the last end is the predicted iteration; replaying
+    allocations and releases along those times never exceeds the planned pool peak, ends
+    empty, and has moved every swapped byte out and back."""
+    from paper_1901_06773_amd import validate as V
+    b = B()
+    net = S.resnet50()
+    ctx = ctx_of(net)
+    s = ctx.plan_swaps(64, budget_gib << 30, b.PLAN_DYNAMIC)
+    assert (s["n_swapped"] > 0) == (budget_gib < 64)
+    tl = ctx.timeline()
+    assert len(tl) == s["n_instr"]
+    assert V.dependency_violations(ctx, tl, slack=0.0) == []
+    for e in tl:
+        if e["op"] == V.OP_COMPUTE:
+            info = ctx.step_info(e["arg"])
+            assert (e["t_start"], e["t_end"]) == (info["t_start"], info["t_end"])
+    assert max(e["t_end"] for e in tl) == pytest.approx(s["t_iter"], rel=1e-12)
+    summ = V.timeline_summary(tl)
+    assert summ["t_compute"] == pytest.approx(s["t_compute"], rel=1e-9)
+    mem = V.memory_curve(ctx, observed=False, points=200)
+    assert 0.5 * (s["peak_bytes"] - s["static_bytes"]) < mem["peak_dynamic_bytes"] <= s["peak_bytes"] - s["static_bytes"]
+    last = mem["series"][-1]
+    assert last["pool_bytes"] == 0 and last["bytes_out"] == last["bytes_in"] == s["bytes_swapped"]
+    # a planning-only context has nothing observed
+    with pytest.raises(b.AccError) as e:
+        ctx.timeline(observed=True)
+    assert e.value.status == b.ACC_ESTATE
