@@ -267,6 +267,37 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
     return true;
   };
 
+  // eager prefetch: swapped maps in the order of their first use in backward
+  std::vector<int> eager_order;
+  size_t next_eager = 0;
+  if (opt.eager_headroom) {
+    for (int t = 0; t < nt; ++t)
+      if (P.swapped[t]) eager_order.push_back(t);
+    std::stable_sort(eager_order.begin(), eager_order.end(),
+                     [&](int a, int b) { return g.tensors[a].first_bwd < g.tensors[b].first_bwd; });
+  }
+  auto eager_prefetch = [&]() {
+    while (next_eager < eager_order.size()) {
+      const int t = eager_order[next_eager];
+      if (st[t] == TS_RESIDENT || st[t] == TS_DEAD) { ++next_eager; continue; }   // came back with its step
+      if (st[t] != TS_OFFLOADED) break;
+      if (live + P.tbytes[t] + opt.eager_headroom > cap) break;
+      int ds, dd;
+      if (!take(t, true, &ds, &dd)) break;
+      st[t] = TS_RESIDENT;
+      P.off2[t] = cur_off[t];
+      --to_prefetch;
+      Instr pf;
+      pf.op = I_PREFETCH; pf.arg = t; pf.seq = P.n_h2d++;
+      pf.wait_step = ds;
+      pf.wait_d2h = std::max(dd, d2h_of[t]);
+      h2d_of[t] = pf.seq;
+      if (ds >= 0) step_record[ds] = 1;
+      P.instrs.push_back(pf);
+      ++next_eager;
+    }
+  };
+
   int ahead = 0;
   int seen_c_d2h = -1, seen_c_h2d = -1;
 
@@ -284,7 +315,7 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
       }
       ++ahead;
     }
-    if (opt.lookahead)
+    if (opt.lookahead && !opt.eager_headroom)
       while (ahead < ns && ahead >= g.n_fwd && to_prefetch > 0) {
         if (!alloc_step(ahead, false)) break;
         ++ahead;
@@ -324,6 +355,7 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
         st[t] = TS_DEAD;
       }
     }
+    if (opt.eager_headroom && j + 1 >= g.n_fwd && to_prefetch > 0) eager_prefetch();
   }
   *why = "";
   // the swap-in stream waits in order too: drop waits it has already passed
@@ -443,9 +475,10 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
     out->mode = mode;
     return ACC_OK;
   }
-  // A swap set is laid out twice, with plain first fit and with first fit that passes over
-  // blocks still being copied out (by the model's clock), and the layout with the shorter
-  // predicted iteration is kept.
+  // A swap set is laid out three times: with plain first fit, with first fit that passes over
+  // blocks still being copied out (by the model's clock), and with eager prefetch on top of
+  // that; the layout with the shortest predicted iteration is kept.
+  const size_t headroom = live_peak(g, k, all);   // working set of the steps: peak with every map away
   auto build_sim = [&](const std::vector<uint8_t>& sw, Plan* p, std::string* w) -> bool {
     Plan pa, pb;
     std::string wa, wb;
@@ -455,8 +488,18 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
     timed.clock = &cm;
     const bool okb = build_plan(g, k, budget, sw, timed, &pb, &wb);
     if (okb) simulate(g, cm, &pb);
-    if (!oka && !okb) { *w = wa; return false; }
-    if (okb && (!oka || pb.t_iter < pa.t_iter)) *p = std::move(pb); else *p = std::move(pa);
+    // third layout: maps come back as early as the pool has room beside the working set
+    Plan pc;
+    std::string wc;
+    PlanOptions eager = timed;
+    eager.eager_headroom = headroom;
+    const bool okc = headroom > 0 && build_plan(g, k, budget, sw, eager, &pc, &wc);
+    if (okc) simulate(g, cm, &pc);
+    if (!oka && !okb && !okc) { *w = wa; return false; }
+    Plan* bestp = nullptr;
+    for (Plan* q : {oka ? &pa : nullptr, okb ? &pb : nullptr, okc ? &pc : nullptr})
+      if (q && (!bestp || q->t_iter < bestp->t_iter)) bestp = q;
+    *p = std::move(*bestp);
     return true;
   };
   if (mode == ACC_PLAN_NAIVE_ALL) {

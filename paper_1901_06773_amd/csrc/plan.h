@@ -72,6 +72,10 @@ struct PlanOptions {
   // is passed over while any other free block fits, so that an allocation does not wait for
   // a copy when untouched memory is at hand.  Without: plain first fit.
   const CostModel* clock = nullptr;
+  // > 0: in backward, bring swapped maps back as soon as the pool has room for the map plus
+  // this many bytes (kept free for the working set of the steps in between), in the order
+  // of their first use, instead of running the allocations of whole steps ahead.
+  size_t eager_headroom = 0;
 };
 
 // Builds instruction list and placement for a fixed swap set.  Returns false (and why)
