@@ -16,6 +16,8 @@
 // beats 128x64 and 128x128 everywhere (70.7 / 86 / 98 TFLOP/s against 56 / 76 / 88 and
 // 40 / 61 / 82): with M a multiple of 49 the larger tiles quantise badly over 256 CUs,
 // and four resident workgroups per CU hide the one barrier per chunk.
+#include <cstdlib>
+
 #include "kernels.h"
 #include "dtype.h"
 
@@ -86,16 +88,31 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
   return ((size_t)(img * g.out_h + g.out_y0 + p * g.out_stride) * g.out_w + g.out_x0 + q * g.out_stride) * g.n_out;
 }
 
-// FAST: c a multiple of the chunk (32 fp32 / 64 bf16 channels), NHWC input, at most 32 filter
-// taps.  Otherwise every element is decoded on its own (any c, K tail); used for the
-// 3-channel stem and for tiny layers.
-template <bool FAST, class T>
+// Loaders.  L_FAST and L_DIRECT: c a multiple of the chunk (32 fp32 / 64 bf16 channels), NHWC
+// input, at most 32 filter taps.  L_GENERIC: every element is decoded on its own (any c, K
+// tail); used for the 3-channel stem and for tiny layers.
+//
+// L_DIRECT moves the chunks from global memory straight into LDS (buffer_load_dwordx4 ... lds:
+// a wave's 64 lanes fill 1024 consecutive LDS bytes, eight 128-byte rows), so no staging
+// registers, no LDS store instructions and no zeroing pass: a lane whose tap falls into the
+// padding (or whose row lies beyond M) is given an offset beyond the buffer descriptor's
+// range and the hardware delivers zeros.  Rows are unpadded (pitch 128 bytes); the 16-byte
+// columns of a row are permuted by XOR with the row number (the lane fetches the column that
+// belongs into its slot), which keeps the fragment reads free of bank conflicts.  Two LDS
+// stages: the loads of chunk kc+1 are issued right after the barrier that opens chunk kc
+// and have its whole MFMA work to land.
+enum { L_GENERIC = 0, L_FAST = 1, L_DIRECT = 2 };
+constexpr int LDD = CHUNK_BYTES / 4;          // LDS row pitch of L_DIRECT in words
+
+template <int LOADER, class T>
 __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
                                                      int main_grid) {
+  constexpr bool FAST = LOADER == L_FAST, DIRECT = LOADER == L_DIRECT;
   constexpr int ES = sizeof(T);
   constexpr int BK = CHUNK_BYTES / ES;       // elements of K per chunk
-  __shared__ __attribute__((aligned(16))) float As[2 * BM * LD];
-  __shared__ __attribute__((aligned(16))) float Bs[2 * BN * LD];
+  constexpr int PITCH = DIRECT ? LDD : LD;
+  __shared__ __attribute__((aligned(128))) float As[2 * BM * PITCH];
+  __shared__ __attribute__((aligned(128))) float Bs[2 * BN * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
     // side job: 1024 elements of a weight gradient, parts added in their fixed order
@@ -240,7 +257,98 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     }
   };
 
-  if constexpr (FAST) {
+  if constexpr (DIRECT) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int AI = BM / 32, BI = BN / 32;
+    const int lrow = tid >> 3;                          // row of the lane's LDS slot within a 32-row half
+    const int lcol = (tid & 7) ^ (lrow & 7);            // 16-byte column that belongs into that slot
+    const int margin = g.pad * g.wd + g.pad + g.pad_dx; // pixels; the descriptor starts that far before the tensor
+    constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;           // beyond any descriptor range: reads as zero
+    uint32_t a_voff[AI], a_mask[AI], b_voff[BI];
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const RowPos rp = decode_row(g, m0 + lrow + 32 * i, M);
+      a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * ES) + lcol * 16;
+      uint32_t mask = 0;
+      for (int kr = 0; kr < g.r; ++kr)
+        for (int kt = 0; kt < g.s; ++kt) {
+          const bool ok = rp.ok && (unsigned)(rp.iy0 + kr) < (unsigned)g.h && (unsigned)(rp.ix0 + kt) < (unsigned)g.wd;
+          mask |= (ok ? 1u : 0u) << (kr * g.s + kt);
+        }
+      a_mask[i] = mask;
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int n = n0 + lrow + 32 * i;
+      b_voff[i] = (uint32_t)(n < g.n_out ? n : 0) * (uint32_t)(K * ES) + lcol * 16;   // beyond n_out: filter 0, never stored
+    }
+    const size_t margin_bytes = (size_t)margin * g.c * ES;
+    const size_t a_bytes = margin_bytes + (size_t)g.n_img * g.h * g.wd * g.c * ES;
+    __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(g.in)) - margin_bytes, 0, (int)(uint32_t)a_bytes, 0x00020000);
+    __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void*>(g.w), 0, (int)(uint32_t)((size_t)g.n_out * K * ES), 0x00020000);
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds_a = (uint32_t)(size_t)As + uwave * 1024, lds_b = (uint32_t)(size_t)Bs + uwave * 1024;
+    int kr = 0, kt = 0, c0 = 0;     // tap and channel offset of the chunk whose loads are issued next (uniform)
+    auto issue = [&](int kc, int buf) {
+      const int tap = kr * g.s + kt;
+      const int soff_a = ((kr * g.wd + kt) * g.c + c0) * ES;
+      const int soff_b = kc * CHUNK_BYTES;
+#pragma unroll
+      for (int i = 0; i < AI; ++i) {
+        const uint32_t voff = ((a_mask[i] >> tap) & 1u) ? a_voff[i] : OUTSIDE;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)(size_t)(lds_a + buf * (BM * CHUNK_BYTES) + i * (32 * CHUNK_BYTES)),
+                                                 16, voff, soff_a, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < BI; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(size_t)(lds_b + buf * (BN * CHUNK_BYTES) + i * (32 * CHUNK_BYTES)),
+                                                 16, b_voff[i], soff_b, 0, 0);
+      c0 += BK;
+      if (c0 == g.c) {
+        c0 = 0;
+        if (++kt == g.s) { kt = 0; ++kr; }
+      }
+    };
+    // fragment of a row: 16-byte column c16 sits in slot c16 ^ (row & 7)
+    const int ra_ = wm0 + (lane & 31), rb_ = wn0 + (lane & 31);
+    auto compute_direct = [&](int buf) {
+      const float* as = As + buf * (BM * LDD) + ra_ * LDD;
+      const float* bs = Bs + buf * (BN * LDD) + rb_ * LDD;
+#pragma unroll
+      for (int g8 = 0; g8 < 4; ++g8) {
+        const int c16 = g8 * 2 + (lane >> 5);
+        const float4 af = *reinterpret_cast<const float4*>(as + ((c16 ^ (ra_ & 7)) << 2));
+        const float4 bf = *reinterpret_cast<const float4*>(bs + ((c16 ^ (rb_ & 7)) << 2));
+        if constexpr (ES == 4) {
+          acc = mfma32x32x2(af.x, bf.x, acc);
+          acc = mfma32x32x2(af.y, bf.y, acc);
+          acc = mfma32x32x2(af.z, bf.z, acc);
+          acc = mfma32x32x2(af.w, bf.w, acc);
+        } else {
+          acc = mfma32x32x16bf(af, bf, acc);
+        }
+      }
+    };
+    // The barrier that opens chunk kc says two things: every wave's part of chunk kc has
+    // landed in LDS (each wave waits for its own loads first), and every wave is done with
+    // chunk kc-1, whose stage the loads of chunk kc+1 may now overwrite.
+    issue(0, 0);
+    for (int kc = 0; kc < n_chunks; kc += 2) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads are in LDS
+      __syncthreads();
+      if (kc + 1 < n_chunks) issue(kc + 1, 1);
+      compute_direct(0);
+      if (kc + 1 >= n_chunks) break;
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      if (kc + 2 < n_chunks) issue(kc + 2, 0);
+      compute_direct(1);
+    }
+#endif
+  } else if constexpr (FAST) {
     // Addresses are split into a per-lane 32-bit byte offset that never changes (the row's
     // pixel, shifted by the padding margin so that it is never negative) and a uniform
     // base that moves with the filter tap and the channel chunk, so the K loop spends no
@@ -368,7 +476,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   }
 }
 
-template <bool FAST, class T>
+template <int LOADER, class T>
 hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchProbe* probe) {
   const int tm = (M + BM - 1) / BM, tn = (g.n_out + BN - 1) / BN;
   const long tiles = (long)tm * tn;
@@ -381,7 +489,7 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   }
   if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
   if (probe->before) (void)hipEventRecord(probe->before, st);
-  hipLaunchKernelGGL((igemm_kernel<FAST, T>), dim3((unsigned)(main_grid + side_blocks)), dim3(256), 0, st, g, M, K, tn,
+  hipLaunchKernelGGL((igemm_kernel<LOADER, T>), dim3((unsigned)(main_grid + side_blocks)), dim3(256), 0, st, g, M, K, tn,
                      (int)tiles, main_grid);
   if (probe->after) (void)hipEventRecord(probe->after, st);
   return hipGetLastError();
@@ -391,7 +499,7 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
 
 const char* conv_variant_name(int v) {
   static const char* names[V_COUNT] = {"igemm_kernel<fast>", "igemm_kernel<generic>", "wgrad_kernel<fast>",
-                                       "wgrad_kernel<generic>"};
+                                       "wgrad_kernel<generic>", "igemm_kernel<direct>"};
   return (v >= 0 && v < V_COUNT) ? names[v] : "?";
 }
 
@@ -419,10 +527,28 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   const bool fast = (g.c % (CHUNK_BYTES / es) == 0) && g.r * g.s <= 32 &&
                     ((long)g.n_img * g.h * g.wd + 2L * (g.pad + (g.pad_dx > 0 ? g.pad_dx : 0)) * (g.wd + 1)) * g.c * es < (1L << 32) &&
                     (long)g.n_out * K * es < (1L << 32);
-  probe->variant = fast ? V_IGEMM_FAST : V_IGEMM_GENERIC;
-  if (g.dtype == DT_F32)
-    return fast ? launch<true, float>(g, (int)M, (int)K, st, probe) : launch<false, float>(g, (int)M, (int)K, st, probe);
-  return fast ? launch<true, bf16_t>(g, (int)M, (int)K, st, probe) : launch<false, bf16_t>(g, (int)M, (int)K, st, probe);
+  // The direct loader addresses both operands through buffer descriptors: 32-bit ranges, the
+  // last bytes kept free for the offset that stands for "outside".  ACC_IGEMM_LOADER=fast in
+  // the environment keeps the register-staged loader (for comparisons).
+  static const bool allow_direct = [] {
+    const char* e = getenv("ACC_IGEMM_LOADER");
+    return !(e && e[0] == 'f');
+  }();
+  const long margin_px = (long)g.pad * g.wd + g.pad + g.pad_dx;
+  const bool direct = fast && allow_direct &&
+                      (margin_px + (long)g.n_img * g.h * g.wd) * g.c * es <= 0xFFFFFF00L &&
+                      (long)g.n_out * K * es <= 0xFFFFFF00L &&
+                      (reinterpret_cast<uintptr_t>(g.in) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.w) & 15) == 0;
+  const int loader = direct ? L_DIRECT : fast ? L_FAST : L_GENERIC;
+  probe->variant = direct ? V_IGEMM_DIRECT : fast ? V_IGEMM_FAST : V_IGEMM_GENERIC;
+  if (g.dtype == DT_F32) {
+    if (loader == L_DIRECT) return launch<L_DIRECT, float>(g, (int)M, (int)K, st, probe);
+    if (loader == L_FAST) return launch<L_FAST, float>(g, (int)M, (int)K, st, probe);
+    return launch<L_GENERIC, float>(g, (int)M, (int)K, st, probe);
+  }
+  if (loader == L_DIRECT) return launch<L_DIRECT, bf16_t>(g, (int)M, (int)K, st, probe);
+  if (loader == L_FAST) return launch<L_FAST, bf16_t>(g, (int)M, (int)K, st, probe);
+  return launch<L_GENERIC, bf16_t>(g, (int)M, (int)K, st, probe);
 }
 
 }  // namespace acc
