@@ -499,7 +499,7 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
 
 const char* conv_variant_name(int v) {
   static const char* names[V_COUNT] = {"igemm_kernel<fast>", "igemm_kernel<generic>", "wgrad_kernel<fast>",
-                                       "wgrad_kernel<generic>", "igemm_kernel<direct>"};
+                                       "wgrad_kernel<generic>", "igemm_kernel<direct>", "wgrad_kernel<direct>"};
   return (v >= 0 && v < V_COUNT) ? names[v] : "?";
 }
 

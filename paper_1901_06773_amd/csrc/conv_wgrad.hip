@@ -14,6 +14,8 @@
 // read a stand-in address and are zeroed on the way into LDS), one barrier per chunk.
 // 64x64 tiles measured best on MI355X (ResNet shapes, minibatch 32 / 256: 66 / 91
 // TFLOP/s against 48 / 86 with 128-wide tiles).
+#include <cstdlib>
+
 #include "kernels.h"
 #include "dtype.h"
 
@@ -69,14 +71,24 @@ __device__ __forceinline__ int gather_pixel(const WgradGeom& g, int m, int kr, i
   return (img * g.h + iy) * g.wd + ix;
 }
 
-// FAST: cin % 64 == 0 (a tile's columns lie inside one tap), cout % 4 == 0, byte offsets
-// below 2^32.
-template <bool FAST, class T>
+// L_FAST, L_DIRECT: cin % 64 == 0 (a tile's columns lie inside one tap), cout % 4 == 0, byte
+// offsets below 2^32.  L_DIRECT (fp32 storage only: bf16 operands are widened on their way
+// into LDS, which needs the registers) moves the chunks from global memory straight into LDS
+// (buffer_load_dwordx4 ... lds: a wave fills four 256-byte rows), rows beyond the range,
+// padded taps and columns beyond cout as offsets outside the buffer descriptor, which read as
+// zero.  Rows are unpadded; odd rows hold their two 128-byte halves swapped (the lane fetches
+// the half that belongs into its slot), so that the two rows one MFMA operand is read from
+// lie on different banks.  Two LDS stages, as in the forward kernel's direct loader.
+enum { L_GENERIC = 0, L_FAST = 1, L_DIRECT = 2 };
+
+template <int LOADER, class T>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int J, int tiles_j, int tiles,
                                                      int splits, int chunks_per_split, float* out,
                                                      size_t split_stride, int main_grid) {
-  __shared__ __attribute__((aligned(16))) float As[2 * BKM * LDT];
-  __shared__ __attribute__((aligned(16))) float Bs[2 * BKM * LDT];
+  constexpr bool FAST = LOADER == L_FAST, DIRECT = LOADER == L_DIRECT;
+  constexpr int PITCH = DIRECT ? 64 : LDT;
+  __shared__ __attribute__((aligned(256))) float As[2 * BKM * PITCH];
+  __shared__ __attribute__((aligned(256))) float Bs[2 * BKM * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
     // side job: one 32 x 32 (co, ci) block of one tap of the flipped, transposed filter
@@ -199,7 +211,94 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
     }
   };
 
-  if constexpr (FAST) {
+  if constexpr (DIRECT) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    static_assert(!DIRECT || sizeof(T) == 4, "the direct loader copies raw fp32 rows");
+    // lane -> LDS slot: row tid/16 (+16 on the second pass), 16-byte column tid%16; the slot of
+    // an odd row holds the column of the other half
+    const int row = tid >> 4;
+    const int col4 = (tid & 15) ^ ((row & 1) << 3);
+    const int tap = j0 / g.cin, ci0 = j0 - tap * g.cin;
+    const int kr = tap / g.s, kt = tap - kr * g.s;
+    const bool plain = g.r == 1 && g.s == 1 && g.stride == 1 && g.pad == 0;
+    const bool a_col_ok = co0 + col4 * 4 < g.cout;
+    constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;
+    uint32_t a_lane[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a_lane[i] = (uint32_t)(row + 16 * i) * (uint32_t)(g.cout * 4) + (uint32_t)(co0 + col4 * 4) * 4;
+    const uint32_t b_lane = (uint32_t)(ci0 + col4 * 4) * 4;
+    int r_org[2] = {0, 0}, r_p[2] = {0, 0}, r_q[2] = {0, 0};
+    if (!plain) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int m = chunk_lo * BKM + row + 16 * i;
+        const int pq = g.p * g.q;
+        const int img = m / pq, rem = m - img * pq;
+        r_p[i] = rem / g.q;
+        r_q[i] = rem - r_p[i] * g.q;
+        r_org[i] = img * g.h * g.wd;
+      }
+    }
+    __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void*>(g.dy), 0, (int)(uint32_t)((size_t)Mrows * g.cout * 4), 0x00020000);
+    __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void*>(g.x), 0, (int)(uint32_t)((size_t)g.n_img * g.h * g.wd * g.cin * 4), 0x00020000);
+    typedef __attribute__((address_space(3))) void* lds_ptr;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds_a = (uint32_t)(size_t)As + uwave * 1024, lds_b = (uint32_t)(size_t)Bs + uwave * 1024;
+    // loads of chunk kc (relative to chunk_lo) into stage buf; chunks are issued in order, so the
+    // gathered position advances by BKM rows per call without any division
+    auto issue = [&](int kc, int buf) {
+      const int mbase = (chunk_lo + kc) * BKM;
+      const int soff_a = (int)((uint32_t)mbase * (uint32_t)(g.cout * 4));   // below 2^32 (launcher)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int m = mbase + row + 16 * i;
+        const bool mok = m < Mrows;
+        const uint32_t va = (mok && a_col_ok) ? a_lane[i] : OUTSIDE;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)(size_t)(lds_a + buf * (BKM * 256) + i * (16 * 256)), 16, va,
+                                                 soff_a, 0, 0);
+        int pix = m;
+        if (!plain) {
+          const int iy = r_p[i] * g.stride + kr - g.pad, ix = r_q[i] * g.stride + kt - g.pad;
+          pix = ((unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd) ? r_org[i] + iy * g.wd + ix : -1;
+          r_q[i] += BKM;
+          while (r_q[i] >= g.q) {
+            r_q[i] -= g.q;
+            if (++r_p[i] == g.p) { r_p[i] = 0; r_org[i] += g.h * g.wd; }
+          }
+        }
+        const uint32_t vb = (mok && pix >= 0) ? (uint32_t)pix * (uint32_t)(g.cin * 4) + b_lane : OUTSIDE;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(size_t)(lds_b + buf * (BKM * 256) + i * (16 * 256)), 16, vb,
+                                                 0, 0, 0);
+      }
+    };
+    // operand of MFMA step kk: lanes 0-31 row kk (even), lanes 32-63 row kk+1 (odd: halves swapped)
+    const int half = lane >> 5;
+    const float* a_rd = As + half * 64 + ((wm0 + (lane & 31)) ^ (half << 5));
+    const float* b_rd = Bs + half * 64 + ((wn0 + (lane & 31)) ^ (half << 5));
+    auto compute_direct = [&](int buf) {
+      const float* as = a_rd + buf * (BKM * 64);
+      const float* bs = b_rd + buf * (BKM * 64);
+#pragma unroll
+      for (int kk = 0; kk < BKM; kk += 2) acc = mfma32x32x2(as[kk * 64], bs[kk * 64], acc);
+    };
+    if (n_chunks > 0) {
+      issue(0, 0);
+      for (int kc = 0; kc < n_chunks; kc += 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's part of chunk kc is in LDS
+        __syncthreads();                        // everybody's is, and chunk kc-1 has been read by all
+        if (kc + 1 < n_chunks) issue(kc + 1, 1);
+        compute_direct(0);
+        if (kc + 1 >= n_chunks) break;
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (kc + 2 < n_chunks) issue(kc + 2, 0);
+        compute_direct(1);
+      }
+    }
+#endif
+  } else if constexpr (FAST) {
     // 16 float4 per 64-wide row, 16 rows per pass, 2 passes per operand and chunk
     const int col4 = tid & 15, row = tid >> 4;
     const int tap = j0 / g.cin, ci0 = j0 - tap * g.cin;
@@ -341,9 +440,11 @@ struct WgradCfg {
   int tiles_co, tiles_j, splits, chunks_per_split;
 };
 
-// Depends on the shape only (never on addresses or on the swap plan).  Three workgroups
-// fit a CU (LDS), 768 the chip: the m range is cut into as many parts as keep the launch
-// within that one round, at least 8 chunks of 32 rows each.
+// Depends on the shape only (never on addresses or on the swap plan).  The m range is cut into
+// as many parts as keep the launch within 768 workgroups, three per CU (what the
+// register-staged loader's LDS allows; measured with the direct loader at minibatch 41:
+// 512 -> 86, 768 -> 96, 1024 -> 99, 1280 -> 88 TFLOP/s, and the larger part count of 1024
+// costs the reduction what it gains here), at least 8 chunks of 32 rows each.
 WgradCfg choose(long Mrows, int cin, int cout, int r, int s) {
   WgradCfg c;
   const long J = (long)r * s * cin;
@@ -404,17 +505,29 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   const dim3 grid((unsigned)(main_grid + flip_blocks));
   const int tiles = c.tiles_co * c.tiles_j;
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
+  // direct loader: fp32 storage, both operands inside 32-bit buffer ranges (the last bytes stay
+  // free for the offset that stands for "outside").  ACC_WGRAD_LOADER=fast in the environment
+  // keeps the register-staged loader (for comparisons).
+  static const bool allow_direct = [] {
+    const char* e = getenv("ACC_WGRAD_LOADER");
+    return !(e && e[0] == 'f');
+  }();
+  const bool direct = fast && allow_direct && g.dtype == DT_F32 && Mrows * g.cout * es <= 0xFFFFFF00L &&
+                      (long)g.n_img * g.h * g.wd * g.cin * es <= 0xFFFFFF00L &&
+                      (reinterpret_cast<uintptr_t>(g.x) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.dy) & 15) == 0;
 #define ACC_WGRAD_LAUNCH(F, T)                                                                             \
   hipLaunchKernelGGL((wgrad_kernel<F, T>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j, tiles, \
                      c.splits, c.chunks_per_split, out, count, main_grid)
   if (g.dtype == DT_F32) {
-    if (fast) ACC_WGRAD_LAUNCH(true, float); else ACC_WGRAD_LAUNCH(false, float);
+    if (direct) ACC_WGRAD_LAUNCH(L_DIRECT, float);
+    else if (fast) ACC_WGRAD_LAUNCH(L_FAST, float);
+    else ACC_WGRAD_LAUNCH(L_GENERIC, float);
   } else {
-    if (fast) ACC_WGRAD_LAUNCH(true, bf16_t); else ACC_WGRAD_LAUNCH(false, bf16_t);
+    if (fast) ACC_WGRAD_LAUNCH(L_FAST, bf16_t); else ACC_WGRAD_LAUNCH(L_GENERIC, bf16_t);
   }
 #undef ACC_WGRAD_LAUNCH
   if (probe && probe->after) (void)hipEventRecord(probe->after, st);
-  if (probe) probe->variant = fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
+  if (probe) probe->variant = direct ? V_WGRAD_DIRECT : fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (c.splits > 1) {

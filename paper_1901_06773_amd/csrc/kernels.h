@@ -53,7 +53,7 @@ struct LaunchProbe {
   hipEvent_t before = nullptr, after = nullptr;
 };
 hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
-enum { V_IGEMM_FAST = 0, V_IGEMM_GENERIC, V_WGRAD_FAST, V_WGRAD_GENERIC, V_IGEMM_DIRECT, V_COUNT };
+enum { V_IGEMM_FAST = 0, V_IGEMM_GENERIC, V_WGRAD_FAST, V_WGRAD_GENERIC, V_IGEMM_DIRECT, V_WGRAD_DIRECT, V_COUNT };
 const char* conv_variant_name(int v);
 
 // dw[co][(r,t,ci)] = sum_{img,p,q} dy[img,p,q,co] * x[img, p*stride+r-pad, q*stride+t-pad, ci]
