@@ -7,17 +7,16 @@
 // A is never materialised: each K-chunk of 32 lies inside one filter tap, so a tile
 // row is 128 contiguous bytes of the NHWC input (or zeros in the padding).  A
 // workgroup of 4 waves (2 x 2) owns a 64 x 64 tile, each wave one 32x32 MFMA block.
-// Operand tiles are staged through LDS (two chunks) as [row][k] with a 36-float pitch,
-// so that one ds_read_b128 per lane feeds four consecutive MFMAs: lanes 0-31 hold
-// k = 8g..8g+3, lanes 32-63 hold k = 8g+4..8g+7 of their row (the pairing of k inside
-// one MFMA is free, A and W use the same one).
+// Operand tiles are staged through LDS (two chunks) as [row][k], so that one ds_read_b128
+// per lane feeds four consecutive MFMAs: lanes 0-31 hold k = 8g..8g+3, lanes 32-63 hold
+// k = 8g+4..8g+7 of their row (the pairing of k inside one MFMA is free, A and W use the
+// same one).  Two loaders fill LDS, see below: straight from global memory (the layers that
+// carry the work), or element by element through registers (odd shapes).
 //
 // Tile shape (measured on MI355X over the ResNet shapes at minibatch 32..256): 64x64
 // beats 128x64 and 128x128 everywhere (70.7 / 86 / 98 TFLOP/s against 56 / 76 / 88 and
 // 40 / 61 / 82): with M a multiple of 49 the larger tiles quantise badly over 256 CUs,
 // and four resident workgroups per CU hide the one barrier per chunk.
-#include <cstdlib>
-
 #include "kernels.h"
 #include "dtype.h"
 
@@ -88,9 +87,10 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
   return ((size_t)(img * g.out_h + g.out_y0 + p * g.out_stride) * g.out_w + g.out_x0 + q * g.out_stride) * g.n_out;
 }
 
-// Loaders.  L_FAST and L_DIRECT: c a multiple of the chunk (32 fp32 / 64 bf16 channels), NHWC
-// input, at most 32 filter taps.  L_GENERIC: every element is decoded on its own (any c, K
-// tail); used for the 3-channel stem and for tiny layers.
+// Loaders.  L_DIRECT: c a multiple of the chunk (32 fp32 / 64 bf16 channels), NHWC input, at
+// most 32 filter taps, both operands within 32-bit byte ranges.  L_GENERIC: every element is
+// decoded on its own and staged through registers (any c, K tail); used for the 3-channel
+// stem and for tiny layers.
 //
 // L_DIRECT moves the chunks from global memory straight into LDS (buffer_load_dwordx4 ... lds:
 // a wave's 64 lanes fill 1024 consecutive LDS bytes, eight 128-byte rows), so no staging
@@ -101,13 +101,13 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
 // belongs into its slot), which keeps the fragment reads free of bank conflicts.  Two LDS
 // stages: the loads of chunk kc+1 are issued right after the barrier that opens chunk kc
 // and have its whole MFMA work to land.
-enum { L_GENERIC = 0, L_FAST = 1, L_DIRECT = 2 };
+enum { L_GENERIC = 0, L_DIRECT = 2 };
 constexpr int LDD = CHUNK_BYTES / 4;          // LDS row pitch of L_DIRECT in words
 
 template <int LOADER, class T>
 __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
                                                      int main_grid) {
-  constexpr bool FAST = LOADER == L_FAST, DIRECT = LOADER == L_DIRECT;
+  constexpr bool DIRECT = LOADER == L_DIRECT;
   constexpr int ES = sizeof(T);
   constexpr int BK = CHUNK_BYTES / ES;       // elements of K per chunk
   constexpr int PITCH = DIRECT ? LDD : LD;
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     compute_chunk2(cur, a0, b0);
   };
 
-  // K loop shared by both loaders.  LDS holds two chunks and registers hold two more:
+  // K loop of the register-staged (per-element) loader.  LDS holds two chunks and registers hold two more:
   // while chunk kc is multiplied out of one LDS half, chunk kc+1 moves from registers
   // into the other half and the global loads of chunk kc+3 are issued into the registers
   // just freed (chunk kc+2 is already on its way).  One barrier per chunk; a global load
@@ -348,77 +348,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       compute_direct(1);
     }
 #endif
-  } else if constexpr (FAST) {
-    // Addresses are split into a per-lane 32-bit byte offset that never changes (the row's
-    // pixel, shifted by the padding margin so that it is never negative) and a uniform
-    // base that moves with the filter tap and the channel chunk, so the K loop spends no
-    // vector instructions on addresses; whether a tap falls into the padding is one bit of
-    // a per-row mask built once.
-    constexpr int AI = BM / 32, BI = BN / 32;
-    const int col4 = tid & 7, row0 = tid >> 3;
-    const int margin = g.pad * g.wd + g.pad + g.pad_dx;    // pixels
-    uint32_t a_voff[AI], a_mask[AI], b_voff[BI];
-#pragma unroll
-    for (int i = 0; i < AI; ++i) {
-      const RowPos rp = decode_row(g, m0 + row0 + 32 * i, M);
-      a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * ES) + col4 * 16;
-      uint32_t mask = 0;
-      for (int kr = 0; kr < g.r; ++kr)
-        for (int kt = 0; kt < g.s; ++kt) {
-          const bool ok = rp.ok && (unsigned)(rp.iy0 + kr) < (unsigned)g.h && (unsigned)(rp.ix0 + kt) < (unsigned)g.wd;
-          mask |= (ok ? 1u : 0u) << (kr * g.s + kt);
-        }
-      a_mask[i] = mask;
-    }
-#pragma unroll
-    for (int i = 0; i < BI; ++i) {
-      const int n = n0 + row0 + 32 * i;
-      b_voff[i] = (uint32_t)(n < g.n_out ? n : 0) * (uint32_t)(K * ES) + col4 * 16;
-    }
-    struct RegsA { v4f v[AI]; } ra0, ra1;        // two register sets
-    struct RegsB { v4f v[BI]; } rb0, rb1;
-    int kr = 0, kt = 0, c0 = 0;  // tap and channel offset of the chunk being loaded (uniform)
-    const uint32_t first_pixel = (uint32_t)margin * (uint32_t)(g.c * ES) + col4 * 16;   // always exists
-
-    // Loads are unconditional so that the number of loads in flight is known statically
-    // (only then can the store of chunk kc+1 wait for its own loads and leave those of
-    // chunk kc+2 in flight).  A lane whose tap falls into the padding (or whose row lies
-    // beyond M) reads the first pixel of the tensor instead and is zeroed when the chunk
-    // moves to LDS.  Filters beyond n_out read filter 0; their products are never stored.
-    auto load_chunk = [&](RegsA& ra, RegsB& rb, int& set_tap, int kc) {
-      const int tap = kr * g.s + kt;
-      set_tap = tap;
-      const char* abase = reinterpret_cast<const char*>(g.in) + ((long)c0 - (long)margin * g.c) * ES;
-      const uint32_t tap_off = (uint32_t)(kr * g.wd + kt) * (uint32_t)(g.c * ES);
-      const char* bbase = reinterpret_cast<const char*>(g.w) + (long)kc * CHUNK_BYTES;
-#pragma unroll
-      for (int i = 0; i < AI; ++i) {
-        const uint32_t off = ((a_mask[i] >> tap) & 1u) ? a_voff[i] + tap_off : first_pixel;
-        ra.v[i] = *reinterpret_cast<const v4f*>(abase + off);
-      }
-#pragma unroll
-      for (int i = 0; i < BI; ++i) rb.v[i] = *reinterpret_cast<const v4f*>(bbase + b_voff[i]);
-      c0 += BK;
-      if (c0 == g.c) {
-        c0 = 0;
-        if (++kt == g.s) { kt = 0; ++kr; }
-      }
-    };
-    auto store_chunk = [&](const RegsA& ra, const RegsB& rb, int tap, int buf) {
-      float* as = As + buf * (BM * LD);
-      float* bs = Bs + buf * (BN * LD);
-#pragma unroll
-      for (int i = 0; i < AI; ++i) {
-        v4f v = ra.v[i];
-        if (!((a_mask[i] >> tap) & 1u)) v = v4f{0.f, 0.f, 0.f, 0.f};
-        *reinterpret_cast<v4f*>(&as[(row0 + 32 * i) * LD + col4 * 4]) = v;
-      }
-#pragma unroll
-      for (int i = 0; i < BI; ++i)
-        *reinterpret_cast<v4f*>(&bs[(row0 + 32 * i) * LD + col4 * 4]) = rb.v[i];
-    };
-
-    main_loop(load_chunk, store_chunk, ra0, rb0, ra1, rb1);
   } else {
     // one element per load: thread -> k column tid % BK, rows tid / BK + RP * i
     constexpr int RP = 256 / BK;                 // rows per pass
@@ -519,36 +448,21 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   const long K = (long)g.r * g.s * g.c;
   if (M >= (1L << 31) || K >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31))
     return hipErrorInvalidValue;
-  // The fast loader needs whole 128-byte chunks of channels (32 fp32 / 64 bf16), at most 32
-  // filter taps (one validity bit each) and every per-lane byte offset below 2^32.  The
-  // choice depends on the shape only, never on addresses or on the swap plan.
   if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
   const long es = (long)dt_size(g.dtype);
-  const bool fast = (g.c % (CHUNK_BYTES / es) == 0) && g.r * g.s <= 32 &&
-                    ((long)g.n_img * g.h * g.wd + 2L * (g.pad + (g.pad_dx > 0 ? g.pad_dx : 0)) * (g.wd + 1)) * g.c * es < (1L << 32) &&
-                    (long)g.n_out * K * es < (1L << 32);
   // The direct loader addresses both operands through buffer descriptors: 32-bit ranges, the
-  // last bytes kept free for the offset that stands for "outside".  ACC_IGEMM_LOADER=fast in
-  // the environment keeps the register-staged loader (for comparisons).
-  static const bool allow_direct = [] {
-    const char* e = getenv("ACC_IGEMM_LOADER");
-    return !(e && e[0] == 'f');
-  }();
+  // last bytes kept free for the offset that stands for "outside"; 16-byte loads want aligned
+  // tensors.  The choice depends on the shape and the alignment only, never on the swap plan
+  // (pool offsets are multiples of 256).
   const long margin_px = (long)g.pad * g.wd + g.pad + g.pad_dx;
-  const bool direct = fast && allow_direct &&
+  const bool direct = (g.c % (CHUNK_BYTES / es) == 0) && g.r * g.s <= 32 &&
                       (margin_px + (long)g.n_img * g.h * g.wd) * g.c * es <= 0xFFFFFF00L &&
                       (long)g.n_out * K * es <= 0xFFFFFF00L &&
                       (reinterpret_cast<uintptr_t>(g.in) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.w) & 15) == 0;
-  const int loader = direct ? L_DIRECT : fast ? L_FAST : L_GENERIC;
-  probe->variant = direct ? V_IGEMM_DIRECT : fast ? V_IGEMM_FAST : V_IGEMM_GENERIC;
-  if (g.dtype == DT_F32) {
-    if (loader == L_DIRECT) return launch<L_DIRECT, float>(g, (int)M, (int)K, st, probe);
-    if (loader == L_FAST) return launch<L_FAST, float>(g, (int)M, (int)K, st, probe);
-    return launch<L_GENERIC, float>(g, (int)M, (int)K, st, probe);
-  }
-  if (loader == L_DIRECT) return launch<L_DIRECT, bf16_t>(g, (int)M, (int)K, st, probe);
-  if (loader == L_FAST) return launch<L_FAST, bf16_t>(g, (int)M, (int)K, st, probe);
-  return launch<L_GENERIC, bf16_t>(g, (int)M, (int)K, st, probe);
+  probe->variant = direct ? V_IGEMM_DIRECT : V_IGEMM_GENERIC;
+  if (g.dtype == DT_F32)
+    return direct ? launch<L_DIRECT, float>(g, (int)M, (int)K, st, probe) : launch<L_GENERIC, float>(g, (int)M, (int)K, st, probe);
+  return direct ? launch<L_DIRECT, bf16_t>(g, (int)M, (int)K, st, probe) : launch<L_GENERIC, bf16_t>(g, (int)M, (int)K, st, probe);
 }
 
 }  // namespace acc
