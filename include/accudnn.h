@@ -60,7 +60,11 @@ typedef struct {
 
 /* Device pool, pinned host arena and the three streams of Sec. 6 (compute,
  * swap-out, swap-in; hipStream_t passed as void*).  With a NULL acc_resources the
- * context is planning-only: everything but calibrate / train_step / weights works. */
+ * context is planning-only: everything but calibrate / train_step / weights works.
+ * s_wgrad (may be NULL) is a fourth stream, different from the other three: the weight
+ * gradient of a convolution then runs there, beside the data gradient and the steps that
+ * follow on the compute stream, and is joined two convolutions later; results are the same
+ * bit for bit.  All streams at the default priority. */
 typedef struct {
   void* pool;        /* device */
   size_t pool_bytes;
@@ -69,6 +73,7 @@ typedef struct {
   void* s_compute;
   void* s_out;
   void* s_in;
+  void* s_wgrad;
 } acc_resources;
 
 typedef struct {
@@ -245,8 +250,12 @@ int acc_get_timeline(acc_ctx* ctx, int which, acc_timeline_entry* out, int max_e
 int acc_train_step(acc_ctx* ctx, const float* images, int images_loc, const int32_t* labels,
                    float lr, float* loss_out);
 int acc_get_stats(acc_ctx* ctx, acc_stats* out);
+/* on = 0: weight gradients run on the compute stream even if the context has a stream for
+ * them (for measurements); on != 0 (default): they use it. */
+int acc_set_wgrad_overlap(acc_ctx* ctx, int on);
 /* level 0: off.  1: timing events around every step and every copy.  2: timing events
- * directly around every convolution kernel launch.  3: both.  Events cost host time. */
+ * directly around every convolution kernel launch (while this is on, weight gradients run on
+ * the compute stream, so that every kernel is timed alone).  3: both.  Events cost host time. */
 int acc_set_profiling(acc_ctx* ctx, int level);
 /* Per convolution kernel instance, summed over the last train_step run at level 2 or 3:
  * launches, milliseconds between the events around the launches, algorithmic flops

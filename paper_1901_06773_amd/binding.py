@@ -41,7 +41,7 @@ class acc_layer(C.Structure):
 class acc_resources(C.Structure):
     _fields_ = [("pool", C.c_void_p), ("pool_bytes", C.c_size_t), ("host", C.c_void_p),
                 ("host_bytes", C.c_size_t), ("s_compute", C.c_void_p), ("s_out", C.c_void_p),
-                ("s_in", C.c_void_p)]
+                ("s_in", C.c_void_p), ("s_wgrad", C.c_void_p)]
 
 
 class acc_plan_summary(C.Structure):
@@ -133,6 +133,7 @@ _PROTOS = {
     "acc_train_step": (_I, [_VP, _VP, _I, _VP, _F, C.POINTER(_F)]),
     "acc_get_stats": (_I, [_VP, C.POINTER(acc_stats)]),
     "acc_set_profiling": (_I, [_VP, _I]),
+    "acc_set_wgrad_overlap": (_I, [_VP, _I]),
     "acc_get_step_times_ms": (_I, [_VP, C.POINTER(_D), _I]),
     "acc_get_kernel_profile": (_I, [_VP, C.POINTER(acc_kernel_profile), _I]),
     "acc_op_conv_workspace": (_SZ, [_I] * 9),
@@ -172,7 +173,7 @@ class Context:
     """One network on one GPU (or, with pool_bytes=None, a planning-only context)."""
 
     def __init__(self, spec_array: np.ndarray, in_chw: Sequence[int], pool_bytes: Optional[int] = None,
-                 host_bytes: int = 0, device: str = "cuda:0", dtype: int = F32):
+                 host_bytes: int = 0, device: str = "cuda:0", dtype: int = F32, wgrad_stream: bool = True):
         self._h = _VP()
         self.dtype = int(dtype)
         self._keep = []
@@ -186,10 +187,11 @@ class Context:
             torch.cuda.set_device(self.device)
             self.pool = torch.empty(int(pool_bytes), dtype=torch.uint8, device=self.device)
             self.host = torch.empty(max(int(host_bytes), 256), dtype=torch.uint8, pin_memory=True)
-            self.streams = [torch.cuda.Stream(device=self.device) for _ in range(3)]
+            # compute, swap-out, swap-in, weight gradients; all at the default priority
+            self.streams = [torch.cuda.Stream(device=self.device) for _ in range(4 if wgrad_stream else 3)]
             res = acc_resources(self.pool.data_ptr(), self.pool.numel(), self.host.data_ptr(), self.host.numel(),
                                 self.streams[0].cuda_stream, self.streams[1].cuda_stream,
-                                self.streams[2].cuda_stream)
+                                self.streams[2].cuda_stream, self.streams[3].cuda_stream if wgrad_stream else None)
             res_ptr = C.byref(res)
             torch.cuda.synchronize(self.device)
         rc = _lib.acc_create(arr, n, int(in_chw[0]), int(in_chw[1]), int(in_chw[2]), self.dtype, res_ptr, C.byref(self._h))
@@ -349,6 +351,10 @@ class Context:
         s = acc_stats()
         self._check(_lib.acc_get_stats(self._h, C.byref(s)))
         return s.as_dict()
+
+    def set_wgrad_overlap(self, on: bool):
+        """Weight gradients on their own stream beside the data gradients (default), or on the compute stream."""
+        self._check(_lib.acc_set_wgrad_overlap(self._h, 1 if on else 0))
 
     def set_profiling(self, level: int):
         """0 off, 1 per step and copy, 2 per convolution kernel launch, 3 both."""

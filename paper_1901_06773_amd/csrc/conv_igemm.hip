@@ -115,9 +115,36 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   __shared__ __attribute__((aligned(128))) float Bs[2 * BN * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
-    // side job: 1024 elements of a weight gradient, parts added in their fixed order
     const ReduceJob& j = g.side;
-    const size_t i4 = ((size_t)(blockIdx.x - main_grid) * 256 + threadIdx.x) * 4;
+    const int reduce_blocks = (int)((j.count + 1023) / 1024);
+    int id = (int)blockIdx.x - main_grid;
+    if (id >= reduce_blocks) {
+      // side job: one 32 x 32 (co, ci) block of one tap of a flipped, transposed filter
+      const FlipJob& f = g.flip;
+      id -= reduce_blocks;
+      const int bx = (f.cin + 31) / 32, by = (f.cout + 31) / 32;
+      const int tap = id / (bx * by), rem = id - tap * (bx * by);
+      if (tap >= f.r * f.s) return;
+      const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
+      const int kr = f.r - 1 - tap / f.s, kt = f.s - 1 - tap % f.s;
+      const int src_tap = kr * f.s + kt;
+      T (*tile)[33] = reinterpret_cast<T (*)[33]>(As);
+      const T* fw = static_cast<const T*>(f.w);
+      T* fwt = static_cast<T*>(f.wt);
+      const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+      for (int i = ty; i < 32; i += 8) {
+        const int co = co0f + i, ci = ci0f + tx;
+        tile[i][tx] = (co < f.cout && ci < f.cin) ? fw[((size_t)co * f.r * f.s + src_tap) * f.cin + ci] : T(0);
+      }
+      __syncthreads();
+      for (int i = ty; i < 32; i += 8) {
+        const int ci = ci0f + i, co = co0f + tx;
+        if (ci < f.cin && co < f.cout) fwt[((size_t)ci * f.r * f.s + tap) * f.cout + co] = tile[tx][i];
+      }
+      return;
+    }
+    // side job: 1024 elements of a weight gradient, parts added in their fixed order
+    const size_t i4 = ((size_t)id * 256 + threadIdx.x) * 4;
     if (i4 >= j.count) return;
     if (i4 + 4 <= j.count && (j.count & 3) == 0) {
       float4 sum = *reinterpret_cast<const float4*>(j.part + i4);
@@ -415,6 +442,10 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   if (g.side.count) {
     if (!g.side.part || !g.side.dw || g.side.splits < 1) return hipErrorInvalidValue;
     side_blocks = (long)((g.side.count + 1023) / 1024);
+  }
+  if (g.flip.wt) {
+    if (!g.flip.w || g.flip.cout <= 0 || g.flip.cin <= 0 || g.flip.r <= 0 || g.flip.s <= 0) return hipErrorInvalidValue;
+    side_blocks += (long)((g.flip.cin + 31) / 32) * ((g.flip.cout + 31) / 32) * g.flip.r * g.flip.s;
   }
   if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
   if (probe->before) (void)hipEventRecord(probe->before, st);

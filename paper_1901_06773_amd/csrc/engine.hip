@@ -39,6 +39,10 @@ struct acc_ctx {
   acc_resources res{};
   std::string err;
   hipStream_t s_c = nullptr, s_o = nullptr, s_i = nullptr;
+  hipStream_t s_w = nullptr;           // optional: weight gradients run here beside the data gradients
+  bool wgrad_overlap = true;           // use s_w when there is one (off: everything on s_c)
+  std::vector<hipEvent_t> ev_fork, ev_wdone;   // per conv backward step: its dy is ready / its wgrad is done
+  std::vector<char> wgrad_in_flight;   // per step: its wgrad went to s_w in this iteration
   // static part of the pool
   float* d_params = nullptr;
   float* d_grads = nullptr;
@@ -202,6 +206,12 @@ extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int i
     c->s_c = (hipStream_t)res->s_compute;
     c->s_o = (hipStream_t)res->s_out;
     c->s_i = (hipStream_t)res->s_in;
+    c->s_w = (hipStream_t)res->s_wgrad;
+    if (c->s_w && (c->s_w == c->s_c || c->s_w == c->s_o || c->s_w == c->s_i)) {
+      g_create_error = "resources: the weight-gradient stream must differ from the other three";
+      delete c;
+      return ACC_EINVAL;
+    }
     char* p = (char*)res->pool;
     const size_t pb = al256(c->g.param_elems * sizeof(float));
     c->d_params = (float*)p; p += pb;
@@ -216,6 +226,17 @@ extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int i
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_loss, 256, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreate(&c->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&c->ev_end);
+    if (c->s_w) {
+      const size_t ns = c->g.steps.size();
+      c->ev_fork.assign(ns, nullptr);
+      c->ev_wdone.assign(ns, nullptr);
+      c->wgrad_in_flight.assign(ns, 0);
+      for (size_t j = 0; j < ns && e == hipSuccess; ++j) {
+        if (c->g.steps[j].wgrad_join < 0) continue;
+        e = hipEventCreateWithFlags(&c->ev_fork[j], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_wdone[j], hipEventDisableTiming);
+      }
+    }
     if (e != hipSuccess) {
       g_create_error = std::string("device setup: ") + hipGetErrorString(e);
       delete c;
@@ -232,7 +253,10 @@ extern "C" void acc_destroy(acc_ctx* c) {
     (void)hipStreamSynchronize(c->s_c);
     (void)hipStreamSynchronize(c->s_o);
     (void)hipStreamSynchronize(c->s_i);
+    if (c->s_w) (void)hipStreamSynchronize(c->s_w);
     c->drop_events();
+    for (auto* v : {&c->ev_fork, &c->ev_wdone})
+      for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     for (auto& kp : c->kprobes) { (void)hipEventDestroy(kp.a); (void)hipEventDestroy(kp.b); }
     for (hipEvent_t e : c->empty_pair) if (e) (void)hipEventDestroy(e);
     if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
@@ -539,10 +563,10 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
     if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
     return e;
   };
-  auto wgrad = [&](const WgradGeom& wg, double flops, ReduceJob* deferred) {
+  auto wgrad = [&](const WgradGeom& wg, double flops, ReduceJob* deferred, hipStream_t on = nullptr) {
     LaunchProbe lp;
     LaunchProbe* pp = c->next_probe(&lp, flops);
-    const hipError_t e = conv_wgrad(wg, st, pp, deferred);
+    const hipError_t e = conv_wgrad(wg, on ? on : st, pp, deferred);
     if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
     return e;
   };
@@ -623,19 +647,43 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       wg.workspace = ptr(s.ws2);
       if (s.dx < 0) return wgrad(wg, conv_flops, nullptr);   // first layer: no data gradient
       const bool split = l->stride > 1 && (l->r > 1 || l->s > 1 || l->pad > 0);
-      if (!split) { wg.flip_w = wk; wg.flip_wt = ptr(s.ws); }   // side jobs as in the fc step
+      // The weight gradient reads x and dy and writes only its own partial sums and dw, so it
+      // may run beside the steps that follow: on the weight-gradient stream if there is one
+      // (not while single kernels are being timed), joined kWgradLag conv steps later.
+      const bool aside = c->s_w && c->wgrad_overlap && !c->kernel_profiling && s.wgrad_join >= 0;
+      const hipStream_t sw = aside ? c->s_w : st;
+      hipError_t e;
+      if (aside) {
+        if ((e = hipEventRecord(c->ev_fork[j], st)) != hipSuccess) return e;        // dy (and x) are ready
+        if ((e = hipStreamWaitEvent(sw, c->ev_fork[j], 0)) != hipSuccess) return e;
+      }
       ReduceJob job;
-      hipError_t e = wgrad(wg, conv_flops, &job);
-      if (e != hipSuccess) return e;
+      if ((e = wgrad(wg, conv_flops, &job, sw)) != hipSuccess) return e;
+      if ((e = reduce_parts(job, sw)) != hipSuccess) return e;
+      if (aside) {
+        if ((e = hipEventRecord(c->ev_wdone[j], sw)) != hipSuccess) return e;
+        c->wgrad_in_flight[j] = 1;
+      }
+      // the flipped, transposed filter: written by the previous conv backward step's launch,
+      // unless this is the first one
+      if (s.flips_itself && (e = filter_flip_transpose(wk, ptr(s.ws), l->cout, l->cin, l->r, l->s, dt, st)) != hipSuccess)
+        return e;
       ConvGeom cg{};
-      cg.side = job;
+      if (s.flip_for >= 0) {   // ... and the next one's rides on this step's launch
+        const Step& nx = g.steps[s.flip_for];
+        const acc_layer& nl = g.layers[nx.layer];
+        const float* nw = c->d_params + g.params[nx.layer].offset;
+        cg.flip.w = dt == ACC_BF16 ? (const void*)(c->d_params16 + g.params[nx.layer].offset) : (const void*)nw;
+        cg.flip.wt = ptr(nx.ws);
+        cg.flip.cout = nl.cout; cg.flip.cin = nl.cin; cg.flip.r = nl.r; cg.flip.s = nl.s;
+      }
       cg.in = ptr(s.dy); cg.w = ptr(s.ws); cg.out = ptr(s.dx); cg.dtype = dt;
       cg.n_img = k; cg.h = ho; cg.wd = wo; cg.c = l->cout; cg.n_out = l->cin;
       cg.r = l->r; cg.s = l->s; cg.stride = 1; cg.accumulate = s.dx_accumulate;
       cg.out_h = h; cg.out_w = wd;
       if (split) {
         // strided and larger than 1x1: one stride-1 convolution per residue class of the dx
-        // position, each with its own sub-filter; the first launch carries the reduction
+        // position, each with its own sub-filter; the first launch carries the side job
         DgradPart parts[kMaxDgradParts];
         bool covers_all = false;
         size_t wt_bytes = 0;
@@ -658,7 +706,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
           cg.out_stride = l->stride; cg.out_y0 = pt.y0; cg.out_x0 = pt.x0;
           e = igemm(cg, conv_flops * ((double)pt.p * pt.q * pt.nr * pt.ns / work));
           if (e != hipSuccess) return e;
-          cg.side = ReduceJob{};
+          cg.flip = FlipJob{};         // the side job went with the first part
         }
         return hipSuccess;
       }
@@ -751,11 +799,19 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
         if (in.wait_d2h >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_d2h[in.wait_d2h], 0));
         if (in.wait_h2d >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_h2d[in.wait_h2d], 0));
         if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_a[in.arg], c->s_c));
+        // weight gradients that went to their own stream and must be complete before this step
+        // (their operands may be released after it; the update reads their results)
+        for (int jw : g.steps[in.arg].joins)
+          if (c->s_w && c->wgrad_in_flight[jw]) {
+            HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_wdone[jw], 0));
+            c->wgrad_in_flight[jw] = 0;
+          }
         hipError_t e = run_step(c, in.arg, lr);
         if (e != hipSuccess) {
           char buf[96];
           snprintf(buf, sizeof buf, "step %d (%s)", in.arg, step_kind_name(g.steps[in.arg].kind));
           (void)hipStreamSynchronize(c->s_c); (void)hipStreamSynchronize(c->s_o); (void)hipStreamSynchronize(c->s_i);
+          if (c->s_w) (void)hipStreamSynchronize(c->s_w);
           return c->hipfail(e, buf);
         }
         if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_b[in.arg], c->s_c));
@@ -793,6 +849,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   HIPCHK(c, hipStreamSynchronize(c->s_c));
   HIPCHK(c, hipStreamSynchronize(c->s_o));
   HIPCHK(c, hipStreamSynchronize(c->s_i));
+  if (c->s_w) HIPCHK(c, hipStreamSynchronize(c->s_w));
   const double t_done = now_ms();
   if (loss_out) *loss_out = *c->h_loss;
   c->stats.step_ms = t_done - t_host0;
@@ -874,6 +931,12 @@ extern "C" int acc_get_timeline(acc_ctx* c, int which, acc_timeline_entry* out, 
 extern "C" int acc_get_stats(acc_ctx* c, acc_stats* out) {
   if (!c || !out) return ACC_EINVAL;
   *out = c->stats;
+  return ACC_OK;
+}
+
+extern "C" int acc_set_wgrad_overlap(acc_ctx* c, int on) {
+  if (!c) return ACC_EINVAL;
+  c->wgrad_overlap = on != 0;
   return ACC_OK;
 }
 

@@ -387,6 +387,33 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
     steps.push_back(u);
   }
 
+  // ---- weight gradients beside the data gradients: join points, operands kept until then,
+  //      and the flipped filter of the next conv backward step written one step early
+  {
+    const int sgd = (int)steps.size() - 1;
+    std::vector<int> convb;
+    for (int j = 0; j < (int)steps.size(); ++j)
+      if (steps[j].kind == K_CONV_B && steps[j].dx >= 0) convb.push_back(j);
+    auto add_unique = [](std::vector<int>& v, int t) {
+      if (t >= 0 && std::find(v.begin(), v.end(), t) == v.end()) v.push_back(t);
+    };
+    for (size_t i = 0; i < convb.size(); ++i) {
+      Step& s = steps[convb[i]];
+      const int join = i + kWgradLag < convb.size() ? convb[i + kWgradLag] : sgd;
+      s.wgrad_join = join;
+      steps[join].joins.push_back(convb[i]);
+      for (int t : {s.x, s.dy, s.ws2}) add_unique(steps[join].reads, t);
+      const acc_layer& l = layers[s.layer];
+      const bool split = l.stride > 1 && (l.r > 1 || l.s > 1 || l.pad > 0);
+      if (split) continue;                       // writes its sub-filters itself
+      if (i == 0) { s.flips_itself = true; continue; }
+      Step& prev = steps[convb[i - 1]];
+      prev.flip_for = convb[i];
+      add_unique(prev.writes, s.ws);
+      add_unique(s.reads, s.ws);
+    }
+  }
+
   // ---- lifetimes
   const int ns = (int)steps.size();
   for (int j = 0; j < ns; ++j) {

@@ -46,7 +46,22 @@ struct Step {
   double bytes_per_image = 0;   // HBM bytes the step touches, per image
   double bytes_fixed = 0;
   std::vector<int> reads, writes;     // GMAP: memory objects touched (scratch included in writes)
+  // Conv backward steps with a data gradient: the weight gradient may run on a stream of its
+  // own beside the steps that follow.  wgrad_join: the step before which it must be complete
+  // (its operands x, dy and its partial sums stay allocated until then: they are among that
+  // step's reads); joins: the steps whose weight gradients this step waits for;
+  // flip_for: the later conv backward step whose flipped filter this step's data-gradient
+  // launch writes on the side (-1: none); flips_itself: nobody did it for this step.
+  int wgrad_join = -1;
+  std::vector<int> joins;
+  int flip_for = -1;
+  bool flips_itself = false;
 };
+
+// A weight gradient is joined this many conv backward steps after its own: a wait for an
+// event that was signalled long ago costs next to nothing on the waiting stream, a wait for
+// a fresh one stalls it (measured: joining at once loses the whole gain of the overlap).
+constexpr int kWgradLag = 2;
 
 struct ParamSlot {       // static device data of a layer
   size_t count = 0;      // elements

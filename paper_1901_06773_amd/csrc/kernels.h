@@ -23,6 +23,14 @@ struct ReduceJob {
   int splits;
 };
 
+// A filter to flip and transpose on the side of another launch (storage type of that launch):
+// wt[ci][r'][t'][co] = w[co][R-1-r'][S-1-t'][ci].  wt == nullptr: nothing to do.
+struct FlipJob {
+  const void* w;
+  void* wt;
+  int cout, cin, r, s;
+};
+
 // Implicit-GEMM view of a convolution-like gather:
 //   out[m][n] (+)= sum_{r,t,c} in[img, p*stride+r-pad, q*stride+t-pad, c] * w[n][(r,t,c)]
 // with row m = (img, p, q) over a P x Q grid (columns use pad + pad_dx).  The result row is
@@ -41,9 +49,11 @@ struct ConvGeom {
   int out_h, out_w, out_stride;
   int out_y0, out_x0;       // first output pixel
   int accumulate;           // out += result
-  // Optional side job: extra workgroups appended to the launch add up the parts of a weight
-  // gradient (independent data; saves a launch of its own).
+  // Optional side jobs: extra workgroups appended to the launch add up the parts of a weight
+  // gradient, and / or write the flipped, transposed filter that a later data gradient needs
+  // (independent data; saves launches of their own).
   ReduceJob side;
+  FlipJob flip;
 };
 
 // Optional probe of one launch: which template instance ran (index into conv_variant_name())

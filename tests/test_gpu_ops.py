@@ -148,6 +148,18 @@ BN_CASES = [  # n, c, h, w
 @pytest.mark.parametrize("case", BN_CASES)
 @pytest.mark.parametrize("variant", ["plain", "relu", "add_relu"])
 def test_bn_fwd_bwd(case, variant):
+    bn_case(case, variant)
+
+
+@pytest.mark.parametrize("case,variant", [((41, 256, 56, 56), "add_relu"), ((41, 1024, 14, 14), "add_relu"),
+                                          ((41, 64, 112, 112), "relu")])
+def test_bn_full_size(case, variant):
+    """The batch-norm shapes of ResNet-152 that move the most bytes, at the benchmark's
+    minibatch (thousands of row slabs, every column slice), element by element."""
+    bn_case(case, variant)
+
+
+def bn_case(case, variant):
     n, c, h, w = case
     x = rnd(5, n, c, h, w) * np.float32(1.7) + np.float32(0.3)
     gamma = (1.0 + 0.2 * rnd(6, c)).astype(np.float32)
