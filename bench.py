@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--mode", default="dynamic", choices=["dynamic", "naive", "none"])
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage of activations / gradients / kernel-side weights (bf16: configs[4])")
+    ap.add_argument("--serial", action="store_true",
+                    help="weight gradients on the compute stream instead of their own (every kernel runs alone: "
+                         "the setting in which single kernels are timed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-noswap-reference", action="store_true")
     ap.add_argument("--cpu-sample-k", type=int, default=12)
@@ -102,6 +105,8 @@ def main():
     t0 = time.time()
     ctx = B.Context(net.as_array(), chw, pool_bytes=budget, host_bytes=host_need + (64 << 20), dtype=dtype)
     ctx.set_weights(S.init_params(net))
+    if args.serial:
+        ctx.set_wgrad_overlap(False)
     log(f"context ready in {time.time() - t0:.1f}s: pool {budget / GiB:.2f} GiB, pinned host {host_need / GiB:.2f} GiB")
 
     # ---- dynamic information: per-step times at the sweep's minibatches, link bandwidth
@@ -187,6 +192,8 @@ def main():
         big = int(summ["noswap_peak_bytes"] * 1.02) + (64 << 20)
         ctx2 = B.Context(net.as_array(), chw, pool_bytes=big, host_bytes=256, dtype=dtype)
         ctx2.set_weights(S.init_params(net))
+        if args.serial:
+            ctx2.set_wgrad_overlap(False)
         ctx2.plan_swaps(k, big, B.PLAN_NONE)
         imgs = batch(k, 0)
         ctx2.train_step(*imgs, 0.1)
@@ -216,7 +223,8 @@ def main():
                     traffic=MEASURED_TRAFFIC_BYTES.get((args.net, k, args.budget_gib)) if args.dtype == "f32" else None, launches_per_step=dom["launches"],
                     avg_launch_us=dom["ms"] * 1e3 / dom["launches"],
                     flop_per_launch=dom["flops"] / dom["launches"],
-                    timed_in="the headline run" if timed_swaps else "the no-swap run of the same minibatch")
+                    timed_in=("two extra steps of the headline context" if timed_swaps else "the no-swap run of the same minibatch") +
+                             ", weight gradients on the compute stream so that every kernel is timed alone")
     # step-level view: BN / pooling / update steps against the HBM roofline
     by_kind = {}
     for n_, ms in zip(names, step_ms):
@@ -257,7 +265,8 @@ def main():
         data="synthetic",
         config=dict(workload=f"{args.net} {'fp32' if args.dtype == 'f32' else 'bf16 (fp32 master weights and statistics)'} training step, 224x224x3 N(0,1) images, 1000 classes, "
                              f"minibatch {k}, device-memory budget {args.budget_gib} GiB, planner mode {args.mode}",
-                    minibatch=k, budget_gib=args.budget_gib, strides="v1", optimizer="plain SGD lr 0.1"),
+                    minibatch=k, budget_gib=args.budget_gib, strides="v1", optimizer="plain SGD lr 0.1",
+                    wgrad_stream=not args.serial),
         roofline=roofline, cpu_baseline=cpu, conv=conv, swap=swap, noswap_reference=noswap,
         plan=dict(n_maps=summ["n_maps"], n_swapped=summ["n_swapped"], peak_gib=summ["peak_bytes"] / GiB,
                   layer_peak_gib=summ["layer_peak_bytes"] / GiB, noswap_peak_gib=summ["noswap_peak_bytes"] / GiB,

@@ -91,8 +91,32 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
   __shared__ __attribute__((aligned(256))) float Bs[2 * BKM * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
+    int id = blockIdx.x - main_grid;
+    const ReduceJob& rj = g.side;
+    const int reduce_blocks = (int)((rj.count + 1023) / 1024);
+    if (id < reduce_blocks) {
+      // side job: 1024 elements of an earlier weight gradient, parts added in their fixed order
+      const size_t i4 = ((size_t)id * 256 + threadIdx.x) * 4;
+      if (i4 >= rj.count) return;
+      if (i4 + 4 <= rj.count && (rj.count & 3) == 0) {
+        float4 sum = *reinterpret_cast<const float4*>(rj.part + i4);
+        for (int k = 1; k < rj.splits; ++k) {
+          const float4 v = *reinterpret_cast<const float4*>(rj.part + (size_t)k * rj.count + i4);
+          sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        *reinterpret_cast<float4*>(rj.dw + i4) = sum;
+      } else {
+        for (size_t i = i4; i < rj.count && i < i4 + 4; ++i) {
+          float sum = rj.part[i];
+          for (int k = 1; k < rj.splits; ++k) sum += rj.part[(size_t)k * rj.count + i];
+          rj.dw[i] = sum;
+        }
+      }
+      return;
+    }
+    id -= reduce_blocks;
+    if (!g.flip_wt) return;
     // side job: one 32 x 32 (co, ci) block of one tap of the flipped, transposed filter
-    const int id = blockIdx.x - main_grid;
     const int bx = (g.cin + 31) / 32, by = (g.cout + 31) / 32;
     const int tap = id / (bx * by), rem = id - tap * (bx * by);
     const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
@@ -501,8 +525,13 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   const size_t count = (size_t)g.cout * J;
   const int main_grid = (int)((work + 7) / 8 * 8);
   const long flip_blocks = g.flip_wt ? (long)((g.cin + 31) / 32) * ((g.cout + 31) / 32) * g.r * g.s : 0;
-  if (main_grid + flip_blocks > (1L << 30)) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)(main_grid + flip_blocks));
+  long reduce_blocks = 0;
+  if (g.side.count) {
+    if (!g.side.part || !g.side.dw || g.side.splits < 1) return hipErrorInvalidValue;
+    reduce_blocks = (long)((g.side.count + 1023) / 1024);
+  }
+  if (main_grid + flip_blocks + reduce_blocks > (1L << 30)) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(main_grid + reduce_blocks + flip_blocks));
   const int tiles = c.tiles_co * c.tiles_j;
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
   // direct loader: fp32 storage, both operands inside 32-bit buffer ranges (the last bytes stay

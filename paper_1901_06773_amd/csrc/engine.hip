@@ -43,6 +43,9 @@ struct acc_ctx {
   bool wgrad_overlap = true;           // use s_w when there is one (off: everything on s_c)
   std::vector<hipEvent_t> ev_fork, ev_wdone;   // per conv backward step: its dy is ready / its wgrad is done
   std::vector<char> wgrad_in_flight;   // per step: its wgrad went to s_w in this iteration
+  ReduceJob pending_reduce{nullptr, nullptr, 0, 0};   // parts of the last conv weight gradient, not added up yet
+  hipStream_t pending_stream = nullptr;               // ... and the stream that gradient ran on
+  hipEvent_t ev_flush = nullptr;
   // static part of the pool
   float* d_params = nullptr;
   float* d_grads = nullptr;
@@ -226,6 +229,7 @@ extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int i
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->h_loss, 256, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreate(&c->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&c->ev_end);
+    if (c->s_w && e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_flush, hipEventDisableTiming);
     if (c->s_w) {
       const size_t ns = c->g.steps.size();
       c->ev_fork.assign(ns, nullptr);
@@ -259,6 +263,7 @@ extern "C" void acc_destroy(acc_ctx* c) {
       for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     for (auto& kp : c->kprobes) { (void)hipEventDestroy(kp.a); (void)hipEventDestroy(kp.b); }
     for (hipEvent_t e : c->empty_pair) if (e) (void)hipEventDestroy(e);
+    if (c->ev_flush) (void)hipEventDestroy(c->ev_flush);
     if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
     if (c->ev_end) (void)hipEventDestroy(c->ev_end);
     if (c->h_loss) (void)hipHostFree(c->h_loss);
@@ -541,6 +546,17 @@ namespace {
 hipError_t fill_pseudo_input(acc_ctx* c, float* p, size_t count);
 
 // launches the kernels of one step on the compute stream
+// Adds up the parts of the last conv weight gradient on the stream it ran on; the compute
+// stream then waits for that stream (the update reads the result).
+hipError_t flush_pending_reduce(acc_ctx* c) {
+  if (!c->pending_reduce.count) return hipSuccess;
+  hipError_t e = reduce_parts(c->pending_reduce, c->pending_stream);
+  c->pending_reduce = ReduceJob{nullptr, nullptr, 0, 0};
+  if (e != hipSuccess || c->pending_stream == c->s_c) return e;
+  if ((e = hipEventRecord(c->ev_flush, c->pending_stream)) != hipSuccess) return e;
+  return hipStreamWaitEvent(c->s_c, c->ev_flush, 0);
+}
+
 hipError_t run_step(acc_ctx* c, int j, float lr) {
   const Graph& g = c->g;
   const Step& s = g.steps[j];
@@ -657,9 +673,16 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
         if ((e = hipEventRecord(c->ev_fork[j], st)) != hipSuccess) return e;        // dy (and x) are ready
         if ((e = hipStreamWaitEvent(sw, c->ev_fork[j], 0)) != hipSuccess) return e;
       }
+      // the parts of the previous conv weight gradient (same stream) are added up by extra
+      // workgroups of this launch; this one's by the next, the last one's before the update
+      if (c->pending_reduce.count && c->pending_stream != sw) {
+        if ((e = flush_pending_reduce(c)) != hipSuccess) return e;
+      }
+      wg.side = c->pending_reduce;
       ReduceJob job;
       if ((e = wgrad(wg, conv_flops, &job, sw)) != hipSuccess) return e;
-      if ((e = reduce_parts(job, sw)) != hipSuccess) return e;
+      c->pending_reduce = job;
+      c->pending_stream = sw;
       if (aside) {
         if ((e = hipEventRecord(c->ev_wdone[j], sw)) != hipSuccess) return e;
         c->wgrad_in_flight[j] = 1;
@@ -722,6 +745,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       return igemm(cg, conv_flops);
     }
     case K_SGD:
+      if (hipError_t e = flush_pending_reduce(c); e != hipSuccess) return e;
       return sgd_update(c->d_params, c->d_grads, lr, g.param_elems, c->d_params16, st);
   }
   return hipErrorInvalidValue;
@@ -757,6 +781,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
     }
   }
   uint64_t bytes_out = 0, bytes_in = 0;
+  c->pending_reduce = ReduceJob{nullptr, nullptr, 0, 0};
   c->kprobes_used = 0;
   if (c->kernel_profiling) {
     // the time between two events with no kernel between them is taken off every probe

@@ -403,6 +403,10 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
       s.wgrad_join = join;
       steps[join].joins.push_back(convb[i]);
       for (int t : {s.x, s.dy, s.ws2}) add_unique(steps[join].reads, t);
+      // the parts are added up on the side of the next weight-gradient launch: they live until
+      // that one is joined
+      const int join_next = i + 1 + kWgradLag < convb.size() ? convb[i + 1 + kWgradLag] : sgd;
+      add_unique(steps[join_next].reads, s.ws2);
       const acc_layer& l = layers[s.layer];
       const bool split = l.stride > 1 && (l.r > 1 || l.s > 1 || l.pad > 0);
       if (split) continue;                       // writes its sub-filters itself

@@ -81,6 +81,8 @@ struct WgradGeom {
   // gradient that follows needs it).  Both null: no side job.
   const void* flip_w;       // dtype
   void* flip_wt;            // dtype
+  // Optional side job: extra workgroups add up the parts of an earlier weight gradient.
+  ReduceJob side;
 };
 size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s);
 // If `deferred` is given and the gradient is split over the minibatch, the reduction of the

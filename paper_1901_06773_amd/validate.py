@@ -223,7 +223,8 @@ def format_report(rep):
         lines.append(f"  {r['t_ms']:8.1f}{r['pool_bytes'] / 2**30:10.2f}{r['bytes_out'] / 2**30:10.2f}{r['bytes_in'] / 2**30:10.2f}")
     lines.append(f"  peak: {rep['memory_observed']['peak_dynamic_bytes'] / 2**30:.2f} GiB observed order, "
                  f"{rep['memory_predicted']['peak_dynamic_bytes'] / 2**30:.2f} GiB predicted order, "
-                 f"{(rep['plan']['peak_bytes'] - rep['plan']['static_bytes']) / 2**30:.2f} GiB planned")
+                 f"{(rep['plan']['peak_bytes'] - rep['plan']['static_bytes']) / 2**30:.2f} GiB the planner's sum of live bytes "
+                 f"(a map being copied out is no longer in that sum)")
     return "\n".join(lines)
 
 

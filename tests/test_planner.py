@@ -550,7 +550,10 @@ def test_simulated_timeline_is_consistent_with_the_plan(budget_gib):
     summ = V.timeline_summary(tl)
     assert summ["t_compute"] == pytest.approx(s["t_compute"], rel=1e-9)
     mem = V.memory_curve(ctx, observed=False, points=200)
-    assert 0.5 * (s["peak_bytes"] - s["static_bytes"]) < mem["peak_dynamic_bytes"] <= s["peak_bytes"] - s["static_bytes"]
+    # (a map being copied out still occupies its block although the planner's sum of live bytes
+    # has let go of it, so the replay may exceed that sum, never the pool)
+    cap = min(budget_gib << 30, s["noswap_peak_bytes"]) - s["static_bytes"]
+    assert 0.5 * (s["peak_bytes"] - s["static_bytes"]) < mem["peak_dynamic_bytes"] <= cap
     last = mem["series"][-1]
     assert last["pool_bytes"] == 0 and last["bytes_out"] == last["bytes_in"] == s["bytes_swapped"]
     # a planning-only context has nothing observed
