@@ -72,11 +72,14 @@ def tight_pool(probe, k, s0):
     raise AssertionError("no layout within 25 % of the layer-wise peak")
 
 
-def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=64 * MiB, lr=0.1, explicit=None, dtype=0):
+def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=64 * MiB, lr=0.1, explicit=None, dtype=0,
+            wgrad_stream=True, overlap=True):
     b = B()
     ctx = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w), pool_bytes=pool or budget, host_bytes=host,
-                    dtype=dtype)
+                    dtype=dtype, wgrad_stream=wgrad_stream)
     ctx.set_weights(params)
+    if not overlap:
+        ctx.set_wgrad_overlap(False)
     summ = ctx.plan_explicit(k, budget, explicit) if explicit is not None else ctx.plan_swaps(k, budget, mode)
     losses = []
     for s in range(steps):
@@ -471,6 +474,30 @@ def test_config_resnet152_bf16_under_24_gib():
     b = B()
     plan, out = _budgeted_vs_resident(S.resnet152(), 320, 24 * GiB, expect_swaps=True, dtype=b.BF16, steps=1)
     assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 0
+
+
+@pytest.mark.parametrize("name", ["mini_resnet_w32", "mini_resnet_basic", "wide_chain"])
+def test_weight_gradient_stream_changes_no_bit(name):
+    """Weight gradients on their own stream beside the data gradients (the default), on the
+    compute stream although the context has the extra stream, and in a context created with
+    three streams only: the same losses, gradients and weights, bit for bit, with everything
+    resident and with every map swapped."""
+    make, k = NETS[name]
+    net = make()
+    params = S.init_params(net)
+    b = B()
+    probe = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w))
+    s0 = probe.plan_swaps(k, 1 << 40, b.PLAN_NAIVE_ALL)
+    tight = tight_pool(probe, k, s0)
+    probe.close()
+    for mode, budget in ((b.PLAN_NONE, 512 * MiB), (b.PLAN_NAIVE_ALL, tight)):
+        ref = run_gpu(net, params, k, mode, budget, steps=2)
+        for kw in (dict(overlap=False), dict(wgrad_stream=False)):
+            out = run_gpu(net, params, k, mode, budget, steps=2, **kw)
+            for a, r in zip(out["losses"], ref["losses"]):
+                assert np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
+            bit_equal(out["grads"], ref["grads"], f"gradients {kw}")
+            bit_equal(out["weights"], ref["weights"], f"weights {kw}")
 
 
 # ------------------------------------------------------------------ model validation (Sec. 7.2)
