@@ -14,7 +14,7 @@
 namespace acc {
 namespace {
 
-constexpr int MAX_SLABS = 1024;     // row slabs of the reduction grid (upper bound)
+constexpr int MAX_SLABS = kBnMaxSlabs;   // row slabs of the reduction grid (upper bound)
 constexpr int ROWS_PER_THREAD = 4;  // rows a thread of the reduction sums at least (else fewer slabs)
 constexpr int THREADS = 256;
 constexpr int FIN_CH = THREADS / 64;  // the finishing kernels give every channel one wave
@@ -144,13 +144,13 @@ __device__ __forceinline__ double wave_sum(double v) {
 }
 
 __device__ __forceinline__ void sum_partials(const double* __restrict__ part, int c, int slabs, int ch,
-                                             int lane, double* out0, double* out1) {
+                                             int lane, double* out0, double* out1, int stride = MAX_SLABS) {
   // every load of the lane is issued before the first sum: the partials were written by
   // other compute units a moment ago, so each access pays a full trip to memory
   constexpr int PER_LANE = MAX_SLABS / 64;
   double v0[PER_LANE], v1[PER_LANE];
   const double* p0 = part + (ch < c ? ch : 0);
-  const double* p1 = p0 + (size_t)MAX_SLABS * c;
+  const double* p1 = p0 + (size_t)stride * c;      // part[2][stride][c]
 #pragma unroll
   for (int u = 0; u < PER_LANE; ++u) {
     const int k = lane + 64 * u;
@@ -171,10 +171,10 @@ __device__ __forceinline__ void sum_partials(const double* __restrict__ part, in
 __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
     const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ beta,
     float* __restrict__ mean, float* __restrict__ istd, float* __restrict__ coef, long rows, int c,
-    float eps, int slabs) {
+    float eps, int slabs, int stride) {
   const int ch = blockIdx.x * FIN_CH + threadIdx.x / 64, lane = threadIdx.x & 63;
   double sum, ss;
-  sum_partials(part, c, slabs, ch, lane, &sum, &ss);
+  sum_partials(part, c, slabs, ch, lane, &sum, &ss, stride);
   if (lane != 0 || ch >= c) return;
   const double m = (double)rows;
   const double mu = sum / m;
@@ -299,15 +299,21 @@ namespace {
 
 template <class T>
 hipError_t bn_forward_t(const T* x, const float* gamma, const float* beta, const T* res, T* y, float* mean,
-                        float* istd, long rows, int c, int relu, float eps, void* workspace, hipStream_t st) {
+                        float* istd, long rows, int c, int relu, float eps, void* workspace, hipStream_t st,
+                        const BnSums& ready) {
   double* part = static_cast<double*>(workspace);
   float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
   const ReduceShape rs = reduce_shape(c);
-  const int slabs = slab_count(rows, rs);
-  hipLaunchKernelGGL((bn_reduce_kernel<0, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, (const T*)nullptr,
-                     (const T*)nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
-  hipLaunchKernelGGL(bn_fwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
-                     gamma, beta, mean, istd, coef, rows, c, eps, slabs);
+  const double* sums = part;
+  int slabs = slab_count(rows, rs), stride = MAX_SLABS;
+  if (ready.part) {
+    sums = ready.part; slabs = ready.slabs; stride = ready.stride;   // the producer of x left them there
+  } else {
+    hipLaunchKernelGGL((bn_reduce_kernel<0, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, (const T*)nullptr,
+                       (const T*)nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
+  }
+  hipLaunchKernelGGL(bn_fwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, sums,
+                     gamma, beta, mean, istd, coef, rows, c, eps, slabs, stride);
   const size_t n4 = (size_t)rows * c / 4;
   hipLaunchKernelGGL(bn_apply_kernel<T>, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, res, coef, y, n4, c, relu);
   return hipGetLastError();
@@ -335,15 +341,17 @@ hipError_t bn_backward_t(const T* x, const T* dy, const T* y, const float* gamma
 
 hipError_t bn_forward(const void* x, const float* gamma, const float* beta, const void* res, void* y,
                       float* mean, float* istd, long rows, int c, int relu, float eps, void* workspace,
-                      int dtype, hipStream_t st) {
+                      int dtype, hipStream_t st, const BnSums* ready_sums) {
   if (!x || !gamma || !beta || !y || !mean || !istd || !workspace) return hipErrorInvalidValue;
   if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  const BnSums ready = ready_sums ? *ready_sums : BnSums{nullptr, 0, 0};
+  if (ready.part && (ready.slabs <= 0 || ready.slabs > MAX_SLABS || ready.stride < ready.slabs)) return hipErrorInvalidValue;
   if (dtype == DT_F32)
     return bn_forward_t((const float*)x, gamma, beta, (const float*)res, (float*)y, mean, istd, rows, c, relu, eps,
-                        workspace, st);
+                        workspace, st, ready);
   if (dtype == DT_BF16)
     return bn_forward_t((const bf16_t*)x, gamma, beta, (const bf16_t*)res, (bf16_t*)y, mean, istd, rows, c, relu,
-                        eps, workspace, st);
+                        eps, workspace, st, ready);
   return hipErrorInvalidValue;
 }
 

@@ -420,6 +420,24 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   // epilogue: accumulator register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32 of its 32x32 block
   const int n = n0 + wn0 + (lane & 31);
+  if (g.stats) {
+    // sums of the column and of its squares over the wave's 32 rows (rows beyond M are exact
+    // zeros: their operand rows were zero), for the batch norm that follows: its slab
+    // tile_m * 2 + (0 or 1).  Fixed order: the lane's 16 values, then the partner lane.
+    float sum = 0.f, sq = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      sum += acc[v];
+      sq = fmaf(acc[v], acc[v], sq);
+    }
+    sum += __shfl_xor(sum, 32);
+    sq += __shfl_xor(sq, 32);
+    if (lane < 32 && n < g.n_out) {
+      const size_t slab = (size_t)tile_m * 2 + (wave >> 1);
+      g.stats[slab * g.n_out + n] = (double)sum;
+      g.stats[((size_t)g.stats_stride + slab) * g.n_out + n] = (double)sq;
+    }
+  }
   if (n >= g.n_out) return;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
@@ -442,6 +460,12 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   if (g.side.count) {
     if (!g.side.part || !g.side.dw || g.side.splits < 1) return hipErrorInvalidValue;
     side_blocks = (long)((g.side.count + 1023) / 1024);
+  }
+  if (g.stats) {
+    // dense fp32 result only, and no more slabs than the batch-norm workspace holds
+    if (g.dtype != DT_F32 || g.accumulate || g.out_stride != 1 || g.out_h != g.p || g.out_w != g.q ||
+        conv_stat_slabs((long)g.n_img * g.p * g.q) > g.stats_stride)
+      return hipErrorInvalidValue;
   }
   if (g.flip.wt) {
     if (!g.flip.w || g.flip.cout <= 0 || g.flip.cin <= 0 || g.flip.r <= 0 || g.flip.s <= 0) return hipErrorInvalidValue;

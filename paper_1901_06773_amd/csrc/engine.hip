@@ -43,6 +43,7 @@ struct acc_ctx {
   bool wgrad_overlap = true;           // use s_w when there is one (off: everything on s_c)
   std::vector<hipEvent_t> ev_fork, ev_wdone;   // per conv backward step: its dy is ready / its wgrad is done
   std::vector<char> wgrad_in_flight;   // per step: its wgrad went to s_w in this iteration
+  std::vector<int> bn_ready_slabs;     // per step: a BN forward step finds its sums in its workspace (slab count)
   ReduceJob pending_reduce{nullptr, nullptr, 0, 0};   // parts of the last conv weight gradient, not added up yet
   hipStream_t pending_stream = nullptr;               // ... and the stream that gradient ran on
   hipEvent_t ev_flush = nullptr;
@@ -598,12 +599,30 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.p = T(s.y).h; cg.q = T(s.y).w; cg.n_out = l->cout;
       cg.r = l->r; cg.s = l->s; cg.stride = l->stride; cg.pad = l->pad;
       cg.out_h = cg.p; cg.out_w = cg.q; cg.out_stride = 1; cg.accumulate = 0;
+      // the batch norm that follows takes its sums from this launch (fp32 storage; with bf16
+      // the statistics are those of the rounded values) unless there are more 32-row blocks
+      // than its finishing pass adds up
+      if (s.stats >= 0) {
+        const long rows = (long)k * cg.p * cg.q;
+        const long slabs = conv_stat_slabs(rows);
+        const long stride = (long)k * 2 * (((long)cg.p * cg.q + 63) / 64);
+        const bool fused = slabs <= kBnMaxSlabs && (size_t)2 * stride * l->cout * sizeof(double) <= c->plan.tbytes[s.stats];
+        c->bn_ready_slabs[s.stats_for] = fused ? (int)slabs : 0;
+        if (fused) { cg.stats = (double*)ptr(s.stats); cg.stats_stride = (int)stride; }
+      }
       return igemm(cg, conv_flops);
     }
     case K_BN_F: {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
+      BnSums ready{nullptr, 0, 0};
+      if (s.stats >= 0 && c->bn_ready_slabs[j] > 0) {
+        ready.part = (const double*)ptr(s.stats);
+        ready.slabs = c->bn_ready_slabs[j];
+        ready.stride = (int)((long)k * 2 * (((long)T(s.x).h * T(s.x).w + 63) / 64));
+      }
       return bn_forward(ptr(s.x), w, w + l->cin, ptr(s.res), ptr(s.y), stat, stat + l->cin,
-                        (long)k * T(s.x).h * T(s.x).w, l->cin, s.relu, 1e-5f, ptr(s.ws), dt, st);
+                        (long)k * T(s.x).h * T(s.x).w, l->cin, s.relu, 1e-5f, ptr(s.ws), dt, st,
+                        ready.part ? &ready : nullptr);
     }
     case K_MAXPOOL_F:
       return maxpool_forward(ptr(s.x), ptr(s.y), k, T(s.x).h, T(s.x).w, T(s.x).c, l->r, l->s, l->stride, l->pad, dt, st);
@@ -781,6 +800,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
     }
   }
   uint64_t bytes_out = 0, bytes_in = 0;
+  c->bn_ready_slabs.assign(ns, 0);
   c->pending_reduce = ReduceJob{nullptr, nullptr, 0, 0};
   c->kprobes_used = 0;
   if (c->kernel_profiling) {

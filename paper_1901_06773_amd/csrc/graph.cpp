@@ -253,6 +253,21 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
     steps.push_back(s);
   }
   n_fwd = (int)steps.size();
+  // A convolution whose output feeds the next step's batch norm hands it the per-channel sums
+  // of every block of 32 rows (fp32 storage): part[2][stride][cout] doubles with
+  // stride = k * 2 * ceil(Ho*Wo / 64) >= 2 * ceil(k*Ho*Wo / 64) blocks.
+  if (dtype == ACC_F32)
+    for (int j = 0; j + 1 < n_fwd; ++j) {
+      if (steps[j].kind != K_CONV_F || steps[j + 1].kind != K_BN_F || steps[j + 1].x != steps[j].y) continue;
+      const Tensor& y = tensors[steps[j].y];
+      const size_t per_image = (size_t)2 * 2 * (((size_t)y.h * y.w + 63) / 64) * y.c * sizeof(double);
+      const int t = new_tensor(T_WORK, 0, 0, 0, per_image, 0, steps[j].layer);
+      steps[j].stats_for = j + 1;
+      steps[j].stats = t;
+      steps[j + 1].stats = t;
+      steps[j].writes.push_back(t);
+      steps[j + 1].reads.push_back(t);
+    }
 
   // ---- backward steps: reverse order; grad_of[t] is the tensor holding d(loss)/d(t)
   std::vector<int> grad_of(tensors.size() + 4 * n, -1);

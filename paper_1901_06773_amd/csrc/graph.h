@@ -54,6 +54,10 @@ struct Step {
   // this step waits for;
   // flip_for: the later conv backward step whose flipped filter this step's data-gradient
   // launch writes on the side (-1: none); flips_itself: nobody did it for this step.
+  // Conv forward steps whose result goes into a batch norm (fp32 storage): stats_for is that
+  // step, stats the tensor in which the conv launch leaves the per-channel partial sums for
+  // it (set on both steps).
+  int stats_for = -1, stats = -1;
   int wgrad_join = -1;
   std::vector<int> joins;
   int flip_for = -1;

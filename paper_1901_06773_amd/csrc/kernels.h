@@ -54,6 +54,21 @@ struct ConvGeom {
   // (independent data; saves launches of their own).
   ReduceJob side;
   FlipJob flip;
+  // Optional (fp32 storage, plain dense output): per-channel sums of the result and of its
+  // square over every block of 32 rows, as the batch norm that follows wants them:
+  // stats[0][b][n] = sum, stats[1][b][n] = sum of squares, b < conv_stat_slabs(rows), layout
+  // double[2][stats_stride][n_out] with stats_stride >= conv_stat_slabs(rows).
+  double* stats;
+  int stats_stride;
+};
+// Largest number of row slabs a batch-norm statistics pass adds up.
+constexpr int kBnMaxSlabs = 1024;
+// Number of 32-row blocks conv_igemm writes sums for (2 per 64-row tile).
+inline long conv_stat_slabs(long rows) { return ((rows + 63) / 64) * 2; }
+// Partial sums some other kernel has left for a batch norm: part[2][stride][c], `slabs` of them valid.
+struct BnSums {
+  const double* part;
+  int slabs, stride;
 };
 
 // Optional probe of one launch: which template instance ran (index into conv_variant_name())
@@ -104,9 +119,11 @@ hipError_t filter_gather_transpose(const void* w, void* wt, int cout, int cin, i
 // Batch norm over rows x c (NHWC flattened).  workspace: bn_workspace_bytes(c).
 // x, res, y, dy, dx, g_out: dtype; gamma, beta, mean, istd, dgamma, dbeta: fp32.
 size_t bn_workspace_bytes(int c);
+// ready_sums (may be null): the partial sums of x and x*x are already there (conv_igemm wrote
+// them, ConvGeom::stats) and are not computed again.
 hipError_t bn_forward(const void* x, const float* gamma, const float* beta, const void* res,
                       void* y, float* mean, float* istd, long rows, int c, int relu, float eps,
-                      void* workspace, int dtype, hipStream_t st);
+                      void* workspace, int dtype, hipStream_t st, const BnSums* ready_sums = nullptr);
 hipError_t bn_backward(const void* x, const void* dy, const void* y, const float* gamma,
                        const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
                        void* g_out, long rows, int c, void* workspace, int dtype, hipStream_t st);
