@@ -193,10 +193,10 @@ __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
 __global__ __launch_bounds__(THREADS) void bn_bwd_finish_kernel(
     const double* __restrict__ part, const float* __restrict__ gamma, const float* __restrict__ istd,
     float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef, long rows, int c,
-    int slabs) {
+    int slabs, int stride) {
   const int ch = blockIdx.x * FIN_CH + threadIdx.x / 64, lane = threadIdx.x & 63;
   double db, dg;
-  sum_partials(part, c, slabs, ch, lane, &db, &dg);
+  sum_partials(part, c, slabs, ch, lane, &db, &dg, stride);
   if (lane != 0 || ch >= c) return;
   dbeta[ch] = (float)db;
   dgamma[ch] = (float)dg;
@@ -322,15 +322,20 @@ hipError_t bn_forward_t(const T* x, const float* gamma, const float* beta, const
 template <class T>
 hipError_t bn_backward_t(const T* x, const T* dy, const T* y, const float* gamma, const float* mean,
                          const float* istd, T* dx, float* dgamma, float* dbeta, T* g_out, long rows, int c,
-                         void* workspace, hipStream_t st) {
+                         void* workspace, hipStream_t st, const BnSums& ready) {
   double* part = static_cast<double*>(workspace);
   float* coef = reinterpret_cast<float*>(part + (size_t)2 * MAX_SLABS * c);
   const ReduceShape rs = reduce_shape(c);
-  const int slabs = slab_count(rows, rs);
-  hipLaunchKernelGGL((bn_reduce_kernel<1, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
-                     istd, part, rows, c, rs.tpr, rs.rpi, slabs);
-  hipLaunchKernelGGL(bn_bwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, part,
-                     gamma, istd, dgamma, dbeta, coef, rows, c, slabs);
+  const double* sums = part;
+  int slabs = slab_count(rows, rs), stride = MAX_SLABS;
+  if (ready.part) {
+    sums = ready.part; slabs = ready.slabs; stride = ready.stride;   // the data gradient left them there
+  } else {
+    hipLaunchKernelGGL((bn_reduce_kernel<1, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
+                       istd, part, rows, c, rs.tpr, rs.rpi, slabs);
+  }
+  hipLaunchKernelGGL(bn_bwd_finish_kernel, dim3((c + FIN_CH - 1) / FIN_CH), dim3(THREADS), 0, st, sums,
+                     gamma, istd, dgamma, dbeta, coef, rows, c, slabs, stride);
   const size_t n4 = (size_t)rows * c / 4;
   hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3(apply_grid(n4)), dim3(THREADS), 0, st, x, dy, y, mean, istd,
                      coef, dx, g_out, n4, c);
@@ -357,16 +362,19 @@ hipError_t bn_forward(const void* x, const float* gamma, const float* beta, cons
 
 hipError_t bn_backward(const void* x, const void* dy, const void* y, const float* gamma, const float* mean,
                        const float* istd, void* dx, float* dgamma, float* dbeta, void* g_out, long rows, int c,
-                       void* workspace, int dtype, hipStream_t st) {
+                       void* workspace, int dtype, hipStream_t st, const BnSums* ready_sums) {
   if (!x || !dy || !gamma || !mean || !istd || !dx || !dgamma || !dbeta || !workspace)
     return hipErrorInvalidValue;
   if (rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  const BnSums ready = ready_sums ? *ready_sums : BnSums{nullptr, 0, 0};
+  if (ready.part && (y || ready.slabs <= 0 || ready.slabs > MAX_SLABS || ready.stride < ready.slabs))
+    return hipErrorInvalidValue;
   if (dtype == DT_F32)
     return bn_backward_t((const float*)x, (const float*)dy, (const float*)y, gamma, mean, istd, (float*)dx, dgamma,
-                         dbeta, (float*)g_out, rows, c, workspace, st);
+                         dbeta, (float*)g_out, rows, c, workspace, st, ready);
   if (dtype == DT_BF16)
     return bn_backward_t((const bf16_t*)x, (const bf16_t*)dy, (const bf16_t*)y, gamma, mean, istd, (bf16_t*)dx,
-                         dgamma, dbeta, (bf16_t*)g_out, rows, c, workspace, st);
+                         dgamma, dbeta, (bf16_t*)g_out, rows, c, workspace, st, ready);
   return hipErrorInvalidValue;
 }
 

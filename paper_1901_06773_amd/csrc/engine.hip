@@ -670,6 +670,13 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
                               l->stride, l->pad, s.dx_accumulate, dt, st);
     case K_BN_B: {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
+      if (s.bnb >= 0 && c->bn_ready_slabs[j] > 0) {
+        // the data gradient before this step masked dy and left the sums
+        BnSums ready{(const double*)ptr(s.bnb), c->bn_ready_slabs[j],
+                     (int)((long)k * 2 * (((long)T(s.x).h * T(s.x).w + 63) / 64))};
+        return bn_backward(ptr(s.x), ptr(s.dy), nullptr, w, stat, stat + l->cin, ptr(s.dx), dw, dw + l->cin, nullptr,
+                           (long)k * T(s.x).h * T(s.x).w, l->cin, ptr(s.ws), dt, st, &ready);
+      }
       return bn_backward(ptr(s.x), ptr(s.dy), ptr(s.y), w, stat, stat + l->cin, ptr(s.dx), dw, dw + l->cin,
                          s.g_inplace ? ptr(s.dy) : nullptr, (long)k * T(s.x).h * T(s.x).w, l->cin, ptr(s.ws), dt, st);
     }
@@ -754,6 +761,21 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       }
       if (l->stride == 1) {
         cg.p = h; cg.q = wd; cg.pad = l->r - 1 - l->pad; cg.out_stride = 1;
+        // the batch norm whose ReLU output was this convolution's input gets its backward sums
+        // (and the masked gradient) from this launch, unless there are more 32-row blocks than
+        // its finishing pass adds up
+        if (s.bnb >= 0) {
+          const Step& bb = g.steps[s.bnb_for];
+          const long rows = (long)k * h * wd;
+          const long slabs = conv_stat_slabs(rows);
+          const long stride = (long)k * 2 * (((long)h * wd + 63) / 64);
+          const bool fused = slabs <= kBnMaxSlabs && (size_t)2 * stride * l->cin * sizeof(double) <= c->plan.tbytes[s.bnb];
+          c->bn_ready_slabs[s.bnb_for] = fused ? (int)slabs : 0;
+          if (fused) {
+            const float* stat = c->d_stats + g.params[bb.layer].stat_offset;
+            cg.bnb = BnBackwardSums{ptr(bb.x), ptr(s.x), stat, stat + l->cin, (double*)ptr(s.bnb), (int)stride};
+          }
+        }
       } else {  // 1x1, pad 0: dense product on the strided positions, zeros elsewhere
         cg.p = ho; cg.q = wo; cg.pad = 0; cg.out_stride = l->stride;
         if (!s.dx_accumulate) {

@@ -402,6 +402,26 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
     steps.push_back(u);
   }
 
+  // ---- the data gradient of a stride-1 convolution hands the batch norm before it (the one
+  //      whose ReLU output is the convolution's only input) the sums its backward pass needs
+  if (dtype == ACC_F32)
+    for (int j = n_fwd; j + 1 < (int)steps.size(); ++j) {
+      Step& cb = steps[j];
+      Step& bb = steps[j + 1];
+      if (cb.kind != K_CONV_B || cb.dx < 0 || cb.dx_accumulate || bb.kind != K_BN_B) continue;
+      const acc_layer& cl = layers[cb.layer];
+      if (cl.stride != 1 || bb.dy != cb.dx || !bb.relu || bb.res >= 0 || bb.g_inplace || bb.y != cb.x) continue;
+      const Tensor& bx = tensors[bb.x];
+      const size_t per_image = (size_t)2 * 2 * (((size_t)bx.h * bx.w + 63) / 64) * bx.c * sizeof(double);
+      const int t = new_tensor(T_WORK, 0, 0, 0, per_image, 0, bb.layer);
+      cb.bnb_for = j + 1;
+      cb.bnb = t;
+      bb.bnb = t;
+      cb.writes.push_back(t);
+      if (std::find(cb.reads.begin(), cb.reads.end(), bb.x) == cb.reads.end()) cb.reads.push_back(bb.x);
+      bb.reads.push_back(t);
+    }
+
   // ---- weight gradients beside the data gradients: join points, operands kept until then,
   //      and the flipped filter of the next conv backward step written one step early
   {

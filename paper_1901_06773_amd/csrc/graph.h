@@ -58,6 +58,11 @@ struct Step {
   // step, stats the tensor in which the conv launch leaves the per-channel partial sums for
   // it (set on both steps).
   int stats_for = -1, stats = -1;
+  // Conv backward steps (fp32 storage, stride 1) whose data gradient is the gradient of a
+  // batch norm's ReLU output, that batch norm's backward being the next step: bnb_for is that
+  // step, bnb the tensor in which the data-gradient launch leaves the sums of the masked
+  // gradient g and of g * xhat for it (set on both steps); the launch also applies the mask.
+  int bnb_for = -1, bnb = -1;
   int wgrad_join = -1;
   std::vector<int> joins;
   int flip_for = -1;

@@ -31,6 +31,21 @@ struct FlipJob {
   int cout, cin, r, s;
 };
 
+// Optional work of a data-gradient launch for the batch norm (with ReLU) whose output was the
+// convolution's input: the result is the gradient of that output, so the launch masks it with
+// [y > 0] before storing it and leaves, per block of 32 rows and per channel, the sums of the
+// masked gradient g and of g * xhat (xhat = (x - mean) * istd) in sums[2][stride][n_out]
+// (doubles; stride >= conv_stat_slabs(rows)).  x, y: the batch norm's input and output, laid
+// out like the launch's dense output.  sums == nullptr: off.
+struct BnBackwardSums {
+  const void* x;
+  const void* y;
+  const float* mean;
+  const float* istd;
+  double* sums;
+  int stride;
+};
+
 // Implicit-GEMM view of a convolution-like gather:
 //   out[m][n] (+)= sum_{r,t,c} in[img, p*stride+r-pad, q*stride+t-pad, c] * w[n][(r,t,c)]
 // with row m = (img, p, q) over a P x Q grid (columns use pad + pad_dx).  The result row is
@@ -60,6 +75,7 @@ struct ConvGeom {
   // double[2][stats_stride][n_out] with stats_stride >= conv_stat_slabs(rows).
   double* stats;
   int stats_stride;
+  BnBackwardSums bnb;   // fp32 storage, plain dense output, no accumulation
 };
 // Largest number of row slabs a batch-norm statistics pass adds up.
 constexpr int kBnMaxSlabs = 1024;
@@ -124,9 +140,12 @@ size_t bn_workspace_bytes(int c);
 hipError_t bn_forward(const void* x, const float* gamma, const float* beta, const void* res,
                       void* y, float* mean, float* istd, long rows, int c, int relu, float eps,
                       void* workspace, int dtype, hipStream_t st, const BnSums* ready_sums = nullptr);
+// ready_sums (may be null): the sums of g and g * xhat are already there (a data-gradient launch
+// wrote them, ConvGeom::bnb, and masked dy); they are not computed again, and y must be null.
 hipError_t bn_backward(const void* x, const void* dy, const void* y, const float* gamma,
                        const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
-                       void* g_out, long rows, int c, void* workspace, int dtype, hipStream_t st);
+                       void* g_out, long rows, int c, void* workspace, int dtype, hipStream_t st,
+                       const BnSums* ready_sums = nullptr);
 
 hipError_t maxpool_forward(const void* x, void* y, int n, int h, int wd, int c, int r, int s,
                            int stride, int pad, int dtype, hipStream_t st);

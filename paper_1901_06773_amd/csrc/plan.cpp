@@ -38,7 +38,7 @@ struct Seg {
 
 class Arena {
  public:
-  explicit Arena(size_t cap) { free_.push_back({0, cap, -1, -1}); }
+  explicit Arena(size_t cap, bool best_fit = false) : best_fit_(best_fit) { free_.push_back({0, cap, -1, -1}); }
 
   // First fit; blocks whose offload has a sequence number above `ready_d2h` (still being
   // copied out) are used only if nothing else fits.
@@ -55,6 +55,22 @@ class Arena {
     auto usable = [&](int q) { return free_[q].tag_d2h <= limit; };
     *dstep = -1;
     *dd2h = -1;
+    if (best_fit_ && need > 0) {
+      // maximal runs of adjacent usable segments; the smallest one that holds the block wins
+      // (bottom-up blocks sit at its low end, top-down blocks at its high end)
+      int bi = -1, bj = -1;
+      size_t bsize = 0;
+      for (int i = 0; i < n;) {
+        if (!usable(i)) { ++i; continue; }
+        int j = i;
+        size_t total = free_[i].size;
+        while (j + 1 < n && usable(j + 1) && free_[j + 1].off == free_[j].off + free_[j].size) total += free_[++j].size;
+        if (total >= need && (bi < 0 || total < bsize)) { bi = i; bj = j; bsize = total; }
+        i = j + 1;
+      }
+      if (bi < 0) return false;
+      return take_from_run(bi, bj, need, top, off, dstep, dd2h);
+    }
     if (!top) {
       int i = 0;
       while (i < n) {
@@ -118,6 +134,34 @@ class Arena {
     return false;
   }
 
+  // carves `need` bytes out of the run of adjacent segments [i, j]: from its low end, or from its
+  // high end for top-down blocks; segments that are used up disappear, one may shrink
+  bool take_from_run(int i, int j, size_t need, bool top, size_t* off, int* dstep, int* dd2h) {
+    size_t left = need;
+    if (!top) {
+      *off = free_[i].off;
+      int q = i;
+      while (left > 0) {
+        *dstep = std::max(*dstep, free_[q].tag_step);
+        *dd2h = std::max(*dd2h, free_[q].tag_d2h);
+        if (free_[q].size <= left) { left -= free_[q].size; ++q; }
+        else { free_[q].off += left; free_[q].size -= left; left = 0; }
+      }
+      free_.erase(free_.begin() + i, free_.begin() + q);
+    } else {
+      *off = free_[j].off + free_[j].size - need;
+      int q = j;
+      while (left > 0) {
+        *dstep = std::max(*dstep, free_[q].tag_step);
+        *dd2h = std::max(*dd2h, free_[q].tag_d2h);
+        if (free_[q].size <= left) { left -= free_[q].size; --q; }
+        else { free_[q].size -= left; left = 0; }
+      }
+      free_.erase(free_.begin() + q + 1, free_.begin() + j + 1);   // the segments used up entirely
+    }
+    return true;
+  }
+
   void release(size_t off, size_t size, int tag_step, int tag_d2h) {
     Seg s{off, size, tag_step, tag_d2h};
     auto it = std::lower_bound(free_.begin(), free_.end(), s,
@@ -139,6 +183,7 @@ class Arena {
 
  private:
   std::vector<Seg> free_;
+  bool best_fit_ = false;
 };
 
 enum TState { TS_NONE = 0, TS_FWD, TS_OFFLOADED, TS_RESIDENT, TS_DEAD };
@@ -163,7 +208,7 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
   const size_t stat = g.static_bytes();
   if (!opt.unlimited && budget < stat + 256) { *why = "budget below the resident parameters and gradients"; return false; }
   const size_t cap = opt.unlimited ? ((size_t)1 << 56) : ((budget - stat) & ~(size_t)255);
-  Arena arena(cap);
+  Arena arena(cap, opt.best_fit);
 
   std::vector<int> st(nt, TS_NONE), d2h_of(nt, -1), h2d_of(nt, -1);
   std::vector<size_t> cur_off(nt, 0);
@@ -380,6 +425,9 @@ bool build_plan(const Graph& g, int k, size_t budget, const std::vector<uint8_t>
   PlanOptions jit = opt;
   jit.lookahead = false;
   std::string why2;
+  if (build_plan_once(g, k, budget, swap_of_tensor, jit, out, &why2)) { *why = ""; return true; }
+  // ... and if first fit still cannot place a step, best fit, which fragments less
+  jit.best_fit = true;
   if (build_plan_once(g, k, budget, swap_of_tensor, jit, out, &why2)) { *why = ""; return true; }
   return false;
 }

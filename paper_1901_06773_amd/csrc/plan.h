@@ -76,6 +76,9 @@ struct PlanOptions {
   // this many bytes (kept free for the working set of the steps in between), in the order
   // of their first use, instead of running the allocations of whole steps ahead.
   size_t eager_headroom = 0;
+  // Among the free runs that are large enough take the smallest instead of the first (less
+  // fragmentation; tried when first fit cannot place a step).
+  bool best_fit = false;
 };
 
 // Builds instruction list and placement for a fixed swap set.  Returns false (and why)
