@@ -1,4 +1,4 @@
-// CPU oracle: one SGD training step of a bottleneck ResNet, written out as the
+// CPU oracle: one SGD training step of a layer list (ResNets, VGG), written out as the
 // plain definitions of its layers.  TEST INFRASTRUCTURE ONLY: the product path
 // never links, loads or calls this file; it shares no code with the HIP library.
 //
@@ -9,7 +9,7 @@
 // textbook forward / backward / SGD step of the network.
 //
 // Conventions: NCHW activations, OIHW filters, cross-correlation with zero
-// padding and no bias, batch-norm with minibatch statistics (biased variance,
+// padding and no bias (a per-channel bias is a layer of its own), batch-norm with minibatch statistics (biased variance,
 // eps passed in), first-maximum tie-break in max-pooling, ReLU'(0) = 0.
 // Storage type T is float or double; every reduction (dot products, means,
 // sums over the minibatch, log-sum-exp) is accumulated in double and rounded to
@@ -26,7 +26,7 @@
 
 namespace {
 
-enum Kind { CONV = 0, BN = 1, RELU = 2, ADD = 3, MAXPOOL = 4, GAP = 5, FC = 6, SOFTMAX_CE = 7 };
+enum Kind { CONV = 0, BN = 1, RELU = 2, ADD = 3, MAXPOOL = 4, GAP = 5, FC = 6, SOFTMAX_CE = 7, BIAS = 8 };
 
 struct LayerRec {  // same field order as the int32[9] record handed in
   int kind, in0, in1, cin, cout, r, s, stride, pad;
@@ -379,6 +379,15 @@ int train_step(const int32_t* recs, int nl, int in_c, int in_h, int in_w, int k,
         out[i].assign(k * a.per_image(), (T)0);
         relu_fwd(x, out[i].data(), out[i].size());
         break;
+      case BIAS: {
+        // y[n,c,h,w] = x[n,c,h,w] + b[c]
+        if (a.c != l.cin) return -(1 + i);
+        shp[i] = a;
+        out[i].resize(k * a.per_image());
+        const size_t hw = (size_t)a.h * a.w;
+        for (size_t e = 0; e < out[i].size(); ++e) out[i][e] = (T)((double)x[e] + (double)params[i][(e / hw) % a.c]);
+        break;
+      }
       case ADD: {
         const Shape b = in_shape(l.in1);
         if (a.c != b.c || a.h != b.h || a.w != b.w) return -(1 + i);
@@ -452,6 +461,17 @@ int train_step(const int32_t* recs, int nl, int in_c, int in_h, int in_w, int k,
       case RELU:
         if (dx) relu_bwd(out[i].data(), dy, dx, out[i].size());
         break;
+      case BIAS: {
+        // db[c] = sum over n, h, w of dy; dx += dy
+        gpar[i].assign((size_t)a.c, (T)0);
+        const size_t hw = (size_t)a.h * a.w;
+        std::vector<double> db((size_t)a.c, 0.0);
+        for (size_t e = 0; e < out[i].size(); ++e) db[(e / hw) % a.c] += (double)dy[e];
+        for (int c = 0; c < a.c; ++c) gpar[i][c] = (T)db[c];
+        if (dx)
+          for (size_t e = 0; e < out[i].size(); ++e) dx[e] = (T)((double)dx[e] + (double)dy[e]);
+        break;
+      }
       case ADD: {
         T* dx1 = grad_of(l.in1);
         for (size_t e = 0; e < out[i].size(); ++e) {

@@ -6,14 +6,14 @@ records that describe a network, and the recipe for weights / images / labels.
 """
 from .rng import splitmix64, uniform01, normal, labels_uniform
 from .netspec import (
-    CONV, BN, RELU, ADD, MAXPOOL, GAP, FC, SOFTMAX_CE, KIND_NAMES,
-    Layer, NetSpec, bottleneck_unit, resnet, resnet18, resnet34, resnet50, resnet101, resnet152,
+    CONV, BN, RELU, ADD, MAXPOOL, GAP, FC, SOFTMAX_CE, BIAS, KIND_NAMES,
+    Layer, NetSpec, bottleneck_unit, vgg, vgg16, resnet, resnet18, resnet34, resnet50, resnet101, resnet152,
     param_count, init_params, make_batch,
 )
 
 __all__ = [
     "splitmix64", "uniform01", "normal", "labels_uniform",
-    "CONV", "BN", "RELU", "ADD", "MAXPOOL", "GAP", "FC", "SOFTMAX_CE", "KIND_NAMES",
-    "Layer", "NetSpec", "bottleneck_unit", "resnet", "resnet18", "resnet34", "resnet50", "resnet101",
+    "CONV", "BN", "RELU", "ADD", "MAXPOOL", "GAP", "FC", "SOFTMAX_CE", "BIAS", "KIND_NAMES",
+    "Layer", "NetSpec", "bottleneck_unit", "vgg", "vgg16", "resnet", "resnet18", "resnet34", "resnet50", "resnet101",
     "resnet152", "param_count", "init_params", "make_batch",
 ]

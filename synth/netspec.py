@@ -13,8 +13,8 @@ import numpy as np
 
 from .rng import normal, labels_uniform, splitmix64
 
-CONV, BN, RELU, ADD, MAXPOOL, GAP, FC, SOFTMAX_CE = range(8)
-KIND_NAMES = ["conv", "bn", "relu", "add", "maxpool", "gap", "fc", "softmax_ce"]
+CONV, BN, RELU, ADD, MAXPOOL, GAP, FC, SOFTMAX_CE, BIAS = range(9)
+KIND_NAMES = ["conv", "bn", "relu", "add", "maxpool", "gap", "fc", "softmax_ce", "bias"]
 
 
 @dataclass
@@ -60,6 +60,8 @@ class NetSpec:
                 out.append(2 * l.cin)
             elif l.kind == FC:
                 out.append(l.cout * l.cin + l.cout)
+            elif l.kind == BIAS:
+                out.append(l.cin)
             else:
                 out.append(0)
         return out
@@ -142,6 +144,36 @@ def resnet(blocks=(3, 4, 6, 3), in_c: int = 3, in_hw: int = 224, classes: int = 
     return net
 
 
+def vgg(cfg=((64, 64), (128, 128), (256, 256, 256), (512, 512, 512), (512, 512, 512)), in_c: int = 3,
+        in_hw: int = 224, classes: int = 1000, fc: int = 4096, name: str = "") -> NetSpec:
+    """VGG-style network: stages of 3x3 convolutions (padding 1) with a per-channel bias and
+    ReLU, a 2x2 / 2 max-pool after every stage, then FC-ReLU-FC-ReLU-FC over the flattened map
+    and softmax cross-entropy.  The default is configuration D of Simonyan & Zisserman (16
+    weight layers).  Dropout is not part of the step here."""
+    net = NetSpec(name or f"vgg_{sum(len(st) for st in cfg) + 3}", in_c, in_hw, in_hw, classes)
+    x, c, hw = -1, in_c, in_hw
+    for stage in cfg:
+        for cout in stage:
+            x = net.add(Layer(CONV, in0=x, cin=c, cout=cout, r=3, s=3, stride=1, pad=1))
+            x = net.add(Layer(BIAS, in0=x, cin=cout, cout=cout))
+            x = net.add(Layer(RELU, in0=x, cin=cout, cout=cout))
+            c = cout
+        x = net.add(Layer(MAXPOOL, in0=x, cin=c, cout=c, r=2, s=2, stride=2, pad=0))
+        hw //= 2
+    feat = c * hw * hw
+    for width in (fc, fc):
+        x = net.add(Layer(FC, in0=x, cin=feat, cout=width))
+        x = net.add(Layer(RELU, in0=x, cin=width, cout=width))
+        feat = width
+    x = net.add(Layer(FC, in0=x, cin=feat, cout=classes))
+    net.add(Layer(SOFTMAX_CE, in0=x, cin=classes, cout=1))
+    return net
+
+
+def vgg16(**kw) -> NetSpec:
+    return vgg(name="vgg16", **kw)
+
+
 def resnet18(**kw) -> NetSpec:
     return resnet((2, 2, 2, 2), name="resnet18", block="basic", **kw)
 
@@ -173,6 +205,7 @@ def _layer_seed(seed: int, layer_id: int) -> int:
 def init_params(net: NetSpec, seed: int = 42) -> List[np.ndarray]:
     """One float32 array per layer (empty for parameter-free layers).
     conv: OIHW weights ~ N(0, 2/fan_in), fan_in = cin*r*s.
+    bias: C zeros.
     bn:   [gamma (C ones) | beta (C zeros)].
     fc:   [W (cout x cin, row major) ~ N(0, 2/cin) | b (cout zeros)].
     Layer i draws from its own stream, seeded by output i of splitmix64(seed)."""
@@ -189,6 +222,8 @@ def init_params(net: NetSpec, seed: int = 42) -> List[np.ndarray]:
             std = np.sqrt(2.0 / l.cin)
             w = (normal(_layer_seed(seed, i), n) * std).astype(np.float32)
             out.append(np.concatenate([w, np.zeros(l.cout, np.float32)]))
+        elif l.kind == BIAS:
+            out.append(np.zeros(l.cin, np.float32))
         else:
             out.append(np.zeros(0, np.float32))
     return out

@@ -17,6 +17,8 @@ NETS = {
     "mini_resnet_v1": lambda: S.resnet((1, 2), in_hw=20, classes=7, width=4),
     "mini_resnet_v15": lambda: S.resnet((2, 1), in_hw=18, classes=5, width=4, variant="v1.5"),
     "mini_resnet_basic": lambda: S.resnet((2, 1), in_hw=20, classes=6, width=4, block="basic"),
+    # conv + bias + ReLU stages, 2x2 max-pools, three FC layers over the flattened map
+    "mini_vgg": lambda: S.vgg(cfg=((4, 4), (6,)), in_c=3, in_hw=12, classes=5, fc=10),
 }
 
 
@@ -34,6 +36,8 @@ def perturbed_params(net, seed=42):
             params[i] = (params[i] + 0.2 * rng.standard_normal(params[i].size)).astype(np.float32)
         if l.kind == S.FC:
             params[i][-l.cout:] = 0.1 * rng.standard_normal(l.cout)
+        if l.kind == S.BIAS:
+            params[i] = (0.1 * rng.standard_normal(l.cin)).astype(np.float32)
     return params
 
 
@@ -61,6 +65,8 @@ def torch_step(net, params, img, lab, eps=O.BN_EPS):
             y = F.relu(x)
         elif l.kind == S.ADD:
             y = x + get(l.in1)
+        elif l.kind == S.BIAS:
+            y = x + p.view(1, -1, 1, 1)
         elif l.kind == S.MAXPOOL:
             y = F.max_pool2d(x, l.r, l.stride, l.pad)
         elif l.kind == S.GAP:
@@ -194,6 +200,8 @@ def test_resnet_specs_match_published_parameter_counts():
     # the basic-block networks (two 3x3 convolutions per block): 11.69 M / 21.80 M
     assert S.param_count(S.resnet18()) == 11_689_512
     assert S.param_count(S.resnet34()) == 21_797_672
+    # configuration D of the VGG paper ("138M" in its table of parameter counts)
+    assert S.param_count(S.vgg16()) == 138_357_544
     net = S.bottleneck_unit()
     assert [l.kind for l in net.layers][:11] == [S.CONV, S.BN, S.RELU, S.CONV, S.BN, S.RELU,
                                                   S.CONV, S.BN, S.ADD, S.RELU, S.GAP]
