@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--k", default="auto", help="headline minibatch, or 'auto' = best of the sweep")
     ap.add_argument("--sweep", default="32,64,128,256", help="minibatch sizes of the sweep (configs[3])")
     ap.add_argument("--budget-gib", type=float, default=8.0)
-    ap.add_argument("--net", default="resnet152", choices=["resnet18", "resnet34", "resnet50", "resnet101", "resnet152"])
+    ap.add_argument("--net", default="resnet152", choices=["vgg16", "resnet18", "resnet34", "resnet50", "resnet101", "resnet152"])
     ap.add_argument("--mode", default="dynamic", choices=["dynamic", "naive", "none"])
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage of activations / gradients / kernel-side weights (bf16: configs[4])")

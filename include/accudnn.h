@@ -43,7 +43,7 @@ typedef enum {
 
 /* layer kinds of a network record */
 enum { ACC_CONV = 0, ACC_BN = 1, ACC_RELU = 2, ACC_ADD = 3, ACC_MAXPOOL = 4, ACC_GAP = 5,
-       ACC_FC = 6, ACC_SOFTMAX_CE = 7 };
+       ACC_FC = 6, ACC_SOFTMAX_CE = 7, ACC_BIAS = 8 };
 enum { ACC_F32 = 0, ACC_BF16 = 1 };
 /* planner modes: keep everything / swap every feature map (the "naive" strategy of
  * Sec. 4.1) / performance-model-guided choice (the "dynamic" strategy, Sec. 4.1, 4.4, 5.1) */

@@ -471,12 +471,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     }
   }
   if (n >= g.n_out) return;
+  const float bias_n = g.bias ? g.bias[n] : 0.f;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int m = m0 + wm0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
     if (m >= M) continue;
     T* o = static_cast<T*>(g.out) + out_row_offset(g, m) + n;
-    float val = acc[v];
+    float val = acc[v] + bias_n;
+    if (g.relu) val = fmaxf(val, 0.f);
     if (g.accumulate) val += Elem<T>::load(o);
     Elem<T>::store(o, val);
   }
@@ -493,6 +495,7 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
     if (!g.side.part || !g.side.dw || g.side.splits < 1) return hipErrorInvalidValue;
     side_blocks = (long)((g.side.count + 1023) / 1024);
   }
+  if ((g.bias || g.relu) && (g.accumulate || g.stats || g.bnb.sums)) return hipErrorInvalidValue;
   if (g.stats) {
     // dense fp32 result only, and no more slabs than the batch-norm workspace holds
     if (g.dtype != DT_F32 || g.accumulate || g.out_stride != 1 || g.out_h != g.p || g.out_w != g.q ||

@@ -151,8 +151,21 @@ int param_io(acc_ctx* c, int layer, float* host, size_t n, bool to_device, bool 
   const acc_layer& l = c->g.layers[layer];
   float* dev = (grads ? c->d_grads : c->d_params) + ps.offset;
   std::vector<float> tmp(n);
+  // An FC layer over a map with h * w > 1 reads it flattened in the device's h, w, c order: its
+  // weight rows are permuted like a filter of that size (the bias behind them stays).
+  int fc_c = 0, fc_h = 1, fc_w = 1;
+  if (l.kind == ACC_FC) {
+    fc_c = l.in0 < 0 ? c->g.in_c : c->g.shape_c[l.in0];
+    fc_h = l.in0 < 0 ? c->g.in_h : c->g.shape_h[l.in0];
+    fc_w = l.in0 < 0 ? c->g.in_w : c->g.shape_w[l.in0];
+  }
+  const bool fc_map = l.kind == ACC_FC && fc_h * fc_w > 1;
   if (to_device) {
     if (l.kind == ACC_CONV) oihw_to_ohwi(host, tmp.data(), l.cout, l.cin, l.r, l.s);
+    else if (fc_map) {
+      oihw_to_ohwi(host, tmp.data(), l.cout, fc_c, fc_h, fc_w);
+      std::memcpy(tmp.data() + (size_t)l.cout * l.cin, host + (size_t)l.cout * l.cin, l.cout * sizeof(float));
+    }
     else std::memcpy(tmp.data(), host, n * sizeof(float));
     HIPCHK(c, hipMemcpyAsync(dev, tmp.data(), n * sizeof(float), hipMemcpyHostToDevice, c->s_c));
     HIPCHK(c, hipStreamSynchronize(c->s_c));
@@ -166,6 +179,10 @@ int param_io(acc_ctx* c, int layer, float* host, size_t n, bool to_device, bool 
     HIPCHK(c, hipMemcpyAsync(tmp.data(), dev, n * sizeof(float), hipMemcpyDeviceToHost, c->s_c));
     HIPCHK(c, hipStreamSynchronize(c->s_c));
     if (l.kind == ACC_CONV) ohwi_to_oihw(tmp.data(), host, l.cout, l.cin, l.r, l.s);
+    else if (fc_map) {
+      ohwi_to_oihw(tmp.data(), host, l.cout, fc_c, fc_h, fc_w);
+      std::memcpy(host + (size_t)l.cout * l.cin, tmp.data() + (size_t)l.cout * l.cin, l.cout * sizeof(float));
+    }
     else std::memcpy(host, tmp.data(), n * sizeof(float));
   }
   return ACC_OK;
@@ -599,6 +616,10 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.p = T(s.y).h; cg.q = T(s.y).w; cg.n_out = l->cout;
       cg.r = l->r; cg.s = l->s; cg.stride = l->stride; cg.pad = l->pad;
       cg.out_h = cg.p; cg.out_w = cg.q; cg.out_stride = 1; cg.accumulate = 0;
+      if (s.bias_layer >= 0) {   // conv + bias (+ ReLU) in one launch
+        cg.bias = c->d_params + g.params[s.bias_layer].offset;
+        cg.relu = s.relu ? 1 : 0;
+      }
       // the batch norm that follows takes its sums from this launch (fp32 storage; with bf16
       // the statistics are those of the rounded values) unless there are more 32-row blocks
       // than its finishing pass adds up
@@ -635,13 +656,17 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       cg.r = 1; cg.s = 1; cg.stride = 1; cg.pad = 0; cg.out_h = 1; cg.out_w = 1; cg.out_stride = 1;
       hipError_t e = igemm(cg, conv_flops);
       if (e != hipSuccess) return e;
-      return bias_add(ptr(s.y), w + (size_t)l->cout * l->cin, k, l->cout, dt, st);
+      return bias_add(ptr(s.y), w + (size_t)l->cout * l->cin, k, l->cout, dt, st, s.relu ? 1 : 0);
     }
     case K_LOSS_F:
       return softmax_ce_forward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.ws), c->d_loss, k, g.classes, dt, st);
     case K_LOSS_B:
       return softmax_ce_backward(ptr(s.x), (const int32_t*)ptr(g.t_labels), ptr(s.dx), k, g.classes, dt, st);
     case K_FC_B: {
+      if (s.relu) {   // FC + ReLU: mask the gradient with [y > 0] first
+        const hipError_t em = relu_mask(ptr(s.dy), ptr(s.y), (size_t)k * l->cout, dt, st);
+        if (em != hipSuccess) return em;
+      }
       WgradGeom wg{};
       wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw; wg.dtype = dt;
       wg.n_img = k; wg.h = 1; wg.wd = 1; wg.cin = l->cin; wg.p = 1; wg.q = 1; wg.cout = l->cout;
@@ -682,6 +707,14 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
     }
     case K_CONV_B: {
       const int h = T(s.x).h, wd = T(s.x).w, ho = T(s.dy).h, wo = T(s.dy).w;
+      if (s.bias_layer >= 0) {
+        // conv + bias (+ ReLU): mask the gradient with [y > 0] in place and sum it per channel
+        // (the bias gradient) before the two GEMMs read it
+        float* db = c->d_grads + g.params[s.bias_layer].offset;
+        const hipError_t eb = relu_bias_backward(ptr(s.dy), s.relu ? ptr(s.y) : nullptr, db, (long)k * ho * wo, l->cout,
+                                                 ptr(s.ws3), dt, st);
+        if (eb != hipSuccess) return eb;
+      }
       WgradGeom wg{};
       wg.x = ptr(s.x); wg.dy = ptr(s.dy); wg.dw = dw; wg.dtype = dt;
       wg.n_img = k; wg.h = h; wg.wd = wd; wg.cin = l->cin; wg.p = ho; wg.q = wo; wg.cout = l->cout;

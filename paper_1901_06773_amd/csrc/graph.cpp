@@ -102,6 +102,11 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
       case ACC_RELU:
         shape_c[i] = c; shape_h[i] = h; shape_w[i] = w;
         break;
+      case ACC_BIAS:
+        if (l.cin != c || (c & 3)) { *err = fmt("layer %d: %s", i, "bias channels must match and be a multiple of 4"); return false; }
+        shape_c[i] = c; shape_h[i] = h; shape_w[i] = w;
+        params[i].count = (size_t)c;
+        break;
       case ACC_ADD: {
         int c1, h1, w1;
         in_shape(l.in1, &c1, &h1, &w1);
@@ -119,7 +124,8 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
         shape_c[i] = c; shape_h[i] = 1; shape_w[i] = 1;
         break;
       case ACC_FC:
-        if (l.cin != c * h * w || h != 1 || w != 1 || l.cout <= 0) { *err = fmt("layer %d: %s", i, "fc input must be a 1x1 map of cin channels"); return false; }
+        // a map with h * w > 1 is flattened (on the device in h, w, c order; weights are permuted on their way in)
+        if (l.cin != c * h * w || l.cout <= 0) { *err = fmt("layer %d: %s", i, "fc input must have cin elements per image"); return false; }
         shape_c[i] = l.cout; shape_h[i] = 1; shape_w[i] = 1;
         params[i].count = (size_t)l.cout * l.cin + l.cout;
         break;
@@ -188,7 +194,22 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
       case ACC_CONV: {
         s.kind = K_CONV_F;
         s.x_is_image = l.in0 < 0;
-        s.y = act_of_layer[i] = new_act(i);
+        int out_layer = i;
+        if (consumers[i].size() == 1 && layers[consumers[i][0]].kind == ACC_BIAS) {
+          // conv -> bias (-> ReLU): one step, the bias and the ReLU sit in the epilogue
+          const int bl = consumers[i][0];
+          s.bias_layer = bl;
+          out_layer = bl;
+          fused[bl] = 1;
+          if (consumers[bl].size() == 1 && layers[consumers[bl][0]].kind == ACC_RELU) {
+            s.relu = true;
+            out_layer = consumers[bl][0];
+            fused[out_layer] = 1;
+          }
+        }
+        s.y = new_act(out_layer);
+        act_of_layer[i] = act_of_layer[out_layer] = s.y;
+        if (s.bias_layer >= 0) act_of_layer[s.bias_layer] = s.y;
         s.flops_per_image = 2.0 * shape_h[i] * shape_w[i] * l.cout * l.cin * l.r * l.s;
         s.bytes_per_image = (double)es * (elems(s.x) + elems(s.y));
         s.bytes_fixed = 4.0 * params[i].count;
@@ -219,7 +240,8 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
       }
       case ACC_RELU:
       case ACC_ADD:
-        *err = fmt("layer %d: %s", i, "only BN->ReLU and BN->add->ReLU patterns are supported");
+      case ACC_BIAS:
+        *err = fmt("layer %d: %s", i, "only BN->ReLU, BN->add->ReLU, conv->bias(->ReLU) and FC->ReLU patterns are supported");
         return false;
       case ACC_MAXPOOL:
         s.kind = K_MAXPOOL_F;
@@ -233,7 +255,16 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
         break;
       case ACC_FC:
         s.kind = K_FC_F;
-        s.y = act_of_layer[i] = new_act(i);
+        {
+          int out_layer = i;
+          if (consumers[i].size() == 1 && layers[consumers[i][0]].kind == ACC_RELU) {
+            s.relu = true;
+            out_layer = consumers[i][0];
+            fused[out_layer] = 1;
+          }
+          s.y = new_act(out_layer);
+          act_of_layer[i] = act_of_layer[out_layer] = s.y;
+        }
         s.flops_per_image = 2.0 * l.cin * l.cout;
         s.bytes_per_image = (double)es * (elems(s.x) + elems(s.y));
         s.bytes_fixed = 4.0 * params[i].count;
@@ -316,6 +347,12 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
         b.reads = {f.x, b.dy};
         if (b.dx_accumulate) b.reads.push_back(b.dx);
         b.writes = {b.dx, b.ws, b.ws2};
+        if (f.relu) {   // the gradient is masked with [y > 0] first (in place)
+          b.relu = true;
+          b.y = f.y;
+          b.reads.push_back(b.y);
+          b.writes.push_back(b.dy);
+        }
         break;
       case K_GAP_F:
         b.kind = K_GAP_B;
@@ -386,6 +423,16 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
         if (need_dx && b.dx_accumulate) b.reads.push_back(b.dx);
         if (need_dx) { b.writes.push_back(b.dx); b.writes.push_back(b.ws); }
         b.writes.push_back(b.ws2);
+        if (f.bias_layer >= 0) {
+          // conv + bias (+ ReLU): the gradient is masked with [y > 0] in place and summed per
+          // channel (the bias gradient) before the two GEMMs
+          b.bias_layer = f.bias_layer;
+          b.relu = f.relu;
+          b.ws3 = new_tensor(T_WORK, 0, 0, 0, 0, relu_bias_workspace_bytes(l.cout), f.layer);
+          if (f.relu) { b.y = f.y; b.reads.push_back(b.y); }
+          b.writes.push_back(b.dy);
+          b.writes.push_back(b.ws3);
+        }
         break;
       }
       default:

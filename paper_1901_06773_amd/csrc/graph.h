@@ -42,6 +42,8 @@ struct Step {
   // tensor ids (-1 = unused)
   int x = -1, y = -1, res = -1, dy = -1, dx = -1, ws = -1, ws2 = -1;
   bool relu = false, dx_accumulate = false, g_inplace = false, x_is_image = false;
+  int bias_layer = -1;   // conv steps: the per-channel bias layer fused into them (with relu: conv + bias + ReLU)
+  int ws3 = -1;          // conv backward with a fused bias: slab sums of the (masked) gradient
   double flops_per_image = 0;   // conv / fc steps
   double bytes_per_image = 0;   // HBM bytes the step touches, per image
   double bytes_fixed = 0;

@@ -64,6 +64,8 @@ struct ConvGeom {
   int out_h, out_w, out_stride;
   int out_y0, out_x0;       // first output pixel
   int accumulate;           // out += result
+  const float* bias;        // optional: + bias[n] (fp32), then
+  int relu;                 // ... max(., 0) if set; both only without accumulate
   // Optional side jobs: extra workgroups appended to the launch add up the parts of a weight
   // gradient, and / or write the flipped, transposed filter that a later data gradient needs
   // (independent data; saves launches of their own).
@@ -154,7 +156,16 @@ hipError_t maxpool_backward(const void* x, const void* dy, void* dx, int n, int 
 hipError_t gap_forward(const void* x, void* y, int n, int hw, int c, int dtype, hipStream_t st);
 hipError_t gap_backward(const void* dy, void* dx, int n, int hw, int c, int accumulate, int dtype,
                         hipStream_t st);
-hipError_t bias_add(void* y, const float* b, long rows, int c, int dtype, hipStream_t st);
+// y[row][ch] += b[ch], then max(., 0) if relu
+hipError_t bias_add(void* y, const float* b, long rows, int c, int dtype, hipStream_t st, int relu = 0);
+// Backward of y = relu(x + b) over rows x c (c % 4 == 0): g = dy * [y > 0] is written over dy (y may
+// be null: no mask, dy untouched) and db[ch] = sum over the rows of g (fixed order).
+// workspace: relu_bias_workspace_bytes(c) bytes.
+size_t relu_bias_workspace_bytes(int c);
+// dy[i] = y[i] > 0 ? dy[i] : 0, in place
+hipError_t relu_mask(void* dy, const void* y, size_t count, int dtype, hipStream_t st);
+hipError_t relu_bias_backward(void* dy, const void* y, float* db, long rows, int c, void* workspace, int dtype,
+                              hipStream_t st);
 hipError_t column_sum(const void* dy, float* db, long rows, int c, int dtype, hipStream_t st);
 // loss_rows: n floats of scratch; loss: one float
 hipError_t softmax_ce_forward(const void* z, const int32_t* labels, float* loss_rows, float* loss,

@@ -191,9 +191,71 @@ __global__ __launch_bounds__(THREADS) void gap_bwd_kernel(const T* __restrict__ 
 
 template <class T>
 __global__ __launch_bounds__(THREADS) void bias_add_kernel(T* y, const float* __restrict__ b, size_t total,
-                                                           int c) {
-  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS)
-    Elem<T>::store(y + i, Elem<T>::load(y + i) + b[i % c]);
+                                                           int c, int relu) {
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    float v = Elem<T>::load(y + i) + b[i % c];
+    if (relu) v = fmaxf(v, 0.f);
+    Elem<T>::store(y + i, v);
+  }
+}
+
+// Backward of y = relu(x + b): a workgroup takes one slab of rows and up to 256 channels (four
+// per thread), writes g = dy * [y > 0] over dy and the per-channel sums of g over its slab to
+// part[slab][c]; rows of a slab are spread over the threads that share a channel group and
+// added in a fixed order.  The second kernel adds the slabs in order.
+constexpr int RB_MAX_SLABS = 512;
+template <class T>
+__global__ __launch_bounds__(THREADS) void relu_bias_bwd_kernel(T* dy, const T* __restrict__ y,
+                                                                double* __restrict__ part, long rows, int c,
+                                                                int tpr, int rpi, long rows_per_slab) {
+  __shared__ double red[THREADS][4];
+  const int tid = threadIdx.x;
+  const int lane_r = tid / tpr, lane_c = tid - lane_r * tpr;
+  const int cg = blockIdx.y * tpr + lane_c;
+  const bool active = lane_r < rpi && cg * 4 < c;
+  const long r_lo = (long)blockIdx.x * rows_per_slab;
+  const long r_hi = r_lo + rows_per_slab < rows ? r_lo + rows_per_slab : rows;
+  double s[4] = {0, 0, 0, 0};
+  if (active)
+    for (long r = r_lo + lane_r; r < r_hi; r += rpi) {
+      const size_t off = (size_t)r * c + (size_t)cg * 4;
+      float gv[4];
+      Elem<T>::load4(dy + off, gv);
+      if (y) {
+        float yv[4];
+        Elem<T>::load4(y + off, yv);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) gv[j] = yv[j] > 0.f ? gv[j] : 0.f;
+        Elem<T>::store4(dy + off, gv);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s[j] += (double)gv[j];
+    }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[tid][j] = s[j];
+  __syncthreads();
+  if (lane_r == 0 && cg * 4 < c) {
+    for (int rr = 1; rr < rpi; ++rr)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s[j] += red[rr * tpr + lane_c][j];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) part[(size_t)blockIdx.x * c + (size_t)cg * 4 + j] = s[j];
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(THREADS) void relu_mask_kernel(T* dy, const T* __restrict__ y, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < count; i += (size_t)gridDim.x * THREADS)
+    if (!(Elem<T>::load(y + i) > 0.f)) Elem<T>::store(dy + i, 0.f);
+}
+
+__global__ __launch_bounds__(THREADS) void slab_sum_kernel(const double* __restrict__ part, float* __restrict__ db,
+                                                           int slabs, int c) {
+  const int ch = blockIdx.x * THREADS + threadIdx.x;
+  if (ch >= c) return;
+  double sum = 0.0;
+  for (int k = 0; k < slabs; ++k) sum += part[(size_t)k * c + ch];
+  db[ch] = (float)sum;
 }
 
 // db[ch] = sum over rows, one thread per channel, rows in order
@@ -384,11 +446,42 @@ hipError_t gap_backward(const void* dy, void* dx, int n, int hw, int c, int accu
   return hipGetLastError();
 }
 
-hipError_t bias_add(void* y, const float* b, long rows, int c, int dtype, hipStream_t st) {
+hipError_t bias_add(void* y, const float* b, long rows, int c, int dtype, hipStream_t st, int relu) {
   if (!y || !b || rows <= 0 || c <= 0) return hipErrorInvalidValue;
   const size_t total = (size_t)rows * c;
   ACC_DISPATCH(dtype, hipLaunchKernelGGL(bias_add_kernel<T>, dim3(grid_for(total)), dim3(THREADS), 0, st, (T*)y, b,
-                                         total, c));
+                                         total, c, relu));
+  return hipGetLastError();
+}
+
+size_t relu_bias_workspace_bytes(int c) { return (size_t)RB_MAX_SLABS * c * sizeof(double); }
+
+hipError_t relu_bias_backward(void* dy, const void* y, float* db, long rows, int c, void* workspace, int dtype,
+                              hipStream_t st) {
+  if (!dy || !db || !workspace || rows <= 0 || c <= 0 || (c & 3)) return hipErrorInvalidValue;
+  // threads along the channels first (four channels each), the rest of the workgroup along rows
+  const int cgroups = c / 4;
+  const int tpr = cgroups < 64 ? cgroups : 64;
+  const int rpi = THREADS / tpr;
+  const int col_slices = (cgroups + tpr - 1) / tpr;
+  // enough slabs to fill the chip, at least 4 trips of the workgroup per slab
+  long slabs = (rows + (long)rpi * 4 - 1) / ((long)rpi * 4);
+  const long cap = RB_MAX_SLABS / col_slices > 0 ? RB_MAX_SLABS / col_slices : 1;
+  if (slabs > cap) slabs = cap;
+  if (slabs < 1) slabs = 1;
+  const long rows_per_slab = (rows + slabs - 1) / slabs;
+  slabs = (rows + rows_per_slab - 1) / rows_per_slab;
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(relu_bias_bwd_kernel<T>, dim3((unsigned)slabs, col_slices), dim3(THREADS), 0, st,
+                                         (T*)dy, (const T*)y, (double*)workspace, rows, c, tpr, rpi, rows_per_slab));
+  hipLaunchKernelGGL(slab_sum_kernel, dim3((c + THREADS - 1) / THREADS), dim3(THREADS), 0, st, (const double*)workspace,
+                     db, (int)slabs, c);
+  return hipGetLastError();
+}
+
+hipError_t relu_mask(void* dy, const void* y, size_t count, int dtype, hipStream_t st) {
+  if (!dy || !y || count == 0) return hipErrorInvalidValue;
+  ACC_DISPATCH(dtype, hipLaunchKernelGGL(relu_mask_kernel<T>, dim3(grid_for(count)), dim3(THREADS), 0, st, (T*)dy,
+                                         (const T*)y, count));
   return hipGetLastError();
 }
 

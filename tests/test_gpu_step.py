@@ -52,6 +52,8 @@ NETS = {
     # strided 3x3 convolutions with a data gradient: basic blocks (18/34-layer style) and v1.5 strides
     "mini_resnet_basic": (lambda: S.resnet((2, 1, 1), in_hw=48, classes=10, width=32, block="basic"), 3),
     "mini_resnet_v15": (lambda: S.resnet((1, 2), in_hw=32, classes=10, width=8, variant="v1.5"), 3),
+    # VGG style: conv + bias + ReLU, 2x2 max-pools, FC + ReLU over the flattened map (no batch norm)
+    "mini_vgg": (lambda: S.vgg(cfg=((32, 32), (64, 64), (64,)), in_c=3, in_hw=32, classes=10, fc=96), 4),
 }
 
 
@@ -171,7 +173,9 @@ def test_swapping_everything_is_bit_exact(name):
     stat = s0["static_bytes"]             # weights, gradients, statistics, kernel scratch: always resident
     tight = tight_pool(probe, k, s0)
     probe.close()
-    if name != "config1_unit":          # (the single block is too small for the margin to matter)
+    # (where one layer's working set is most of what the whole network keeps, as in the single
+    # block and the small VGG, the two peaks lie too close for the comparison to say anything)
+    if s0["noswap_peak_bytes"] - stat > 1.25 * (s0["layer_peak_bytes"] - stat):
         assert tight < s0["noswap_peak_bytes"]
     out = run_gpu(net, params, k, b.PLAN_NAIVE_ALL, tight, steps=2)
     assert out["summary"]["n_swapped"] == out["summary"]["n_maps"] > 0

@@ -157,6 +157,26 @@ def test_flops_match_the_published_multiply_adds(name, gmacs):
     assert bwd == pytest.approx(2 * fwd - stem, rel=1e-12)
 
 
+def test_vgg16_flops_and_maps():
+    """VGG-16 (conv + bias + ReLU fused into one step each, FC over the flattened 7x7x512 map):
+    forward multiply-adds within 2 % of the published 15.3 G (convolutions 15.35 G and the three
+    FC layers 0.12 G), backward twice that minus the first layer's data gradient; the maps kept
+    for backward are the image, the 13 ReLU outputs, the 5 pooled maps, the 2 hidden FC outputs
+    and the logits."""
+    b = B()
+    ctx = ctx_of(S.vgg16())
+    k = 64                      # (every map a whole number of 256-byte units)
+    s = ctx.plan_swaps(k, 1 << 40, b.PLAN_NONE)
+    fwd = sum(ctx.step_info(j)["flops"] for j in range(ctx.step_count()) if ctx.step_info(j)["backward"] == 0) / k
+    assert fwd / 2 / 1e9 == pytest.approx(PUB["vgg16_gmacs"], rel=0.02)
+    bwd = sum(ctx.step_info(j)["flops"] for j in range(ctx.step_count()) if ctx.step_info(j)["backward"] == 1) / k
+    assert bwd == pytest.approx(2 * fwd - 2 * 224 * 224 * 64 * 3 * 9, rel=1e-12)
+    assert s["n_maps"] == 1 + 13 + 5 + 2 + 1
+    per_image = 4 * (3 * 224 * 224 + 2 * 64 * 224 ** 2 + 2 * 128 * 112 ** 2 + 3 * 256 * 56 ** 2 + 3 * 512 * 28 ** 2 +
+                     3 * 512 * 14 ** 2 + 64 * 112 ** 2 + 128 * 56 ** 2 + 256 * 28 ** 2 + 512 * 14 ** 2 + 512 * 7 ** 2 + 2 * 4096 + 1000)
+    assert s["bytes_maps"] == k * per_image
+
+
 def test_sizes_and_flops_are_linear_in_the_minibatch():
     """Eq. 1 and static information 2: feature-map bytes and FLOPs scale with k exactly."""
     b = B()
