@@ -51,9 +51,14 @@ enum { ACC_PLAN_NONE = 0, ACC_PLAN_NAIVE_ALL = 1, ACC_PLAN_DYNAMIC = 2 };
 enum { ACC_LOC_HOST = 0, ACC_LOC_DEVICE = 1 };
 
 /* One layer, in execution order.  in0/in1: index of the producing layer, -1 = the
- * network input.  conv: cin,cout,r,s,stride,pad (no bias).  bn: cin channels,
- * parameters [gamma|beta], eps 1e-5, minibatch statistics.  maxpool: r,s,stride,pad.
- * fc: cin,cout, parameters [W cout x cin | b cout].  softmax_ce: in0 = logits. */
+ * network input.  conv: cin,cout,r,s,stride,pad (no bias).  bias: cin channels, one
+ * parameter each, added per channel.  bn: cin channels, parameters [gamma|beta], eps 1e-5,
+ * minibatch statistics.  maxpool: r,s,stride,pad.  fc: cin,cout, parameters
+ * [W cout x cin | b cout]; cin = all elements of the input map of one image (a map larger
+ * than 1x1 is flattened in c, h, w order, as OIHW filters are).  softmax_ce: in0 = logits.
+ * Element-wise layers are executed fused into the step of their producer, so they must
+ * appear in one of these patterns (acc_create returns ACC_EINVAL otherwise):
+ * bn -> relu, bn -> add -> relu, conv -> bias [-> relu], fc -> relu. */
 typedef struct {
   int32_t kind, in0, in1, cin, cout, r, s, stride, pad;
 } acc_layer;
