@@ -856,6 +856,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   }
   uint64_t bytes_out = 0, bytes_in = 0;
   c->bn_ready_slabs.assign(ns, 0);
+  std::fill(c->wgrad_in_flight.begin(), c->wgrad_in_flight.end(), 0);   // (a failed step may have left some set)
   c->pending_reduce = ReduceJob{nullptr, nullptr, 0, 0};
   c->kprobes_used = 0;
   if (c->kernel_profiling) {
