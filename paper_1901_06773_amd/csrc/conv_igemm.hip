@@ -104,7 +104,7 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
 enum { L_GENERIC = 0, L_DIRECT = 2 };
 constexpr int LDD = CHUNK_BYTES / 4;          // LDS row pitch of L_DIRECT in words
 
-template <int LOADER, class T>
+template <int LOADER, class T, bool ACT>
 __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
                                                      int main_grid) {
   constexpr bool DIRECT = LOADER == L_DIRECT;
@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   // epilogue: accumulator register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32 of its 32x32 block
   const int n = n0 + wn0 + (lane & 31);
-  if (g.stats) {
+  if (!ACT && g.stats) {
     // sums of the column and of its squares over the wave's 32 rows (rows beyond M are exact
     // zeros: their operand rows were zero), for the batch norm that follows: its slab
     // tile_m * 2 + (0 or 1).  Fixed order: the lane's 16 values, then the partner lane.
@@ -438,7 +438,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       g.stats[((size_t)g.stats_stride + slab) * g.n_out + n] = (double)sq;
     }
   }
-  if (g.bnb.sums) {
+  if (!ACT && g.bnb.sums) {
     // Data gradient whose result is the gradient of a batch norm's ReLU output: mask it with
     // [y > 0] and leave the sums of g and g * xhat over the wave's 32 rows for that batch
     // norm's backward pass (dense output: element (m, n) of x and y sits at m * n_out + n).
@@ -471,15 +471,21 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     }
   }
   if (n >= g.n_out) return;
-  const float bias_n = g.bias ? g.bias[n] : 0.f;
+  // ACT: the instantiation whose epilogue adds a bias and applies a ReLU (it never accumulates)
+  float bias_n = 0.f;
+  if constexpr (ACT) bias_n = g.bias ? g.bias[n] : 0.f;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int m = m0 + wm0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
     if (m >= M) continue;
     T* o = static_cast<T*>(g.out) + out_row_offset(g, m) + n;
-    float val = acc[v] + bias_n;
-    if (g.relu) val = fmaxf(val, 0.f);
-    if (g.accumulate) val += Elem<T>::load(o);
+    float val = acc[v];
+    if constexpr (ACT) {
+      val += bias_n;
+      if (g.relu) val = fmaxf(val, 0.f);
+    } else {
+      if (g.accumulate) val += Elem<T>::load(o);
+    }
     Elem<T>::store(o, val);
   }
 }
@@ -513,8 +519,11 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   }
   if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
   if (probe->before) (void)hipEventRecord(probe->before, st);
-  hipLaunchKernelGGL((igemm_kernel<LOADER, T>), dim3((unsigned)(main_grid + side_blocks)), dim3(256), 0, st, g, M, K, tn,
-                     (int)tiles, main_grid);
+  const dim3 grid((unsigned)(main_grid + side_blocks));
+  if (g.bias || g.relu)
+    hipLaunchKernelGGL((igemm_kernel<LOADER, T, true>), grid, dim3(256), 0, st, g, M, K, tn, (int)tiles, main_grid);
+  else
+    hipLaunchKernelGGL((igemm_kernel<LOADER, T, false>), grid, dim3(256), 0, st, g, M, K, tn, (int)tiles, main_grid);
   if (probe->after) (void)hipEventRecord(probe->after, st);
   return hipGetLastError();
 }
