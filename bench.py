@@ -48,7 +48,7 @@ def parse():
 # HBM bytes per launch of the dominant kernel (igemm_kernel<direct>), from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs of this script, scaled by what the same counters read for sgd_kernel
 # (profiles/resnet152_k41_hbm_traffic_pmc.txt).  Known for the profiled workload only.
-MEASURED_TRAFFIC_BYTES = {("resnet152", 41, 8.0): 71.3e6}
+MEASURED_TRAFFIC_BYTES = {("resnet152", 41, 8.0): 71.2e6}
 
 
 def log(*a):

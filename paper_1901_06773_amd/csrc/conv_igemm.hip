@@ -102,17 +102,26 @@ __device__ __forceinline__ size_t out_row_offset(const ConvGeom& g, int m) {
 // stages: the loads of chunk kc+1 are issued right after the barrier that opens chunk kc
 // and have its whole MFMA work to land.
 enum { L_GENERIC = 0, L_DIRECT = 2 };
-constexpr int LDD = CHUNK_BYTES / 4;          // LDS row pitch of L_DIRECT in words
+// Chunk of L_DIRECT in bytes of a GEMM row (128 or 256; the loader and the fragment reads are
+// written for both).  256-byte chunks in fp32 (one barrier per 32 MFMAs of a wave, 64 KB of
+// LDS per workgroup) measured 127 against 121 TFLOP/s in a bare copy of the loop at two
+// workgroups per CU, but lost in the kernel itself: no third workgroup fits beside two, so a
+// tile's prologue and epilogue overlap nothing (256->256 3x3 at 4 tiles per CU 106 against
+// 115 TFLOP/s, ResNet-152 step 1039 against 1165 images/s), and the weight-gradient kernel
+// finds no LDS beside it.
+__host__ __device__ constexpr int direct_chunk_bytes(int) { return 128; }
 
 template <int LOADER, class T, bool ACT>
 __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
                                                      int main_grid) {
   constexpr bool DIRECT = LOADER == L_DIRECT;
   constexpr int ES = sizeof(T);
-  constexpr int BK = CHUNK_BYTES / ES;       // elements of K per chunk
+  constexpr int DCHUNK = direct_chunk_bytes(ES);
+  constexpr int BK = (DIRECT ? DCHUNK : CHUNK_BYTES) / ES;       // elements of K per chunk
+  constexpr int LDD = DCHUNK / 4;            // LDS row pitch of L_DIRECT in words
   constexpr int PITCH = DIRECT ? LDD : LD;
-  __shared__ __attribute__((aligned(128))) float As[2 * BM * PITCH];
-  __shared__ __attribute__((aligned(128))) float Bs[2 * BN * PITCH];
+  __shared__ __attribute__((aligned(1024))) float As[2 * BM * PITCH];
+  __shared__ __attribute__((aligned(1024))) float Bs[2 * BN * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
     const ReduceJob& j = g.side;
@@ -286,15 +295,17 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
 
   if constexpr (DIRECT) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    constexpr int AI = BM / 32, BI = BN / 32;
-    const int lrow = tid >> 3;                          // row of the lane's LDS slot within a 32-row half
-    const int lcol = (tid & 7) ^ (lrow & 7);            // 16-byte column that belongs into that slot
+    constexpr int CPR = DCHUNK / 16;                    // 16-byte columns per row: 8 or 16
+    constexpr int RPI = 4096 / DCHUNK;                  // rows one load instruction of the 4 waves fills: 32 or 16
+    constexpr int AI = BM / RPI, BI = BN / RPI;
+    const int lrow = tid / CPR;                         // row of the lane's LDS slot within the first RPI rows
+    const int lcol = (tid & (CPR - 1)) ^ (lrow & (CPR - 1));   // 16-byte column that belongs into that slot
     const int margin = g.pad * g.wd + g.pad + g.pad_dx; // pixels; the descriptor starts that far before the tensor
     constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;           // beyond any descriptor range: reads as zero
     uint32_t a_voff[AI], a_mask[AI], b_voff[BI];
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
-      const RowPos rp = decode_row(g, m0 + lrow + 32 * i, M);
+      const RowPos rp = decode_row(g, m0 + lrow + RPI * i, M);
       a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * ES) + lcol * 16;
       uint32_t mask = 0;
       for (int kr = 0; kr < g.r; ++kr)
@@ -306,7 +317,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
-      const int n = n0 + lrow + 32 * i;
+      const int n = n0 + lrow + RPI * i;
       b_voff[i] = (uint32_t)(n < g.n_out ? n : 0) * (uint32_t)(K * ES) + lcol * 16;   // beyond n_out: filter 0, never stored
     }
     const size_t margin_bytes = (size_t)margin * g.c * ES;
@@ -322,16 +333,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     auto issue = [&](int kc, int buf) {
       const int tap = kr * g.s + kt;
       const int soff_a = ((kr * g.wd + kt) * g.c + c0) * ES;
-      const int soff_b = kc * CHUNK_BYTES;
+      const int soff_b = kc * DCHUNK;
 #pragma unroll
       for (int i = 0; i < AI; ++i) {
         const uint32_t voff = ((a_mask[i] >> tap) & 1u) ? a_voff[i] : OUTSIDE;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)(size_t)(lds_a + buf * (BM * CHUNK_BYTES) + i * (32 * CHUNK_BYTES)),
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr)(size_t)(lds_a + buf * (BM * DCHUNK) + i * 4096),
                                                  16, voff, soff_a, 0, 0);
       }
 #pragma unroll
       for (int i = 0; i < BI; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(size_t)(lds_b + buf * (BN * CHUNK_BYTES) + i * (32 * CHUNK_BYTES)),
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(size_t)(lds_b + buf * (BN * DCHUNK) + i * 4096),
                                                  16, b_voff[i], soff_b, 0, 0);
       c0 += BK;
       if (c0 == g.c) {
@@ -339,40 +350,53 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
         if (++kt == g.s) { kt = 0; ++kr; }
       }
     };
-    // fragment of a row: 16-byte column c16 sits in slot c16 ^ (row & 7)
+    // fragment of a row: 16-byte column c16 sits in slot c16 ^ (row % CPR)
     const int ra_ = wm0 + (lane & 31), rb_ = wn0 + (lane & 31);
     auto compute_direct = [&](int buf) {
       const float* as = As + buf * (BM * LDD) + ra_ * LDD;
       const float* bs = Bs + buf * (BN * LDD) + rb_ * LDD;
+      // all eight fragment reads of the chunk first, so that the matrix cores never wait for LDS
+      constexpr int NG = CPR / 2;              // groups of two 16-byte columns (lanes 0-31 / 32-63)
+      float4 af[NG], bf[NG];
 #pragma unroll
-      for (int g8 = 0; g8 < 4; ++g8) {
+      for (int g8 = 0; g8 < NG; ++g8) {
         const int c16 = g8 * 2 + (lane >> 5);
-        const float4 af = *reinterpret_cast<const float4*>(as + ((c16 ^ (ra_ & 7)) << 2));
-        const float4 bf = *reinterpret_cast<const float4*>(bs + ((c16 ^ (rb_ & 7)) << 2));
+        af[g8] = *reinterpret_cast<const float4*>(as + ((c16 ^ (ra_ & (CPR - 1))) << 2));
+        bf[g8] = *reinterpret_cast<const float4*>(bs + ((c16 ^ (rb_ & (CPR - 1))) << 2));
+      }
+      __builtin_amdgcn_sched_barrier(0);      // keeps the scheduler from sinking the reads between the MFMAs again
+#pragma unroll
+      for (int g8 = 0; g8 < NG; ++g8) {
         if constexpr (ES == 4) {
-          acc = mfma32x32x2(af.x, bf.x, acc);
-          acc = mfma32x32x2(af.y, bf.y, acc);
-          acc = mfma32x32x2(af.z, bf.z, acc);
-          acc = mfma32x32x2(af.w, bf.w, acc);
+          acc = mfma32x32x2(af[g8].x, bf[g8].x, acc);
+          acc = mfma32x32x2(af[g8].y, bf[g8].y, acc);
+          acc = mfma32x32x2(af[g8].z, bf[g8].z, acc);
+          acc = mfma32x32x2(af[g8].w, bf[g8].w, acc);
         } else {
-          acc = mfma32x32x16bf(af, bf, acc);
+          acc = mfma32x32x16bf(af[g8], bf[g8], acc);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);      // ... and from moving the next chunk's wait and barrier up among them
     };
     // The barrier that opens chunk kc says two things: every wave's part of chunk kc has
     // landed in LDS (each wave waits for its own loads first), and every wave is done with
     // chunk kc-1, whose stage the loads of chunk kc+1 may now overwrite.
     issue(0, 0);
-    for (int kc = 0; kc < n_chunks; kc += 2) {
+    int kc = 0;
+    for (; kc + 2 <= n_chunks; kc += 2) {     // whole pairs of chunks: stage 0, then stage 1
       __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads are in LDS
       __syncthreads();
-      if (kc + 1 < n_chunks) issue(kc + 1, 1);
+      issue(kc + 1, 1);
       compute_direct(0);
-      if (kc + 1 >= n_chunks) break;
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
       if (kc + 2 < n_chunks) issue(kc + 2, 0);
       compute_direct(1);
+    }
+    if (kc < n_chunks) {                      // an odd number of chunks: the last one sits in stage 0
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      compute_direct(0);
     }
 #endif
   } else {
@@ -559,7 +583,7 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   // tensors.  The choice depends on the shape and the alignment only, never on the swap plan
   // (pool offsets are multiples of 256).
   const long margin_px = (long)g.pad * g.wd + g.pad + g.pad_dx;
-  const bool direct = (g.c % (CHUNK_BYTES / es) == 0) && g.r * g.s <= 32 &&
+  const bool direct = (g.c % (direct_chunk_bytes((int)es) / es) == 0) && g.r * g.s <= 32 &&
                       (margin_px + (long)g.n_img * g.h * g.wd) * g.c * es <= 0xFFFFFF00L &&
                       (long)g.n_out * K * es <= 0xFFFFFF00L &&
                       (reinterpret_cast<uintptr_t>(g.in) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.w) & 15) == 0;
