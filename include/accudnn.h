@@ -282,7 +282,9 @@ int acc_get_step_times_ms(acc_ctx* ctx, double* ms, int n);
  * dw (O-H-W-I), gamma, beta, mean, istd, dgamma, dbeta are always fp32.  Arithmetic is fp32
  * (bf16 products accumulate in fp32).  stream is a hipStream_t.  workspace may be NULL when
  * workspace_bytes is 0; query the need with acc_op_conv_workspace().  accumulate != 0 adds
- * into dx instead of overwriting. */
+ * into dx instead of overwriting.  Every pointer must be 16-byte aligned (the kernels move
+ * 16 bytes at a time); a misaligned one is ACC_EINVAL, like any other bad argument, and
+ * nothing is launched. */
 size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, int r, int s, int stride,
                              int pad);
 int acc_op_conv_fwd(const void* x, const void* w, void* y, int n, int h, int wd, int cin,

@@ -16,7 +16,10 @@
 // Tile shape (measured on MI355X over the ResNet shapes at minibatch 32..256): 64x64
 // beats 128x64 and 128x128 everywhere (70.7 / 86 / 98 TFLOP/s against 56 / 76 / 88 and
 // 40 / 61 / 82): with M a multiple of 49 the larger tiles quantise badly over 256 CUs,
-// and four resident workgroups per CU hide the one barrier per chunk.
+// and four resident workgroups per CU hide the one barrier per chunk.  A 64x128 variant of the
+// direct loader (each wave two 32x32 blocks on shared input fragments, 48 KB of LDS, three
+// workgroups per CU) for the 1x1 expansions lost as well: igemm 92.8 against 98.7 TFLOP/s over
+// a ResNet-152 step at minibatch 41 when used from three tiles per CU on, 97.5 from six on.
 #include "kernels.h"
 #include "dtype.h"
 

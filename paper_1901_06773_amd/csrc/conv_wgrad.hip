@@ -542,13 +542,8 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   const int tiles = c.tiles_co * c.tiles_j;
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
   // direct loader: fp32 storage, both operands inside 32-bit buffer ranges (the last bytes stay
-  // free for the offset that stands for "outside").  ACC_WGRAD_LOADER=fast in the environment
-  // keeps the register-staged loader (for comparisons).
-  static const bool allow_direct = [] {
-    const char* e = getenv("ACC_WGRAD_LOADER");
-    return !(e && e[0] == 'f');
-  }();
-  const bool direct = fast && allow_direct && g.dtype == DT_F32 && Mrows * g.cout * es <= 0xFFFFFF00L &&
+  // free for the offset that stands for "outside") and 16-byte aligned
+  const bool direct = fast && g.dtype == DT_F32 && Mrows * g.cout * es <= 0xFFFFFF00L &&
                       (long)g.n_img * g.h * g.wd * g.cin * es <= 0xFFFFFF00L &&
                       (reinterpret_cast<uintptr_t>(g.x) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.dy) & 15) == 0;
 #define ACC_WGRAD_LAUNCH(F, T)                                                                             \

@@ -261,7 +261,7 @@ extern "C" int acc_create(const acc_layer* layers, int n_layers, int in_c, int i
     }
     if (e != hipSuccess) {
       g_create_error = std::string("device setup: ") + hipGetErrorString(e);
-      delete c;
+      acc_destroy(c);   // also releases the events and the pinned scalar made so far
       return ACC_EHIP;
     }
   }

@@ -2,6 +2,9 @@
 // launchers, for per-layer parity tests and roofline measurements.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
+#include <initializer_list>
+
 #include "../../include/accudnn.h"
 #include "kernels.h"
 #include "dtype.h"
@@ -16,6 +19,11 @@ inline bool conv_ok(int n, int h, int w, int cin, int cout, int r, int s, int st
          h + 2 * pad >= r && w + 2 * pad >= s;
 }
 inline bool dtype_ok(int dt) { return dt == ACC_F32 || dt == ACC_BF16; }
+// the kernels move 16 bytes at a time: null is let through here (checked where it matters)
+inline bool al16(std::initializer_list<const void*> ps) {
+  for (const void* p : ps) if (reinterpret_cast<uintptr_t>(p) & 15) return false;
+  return true;
+}
 inline int status(hipError_t e) { return e == hipSuccess ? ACC_OK : (e == hipErrorInvalidValue ? ACC_EINVAL : ACC_EHIP); }
 }  // namespace
 
@@ -30,6 +38,7 @@ extern "C" size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, 
 extern "C" int acc_op_conv_fwd(const void* x, const void* w, void* y, int n, int h, int wd, int cin, int cout,
                                int r, int s, int stride, int pad, int dtype, void* stream) {
   if (!x || !w || !y || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+  if (!al16({x, w, y})) return ACC_EINVAL;
   ConvGeom g{};
   g.in = x; g.w = w; g.out = y; g.dtype = dtype;
   g.n_img = n; g.h = h; g.wd = wd; g.c = cin;
@@ -43,6 +52,7 @@ extern "C" int acc_op_conv_dgrad(const void* dy, const void* w, void* dx, int n,
                                  int r, int s, int stride, int pad, int accumulate, void* workspace,
                                  size_t workspace_bytes, int dtype, void* stream) {
   if (!dy || !w || !dx || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+  if (!al16({dy, w, dx, workspace})) return ACC_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
   hipError_t e;
@@ -99,6 +109,7 @@ extern "C" int acc_op_conv_wgrad(const void* x, const void* dy, float* dw, int n
                                  int r, int s, int stride, int pad, void* workspace, size_t workspace_bytes,
                                  int dtype, void* stream) {
   if (!x || !dy || !dw || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
+  if (!al16({x, dy, dw, workspace})) return ACC_EINVAL;
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
   const size_t need = wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s);
   if (need && (!workspace || workspace_bytes < need)) return ACC_EINVAL;
@@ -114,7 +125,7 @@ extern "C" size_t acc_op_bn_workspace(int c) { return c > 0 ? al256(bn_workspace
 extern "C" int acc_op_bn_fwd(const void* x, const float* gamma, const float* beta, const void* res, void* y,
                              float* mean, float* istd, int rows, int c, int relu, float eps, void* workspace,
                              int dtype, void* stream) {
-  if (!dtype_ok(dtype)) return ACC_EINVAL;
+  if (!dtype_ok(dtype) || !al16({x, gamma, beta, res, y, mean, istd, workspace})) return ACC_EINVAL;
   return status(bn_forward(x, gamma, beta, res, y, mean, istd, rows, c, relu, eps, workspace, dtype,
                            (hipStream_t)stream));
 }
@@ -122,7 +133,7 @@ extern "C" int acc_op_bn_fwd(const void* x, const float* gamma, const float* bet
 extern "C" int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const float* gamma, const float* mean,
                              const float* istd, void* dx, float* dgamma, float* dbeta, void* g_out, int rows, int c,
                              void* workspace, int dtype, void* stream) {
-  if (!dtype_ok(dtype)) return ACC_EINVAL;
+  if (!dtype_ok(dtype) || !al16({x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, workspace})) return ACC_EINVAL;
   return status(bn_backward(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, rows, c, workspace, dtype,
                             (hipStream_t)stream));
 }

@@ -67,6 +67,8 @@ CONV_CASES = [  # n, h, w, cin, cout, r, stride, pad
     (2, 12, 10, 20, 24, 3, 1, 1),      # channels not a multiple of 32, non-square image
     (1, 7, 7, 96, 40, 3, 1, 1),        # single image, ragged everything
     (2, 23, 23, 8, 16, 7, 2, 3),       # stem-like filter
+    (8, 57, 55, 64, 256, 1, 1, 0),     # 1x1 expansion: 392 row tiles (ragged M) x 4, two chunks each
+    (8, 57, 55, 256, 64, 1, 1, 0),     # 1x1 reduction: eight chunks; its data gradient is the expansion
 ]
 
 
@@ -211,6 +213,15 @@ def test_bad_arguments_are_rejected():
     ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
     with pytest.raises(b.AccError):
         b.op_conv_dgrad(y, w, torch.zeros(1, 14, 14, 8, device="cuda"), 4, 2, ws)  # 3x3 stride 4 pad 2: not supported
+    # a view that starts one element into its buffer: contiguous, but not 16-byte aligned
+    buf = torch.zeros(x.numel() + 4, device="cuda")
+    x_off = buf[1:1 + x.numel()].view(x.shape)
+    assert x_off.data_ptr() % 16 == 4 and x_off.is_contiguous()
+    with pytest.raises(b.AccError):
+        b.op_conv_fwd(x_off, w, y, 1, 1)
+    dw = torch.zeros_like(w)
+    with pytest.raises(b.AccError):
+        b.op_conv_wgrad(x_off, y, dw, 1, 1, ws)
 
 
 # ------------------------------------------------------------------ full-size layers, sampled

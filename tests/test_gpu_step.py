@@ -44,11 +44,29 @@ def wide_chain():
     return net
 
 
+def tall_chain():
+    """1x1 convolutions over 8 x 56 x 56 positions (25088 GEMM rows, 392 row tiles) with up to 256
+    channels: many output tiles per CU and few K chunks per tile, forward (64 -> 256, with the
+    batch-norm sums in its epilogue) and as a data gradient (of 256 -> 64, with the mask and
+    the backward sums): the shape of the 1x1 expansions of the large networks."""
+    net = S.NetSpec("tall_chain", 64, 56, 56, 10)
+    x = -1
+    for cin, cout in ((64, 256), (256, 64), (64, 128)):
+        x = net.add(S.Layer(S.CONV, in0=x, cin=cin, cout=cout, r=1, s=1, stride=1, pad=0))
+        x = net.add(S.Layer(S.BN, in0=x, cin=cout, cout=cout))
+        x = net.add(S.Layer(S.RELU, in0=x, cin=cout, cout=cout))
+    g = net.add(S.Layer(S.GAP, in0=x, cin=128, cout=128))
+    f = net.add(S.Layer(S.FC, in0=g, cin=128, cout=10))
+    net.add(S.Layer(S.SOFTMAX_CE, in0=f, cin=10, cout=1))
+    return net
+
+
 NETS = {
     "config1_unit": (lambda: S.bottleneck_unit(), 2),                       # BASELINE configs[0]
     "mini_resnet_w8": (lambda: S.resnet((1, 2), in_hw=32, classes=10, width=8), 3),
     "mini_resnet_w32": (lambda: S.resnet((1, 1, 2, 1), in_hw=64, classes=100, width=32), 5),
     "wide_chain": (wide_chain, 6),
+    "tall_chain": (tall_chain, 8),
     # strided 3x3 convolutions with a data gradient: basic blocks (18/34-layer style) and v1.5 strides
     "mini_resnet_basic": (lambda: S.resnet((2, 1, 1), in_hw=48, classes=10, width=32, block="basic"), 3),
     "mini_resnet_v15": (lambda: S.resnet((1, 2), in_hw=32, classes=10, width=8, variant="v1.5"), 3),
@@ -74,7 +92,7 @@ def tight_pool(probe, k, s0):
     raise AssertionError("no layout within 25 % of the layer-wise peak")
 
 
-def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=64 * MiB, lr=0.1, explicit=None, dtype=0,
+def run_gpu(net, params, k, mode, budget, steps=1, pool=None, host=256 * MiB, lr=0.1, explicit=None, dtype=0,
             wgrad_stream=True, overlap=True):
     b = B()
     ctx = b.Context(net.as_array(), (net.in_c, net.in_h, net.in_w), pool_bytes=pool or budget, host_bytes=host,
