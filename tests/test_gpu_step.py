@@ -127,6 +127,25 @@ def test_step_matches_oracle(name):
             close(a, r, f"{name} updated weights of layer {i}")
 
 
+@pytest.mark.parametrize("name", ["config1_unit", "mini_resnet_w8", "mini_vgg"])
+def test_minibatch_of_one(name):
+    """The degenerate minibatch: batch-norm statistics over H x W alone, one-row GEMMs in the head,
+    a single image's worth of tiles everywhere."""
+    make, _ = NETS[name]
+    net = make()
+    params = S.init_params(net)
+    img, lab = S.make_batch(net, 1, 0)
+    o_loss, o_w, o_g = O.train_step(net.as_array(), (net.in_c, net.in_h, net.in_w), params, img, lab, 0.1)
+    g = run_gpu(net, params, 1, B().PLAN_NONE, 512 * MiB)
+    close(g["losses"][0], o_loss, f"{name} loss")
+    for i, (a, r) in enumerate(zip(g["grads"], o_g)):
+        if r.size:
+            close(a, r, f"{name} grad of layer {i} ({S.KIND_NAMES[net.layers[i].kind]})")
+    for i, (a, r) in enumerate(zip(g["weights"], o_w)):
+        if r.size:
+            close(a, r, f"{name} updated weights of layer {i}")
+
+
 def test_resnet152_at_full_input_size_is_as_close_to_the_exact_step_as_fp32_allows():
     """The benchmark's network at 224x224 and a minibatch the oracle finishes in seconds.
     152 layers at random initialisation amplify rounding: the oracle run with fp32 storage
