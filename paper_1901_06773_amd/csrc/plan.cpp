@@ -550,8 +550,27 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
     *p = std::move(*bestp);
     return true;
   };
+  // Last pass over the chosen swap set: eager prefetch that keeps less than the whole working
+  // set free.  The working-set peak lies at the large early layers, which backward reaches
+  // last, so at the start of backward less room is enough and the link need not wait for it;
+  // a layout in which some step then finds no room is dropped (build_plan fails), the others
+  // are simulated and the fastest is kept.
+  auto refine_layout = [&](const std::vector<uint8_t>& sw, Plan* best) {
+    if (headroom == 0 || best->n_swapped == 0) return;
+    for (double f : {0.75, 0.5, 0.25, 0.125}) {
+      PlanOptions eager = opt;
+      eager.clock = &cm;
+      eager.eager_headroom = std::max<size_t>(256, (size_t)(headroom * f));
+      Plan p;
+      std::string w;
+      if (!build_plan(g, k, budget, sw, eager, &p, &w)) continue;
+      simulate(g, cm, &p);
+      if (p.t_iter < best->t_iter * (1.0 - 1e-6)) *best = std::move(p);
+    }
+  };
   if (mode == ACC_PLAN_NAIVE_ALL) {
     if (!build_sim(all, out, why)) return ACC_EUNTRAINABLE;
+    refine_layout(all, out);
     out->mode = mode;
     return ACC_OK;
   }
@@ -617,6 +636,7 @@ int make_plan(const Graph& g, const CostModel& cm, int k, size_t budget, int mod
     }
     if (!changed) break;
   }
+  refine_layout(cur, &best);
   *out = std::move(best);
   out->mode = mode;
   *why = "";
