@@ -306,8 +306,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     const int margin = g.pad * g.wd + g.pad + g.pad_dx; // pixels; the descriptor starts that far before the tensor
     constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;           // beyond any descriptor range: reads as zero
     uint32_t a_voff[AI], a_mask[AI], b_voff[BI];
+    // 1x1, stride 1, no padding (two launches in three): GEMM row m is pixel m, nothing to decode
+    const bool plain = g.r == 1 && g.s == 1 && g.stride == 1 && g.pad == 0 && g.pad_dx == 0 && g.p == g.h && g.q == g.wd;
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
+      if (plain) {
+        const int m = m0 + lrow + RPI * i;
+        a_voff[i] = (uint32_t)(m < M ? m : 0) * (uint32_t)(g.c * ES) + lcol * 16;
+        a_mask[i] = m < M ? 1u : 0u;
+        continue;
+      }
       const RowPos rp = decode_row(g, m0 + lrow + RPI * i, M);
       a_voff[i] = (uint32_t)(rp.pix + rp.iy0 * g.wd + rp.ix0 + margin) * (uint32_t)(g.c * ES) + lcol * 16;
       uint32_t mask = 0;
@@ -473,15 +481,20 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     // the weight-gradient stream beside: 1141 against 1164 images/s.)
     const bool col = n < g.n_out;
     const float mu = col ? g.bnb.mean[n] : 0.f, is = col ? g.bnb.istd[n] : 0.f;
-    const T* bx = static_cast<const T*>(g.bnb.x);
-    const T* by = static_cast<const T*>(g.bnb.y);
+    // the lane's first row; its other rows lie dr = 8*(v/4) + v%4 rows further on, a distance
+    // that is the same for every lane (one scalar product per v, no per-lane 64-bit multiply)
+    const int mb = m0 + wm0 + 4 * (lane >> 5);
+    const int left = !col ? 0 : m0 + BM <= M ? 64 : M - mb;   // rows of the lane that exist, counted from mb
+    const size_t at0 = (size_t)(mb < M ? mb : 0) * g.n_out + (col ? n : 0);
+    const T* bx = static_cast<const T*>(g.bnb.x) + at0;
+    const T* by = static_cast<const T*>(g.bnb.y) + at0;
     float s0 = 0.f, s1 = 0.f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int m = m0 + wm0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int dr = 8 * (v >> 2) + (v & 3);
       float gv = 0.f, xh = 0.f;
-      if (col && m < M) {
-        const size_t at = (size_t)m * g.n_out + n;
+      if (dr < left) {
+        const size_t at = (size_t)dr * g.n_out;
         gv = Elem<T>::load(by + at) > 0.f ? acc[v] : 0.f;
         xh = (Elem<T>::load(bx + at) - mu) * is;
       }
@@ -501,6 +514,47 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   // ACT: the instantiation whose epilogue adds a bias and applies a ReLU (it never accumulates)
   float bias_n = 0.f;
   if constexpr (ACT) bias_n = g.bias ? g.bias[n] : 0.f;
+  if (g.out_stride == 1 && g.out_h == g.p && g.out_w == g.q) {
+    // dense result (every forward pass, every stride-1 data gradient): row m at m * n_out.  One
+    // pointer per lane, the sixteen rows at distances that are the same for every lane.
+    const int mb = m0 + wm0 + 4 * (lane >> 5);
+    const int left = m0 + BM <= M ? 64 : M - mb;      // a whole tile (all but the last row tile): no row is tested
+    T* o0 = static_cast<T*>(g.out) + (size_t)(mb < M ? mb : 0) * g.n_out + n;
+    if (m0 + BM <= M && !(!ACT && g.accumulate)) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float val = acc[v];
+        if constexpr (ACT) {
+          val += bias_n;
+          if (g.relu) val = fmaxf(val, 0.f);
+        }
+        Elem<T>::store(o0 + (size_t)(8 * (v >> 2) + (v & 3)) * g.n_out, val);
+      }
+      return;
+    }
+    if (!ACT && g.accumulate) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int dr = 8 * (v >> 2) + (v & 3);
+        if (dr >= left) continue;
+        T* o = o0 + (size_t)dr * g.n_out;
+        Elem<T>::store(o, acc[v] + Elem<T>::load(o));
+      }
+    } else {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int dr = 8 * (v >> 2) + (v & 3);
+        if (dr >= left) continue;
+        float val = acc[v];
+        if constexpr (ACT) {
+          val += bias_n;
+          if (g.relu) val = fmaxf(val, 0.f);
+        }
+        Elem<T>::store(o0 + (size_t)dr * g.n_out, val);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int m = m0 + wm0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
