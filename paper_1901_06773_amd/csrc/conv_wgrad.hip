@@ -252,6 +252,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
     for (int i = 0; i < 2; ++i) a_lane[i] = (uint32_t)(row + 16 * i) * (uint32_t)(g.cout * 4) + (uint32_t)(co0 + col4 * 4) * 4;
     const uint32_t b_lane = (uint32_t)(ci0 + col4 * 4) * 4;
     int r_org[2] = {0, 0}, r_p[2] = {0, 0}, r_q[2] = {0, 0};
+    const float inv_q = 1.0f / (float)g.q, inv_p = 1.0f / (float)g.p;
     if (!plain) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
@@ -286,11 +287,15 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
         if (!plain) {
           const int iy = r_p[i] * g.stride + kr - g.pad, ix = r_q[i] * g.stride + kt - g.pad;
           pix = ((unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd) ? r_org[i] + iy * g.wd + ix : -1;
-          r_q[i] += BKM;
-          while (r_q[i] >= g.q) {
-            r_q[i] -= g.q;
-            if (++r_p[i] == g.p) { r_p[i] = 0; r_org[i] += g.h * g.wd; }
-          }
+          // 32 positions on, without a loop that runs differently in every lane: the number of
+          // rows and of images passed are small quotients, exact in float with the half added
+          const int xq = r_q[i] + BKM;
+          const int wq = (int)(((float)xq + 0.5f) * inv_q);
+          r_q[i] = xq - wq * g.q;
+          const int xp = r_p[i] + wq;
+          const int wp = (int)(((float)xp + 0.5f) * inv_p);
+          r_p[i] = xp - wp * g.p;
+          r_org[i] += wp * (g.h * g.wd);
         }
         const uint32_t vb = (mok && pix >= 0) ? (uint32_t)pix * (uint32_t)(g.cin * 4) + b_lane : OUTSIDE;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(size_t)(lds_b + buf * (BKM * 256) + i * (16 * 256)), 16, vb,
@@ -543,7 +548,8 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   if (probe && probe->before) (void)hipEventRecord(probe->before, st);
   // direct loader: fp32 storage, both operands inside 32-bit buffer ranges (the last bytes stay
   // free for the offset that stands for "outside") and 16-byte aligned
-  const bool direct = fast && g.dtype == DT_F32 && Mrows * g.cout * es <= 0xFFFFFF00L &&
+  // (p, q <= 4096: the range over which the loader's float quotients were checked exhaustively)
+  const bool direct = fast && g.dtype == DT_F32 && g.p <= 4096 && g.q <= 4096 && Mrows * g.cout * es <= 0xFFFFFF00L &&
                       (long)g.n_img * g.h * g.wd * g.cin * es <= 0xFFFFFF00L &&
                       (reinterpret_cast<uintptr_t>(g.x) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.dy) & 15) == 0;
 #define ACC_WGRAD_LAUNCH(F, T)                                                                             \
