@@ -162,6 +162,77 @@ __global__ __launch_bounds__(THREADS) void maxpool_bwd_kernel(const T* __restric
   }
 }
 
+// The same for 3x3 windows at stride 2 with padding 1 (the stem pool of the ResNets): one thread
+// per 2x2 block of input positions and four channels.  The block (rows 2a, 2a+1, columns 2b,
+// 2b+1) is covered by the windows p in {a, a+1}, q in {b, b+1} and by no other, so each
+// window's maximum is looked up once for the four positions instead of once per position
+// (36 loads for four results instead of 81).  Windows are visited in the same (p, q) order
+// and the same first maximum wins, so every sum has the same terms in the same order as in
+// the kernel above.
+template <class T>
+__global__ __launch_bounds__(THREADS) void maxpool3s2_bwd_kernel(const T* __restrict__ x,
+                                                                 const T* __restrict__ dy, T* dx, int n,
+                                                                 int h, int wd, int c, int ho, int wo,
+                                                                 int accumulate) {
+  const int cg = c >> 2, hb = (h + 1) >> 1, wb = (wd + 1) >> 1;
+  const size_t total = (size_t)n * hb * wb * cg;
+  for (size_t i = (size_t)blockIdx.x * THREADS + threadIdx.x; i < total; i += (size_t)gridDim.x * THREADS) {
+    const int g = (int)(i % cg);
+    size_t rest = i / cg;
+    const int b = (int)(rest % wb); rest /= wb;
+    const int a = (int)(rest % hb);
+    const int img = (int)(rest / hb);
+    float acc[2][2][4] = {};
+    for (int p = a; p <= a + 1 && p < ho; ++p)
+      for (int q = b; q <= b + 1 && q < wo; ++q) {
+        float best[4] = {0.f, 0.f, 0.f, 0.f};
+        int at[4] = {-1, -1, -1, -1};
+#pragma unroll
+        for (int kr = 0; kr < 3; ++kr) {
+          const int yy = 2 * p + kr - 1;
+          if ((unsigned)yy >= (unsigned)h) continue;
+#pragma unroll
+          for (int kt = 0; kt < 3; ++kt) {
+            const int xx = 2 * q + kt - 1;
+            if ((unsigned)xx >= (unsigned)wd) continue;
+            float v[4];
+            Elem<T>::load4(x + ((size_t)(img * h + yy) * wd + xx) * c + g * 4, v);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (at[j] < 0 || v[j] > best[j]) { best[j] = v[j]; at[j] = yy * wd + xx; }
+          }
+        }
+        float d[4];
+        Elem<T>::load4(dy + ((size_t)(img * ho + p) * wo + q) * c + g * 4, d);
+#pragma unroll
+        for (int ry = 0; ry < 2; ++ry)
+#pragma unroll
+          for (int rx = 0; rx < 2; ++rx) {
+            const int me = (2 * a + ry) * wd + 2 * b + rx;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (at[j] == me) acc[ry][rx][j] += d[j];
+          }
+      }
+#pragma unroll
+    for (int ry = 0; ry < 2; ++ry)
+#pragma unroll
+      for (int rx = 0; rx < 2; ++rx) {
+        const int iy = 2 * a + ry, ix = 2 * b + rx;
+        if (iy >= h || ix >= wd) continue;
+        T* out = dx + ((size_t)(img * h + iy) * wd + ix) * c + g * 4;
+        float o[4] = {acc[ry][rx][0], acc[ry][rx][1], acc[ry][rx][2], acc[ry][rx][3]};
+        if (accumulate) {
+          float old[4];
+          Elem<T>::load4(out, old);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[j] = old[j] + o[j];
+        }
+        Elem<T>::store4(out, o);
+      }
+  }
+}
+
 // y[n][c] = mean over hw of x[n][hw][c]
 template <class T>
 __global__ __launch_bounds__(THREADS) void gap_fwd_kernel(const T* __restrict__ x, T* __restrict__ y,
@@ -418,7 +489,11 @@ hipError_t maxpool_backward(const void* x, const void* dy, void* dx, int n, int 
     return hipErrorInvalidValue;
   const int ho = (h + 2 * pad - r) / stride + 1, wo = (wd + 2 * pad - s) / stride + 1;
   if (ho <= 0 || wo <= 0) return hipErrorInvalidValue;
-  if (c % 4 == 0) {
+  if (c % 4 == 0 && r == 3 && s == 3 && stride == 2 && pad == 1) {
+    const size_t total = (size_t)n * ((h + 1) / 2) * ((wd + 1) / 2) * (c / 4);
+    ACC_DISPATCH(dtype, hipLaunchKernelGGL(maxpool3s2_bwd_kernel<T>, dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0, st,
+                                           (const T*)x, (const T*)dy, (T*)dx, n, h, wd, c, ho, wo, accumulate));
+  } else if (c % 4 == 0) {
     const size_t total = (size_t)n * h * wd * (c / 4);
     ACC_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_kernel<T, 4>), dim3(grid_for(total, 256 * 64)), dim3(THREADS), 0,
                                            st, (const T*)x, (const T*)dy, (T*)dx, n, h, wd, c, r, s, stride, pad, ho,

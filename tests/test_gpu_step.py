@@ -65,6 +65,8 @@ NETS = {
     "config1_unit": (lambda: S.bottleneck_unit(), 2),                       # BASELINE configs[0]
     "mini_resnet_w8": (lambda: S.resnet((1, 2), in_hw=32, classes=10, width=8), 3),
     "mini_resnet_w32": (lambda: S.resnet((1, 1, 2, 1), in_hw=64, classes=100, width=32), 5),
+    # 30 x 30 input: the stem leaves 15 x 15 for the max-pool (odd: ragged last windows and blocks)
+    "mini_resnet_odd": (lambda: S.resnet((1, 1), in_hw=30, classes=10, width=8), 3),
     "wide_chain": (wide_chain, 6),
     "tall_chain": (tall_chain, 8),
     # strided 3x3 convolutions with a data gradient: basic blocks (18/34-layer style) and v1.5 strides
