@@ -489,7 +489,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, f
   if (i4 >= count) return;
   if (i4 + 4 <= count && (count & 3) == 0) {
     float4 s = *reinterpret_cast<const float4*>(part + i4);
-    for (int k = 1; k < splits; ++k) {
+    // eight parts fetched at a time, added in their order: with hundreds of parts (the stem's
+    // weight gradient) one load waiting for the sum before it made this a chain of latencies
+    int k = 1;
+    for (; k + 8 <= splits; k += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(part + (size_t)(k + u) * count + i4);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+    }
+    for (; k < splits; ++k) {
       const float4 v = *reinterpret_cast<const float4*>(part + (size_t)k * count + i4);
       s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
