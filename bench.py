@@ -181,6 +181,11 @@ def main():
     if timed_swaps:
         kp, step_ms, pstats = profiled(ctx)
     names = [ctx.step_info(j)["name"] for j in range(ctx.step_count())]
+    # bytes of the tensors every step reads and writes (the headline plan is the installed one)
+    step_bytes = []
+    for j in range(ctx.step_count()):
+        reads, writes = ctx.step_io(j)
+        step_bytes.append(sum(ctx.tensor_info(t)["bytes"] for t in set(reads) | set(writes)))
     ctx.close()
     del ctx
     torch.cuda.empty_cache()
@@ -226,9 +231,16 @@ def main():
                     timed_in=("two extra steps of the headline context" if timed_swaps else "the no-swap run of the same minibatch") +
                              ", weight gradients on the compute stream so that every kernel is timed alone")
     # step-level view: BN / pooling / update steps against the HBM roofline
-    by_kind = {}
-    for n_, ms in zip(names, step_ms):
+    by_kind, bytes_by_kind = {}, {}
+    for n_, ms, nb in zip(names, step_ms, step_bytes):
         by_kind[n_] = by_kind.get(n_, 0.0) + float(ms)
+        bytes_by_kind[n_] = bytes_by_kind.get(n_, 0) + nb
+    # batch norm (+ReLU, +add) against the HBM roofline: bytes of the tensors the steps touch
+    # (each counted once per step, although backward reads x and dy twice) over their time
+    hbm = {n_: dict(gb_per_step=bytes_by_kind[n_] / 1e9, ms_per_step=by_kind[n_],
+                    gbs=bytes_by_kind[n_] / 1e9 / (by_kind[n_] * 1e-3), frac_of_hbm_peak=bytes_by_kind[n_] / 1e9 /
+                    (by_kind[n_] * 1e-3) / 8000.0)
+           for n_ in ("bn_fwd", "bn_bwd", "maxpool_fwd", "maxpool_bwd") if by_kind.get(n_, 0) > 0}
     conv = dict(tflops=conv_flops / (conv_ms * 1e-3) / 1e12, frac_of_mfma_peak=conv_flops / (conv_ms * 1e-3) / 1e12 /
                 PEAK_FP32_MFMA_TFLOPS, ms_per_step=conv_ms, flops_per_step=conv_flops,
                 kernels=[dict(name=r["name"], launches=r["launches"], ms=r["ms"],
@@ -273,7 +285,7 @@ def main():
                   predicted_ms=summ["t_iter"] * 1e3, predicted_stall_ms=summ["t_stall"] * 1e3,
                   predicted_compute_ms=summ["t_compute"] * 1e3, plan_ms=summ["plan_ms"],
                   host_issue_ms=stats["host_issue_ms"]),
-        step_ms_by_kind=by_kind, sweep=sweep, noswap_max_k=noswap_max_k, tuner=tuner, loss=loss,
+        step_ms_by_kind=by_kind, hbm_bound_steps=hbm, sweep=sweep, noswap_max_k=noswap_max_k, tuner=tuner, loss=loss,
         paper_context="AccUDNN on an NVIDIA M40 (Caffe + cuDNN): ResNet-152, 12 GB budget, k=54, 24 images/s "
                       "(Table 1); 8.3 GB at k=32 with 64% of maps offloaded (Sec. 7.3)")
     print(json.dumps(out))
