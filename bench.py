@@ -287,7 +287,7 @@ def main():
                   host_issue_ms=stats["host_issue_ms"]),
         step_ms_by_kind=by_kind, hbm_bound_steps=hbm, sweep=sweep, noswap_max_k=noswap_max_k, tuner=tuner, loss=loss,
         paper_context="AccUDNN on an NVIDIA M40 (Caffe + cuDNN): ResNet-152, 12 GB budget, k=54, 24 images/s "
-                      "(Table 1); 8.3 GB at k=32 with 64% of maps offloaded (Sec. 7.3)")
+                      "(Table 1); 8.3 GB at k=32 with 64% of maps offloaded (Sec. 6.3)")
     print(json.dumps(out))
 
 

@@ -1,11 +1,12 @@
 /*
  * accudnn.h - C ABI of the MI355X-native training-step library.
  *
- * One context trains one network on one GPU under a device-memory budget, the
- * problem the paper states in Sec. 3 ("given a certain UDNN and hardware
- * configuration ... memory budget"): the layer list is unfolded into 2N steps
- * (Sec. 4.1), feature maps are the swap targets, and the runtime knows four
- * operations: allocate, release, offload, prefetch (Sec. 4.1, Sec. 6).
+ * One context trains one network on one GPU under a device-memory budget.  That is
+ * the problem of Sec. 2 (overall architecture): a network, a machine and a memory
+ * budget come in; a swapping strategy and a minibatch come out and are then executed.
+ * The layer list is unfolded into 2N steps (Sec. 3.1), feature maps are the swap
+ * targets, and the runtime knows four operations: allocate, release, offload,
+ * prefetch (Sec. 3.1, Sec. 5).
  *
  * Conventions
  *  - Every function returns ACC_OK (0) or a negative acc_status; nothing throws
@@ -15,7 +16,7 @@
  *    pool, the host arena and the streams alive until acc_destroy().
  *  - The library calls no hipMalloc: all device data (weights, gradients, feature
  *    maps, workspace, the input batch) lives inside the caller's pool, so the
- *    budget is a hard cap by construction (Sec. 6: one buffer pool of the size of
+ *    budget is a hard cap by construction (Sec. 5: one buffer pool of the size of
  *    the budget, sub-allocated at run time).
  *  - Activations are NHWC fp32 on the device, filters O-H-W-I; the host-side
  *    weight interface uses the framework-neutral OIHW order and converts.
@@ -46,7 +47,7 @@ enum { ACC_CONV = 0, ACC_BN = 1, ACC_RELU = 2, ACC_ADD = 3, ACC_MAXPOOL = 4, ACC
        ACC_FC = 6, ACC_SOFTMAX_CE = 7, ACC_BIAS = 8 };
 enum { ACC_F32 = 0, ACC_BF16 = 1 };
 /* planner modes: keep everything / swap every feature map (the "naive" strategy of
- * Sec. 4.1) / performance-model-guided choice (the "dynamic" strategy, Sec. 4.1, 4.4, 5.1) */
+ * Sec. 3.1) / performance-model-guided choice (the "dynamic" strategy, Sec. 3.1, 3.4, 4.1) */
 enum { ACC_PLAN_NONE = 0, ACC_PLAN_NAIVE_ALL = 1, ACC_PLAN_DYNAMIC = 2 };
 enum { ACC_LOC_HOST = 0, ACC_LOC_DEVICE = 1 };
 
@@ -63,7 +64,7 @@ typedef struct {
   int32_t kind, in0, in1, cin, cout, r, s, stride, pad;
 } acc_layer;
 
-/* Device pool, pinned host arena and the three streams of Sec. 6 (compute,
+/* Device pool, pinned host arena and the three streams of Sec. 5 (compute,
  * swap-out, swap-in; hipStream_t passed as void*).  With a NULL acc_resources the
  * context is planning-only: everything but calibrate / train_step / weights works.
  * s_wgrad (may be NULL) is a fourth stream, different from the other three: the weight
@@ -134,7 +135,7 @@ typedef struct {
 typedef struct acc_ctx acc_ctx;
 
 /* ---- context ---------------------------------------------------------------------- */
-/* Builds the fused step list and the tensor table (static information of Sec. 4.2).
+/* Builds the fused step list and the tensor table (static information of Sec. 3.2).
  * With resources: places weights / gradients / statistics at the bottom of the pool.
  * dtype: ACC_F32, or ACC_BF16 = activations, activation gradients and the copy of the
  * weights that the kernels read are stored as bf16 (half the bytes to keep and to swap),
@@ -146,19 +147,22 @@ void acc_destroy(acc_ctx* ctx);
 const char* acc_last_error(const acc_ctx* ctx);   /* ctx may be NULL: last create error */
 const char* acc_step_kind_name(int kind);
 
-/* fp32 master weights of one layer, host side, OIHW / [gamma|beta] / [W|b]; n = element
- * count and must match.  Blocking.  get_grads returns d(loss)/d(weights) of the last step. */
+/* Parameters and their gradients are the memory objects that never leave the GPU (Sec. 3.1:
+ * feature maps are the swap targets; M_para of Algorithm 2).  fp32 master weights of one
+ * layer, host side, OIHW / [gamma|beta] / [W|b]; n = element count and must match.
+ * Blocking.  get_grads returns d(loss)/d(weights) of the last step (a parity hook: the
+ * abstract's claim that swapping costs no accuracy is checked on these, bit for bit). */
 int acc_set_weights(acc_ctx* ctx, int layer, const float* host_w, size_t n);
 int acc_get_weights(acc_ctx* ctx, int layer, float* host_w, size_t n);
 int acc_get_grads(acc_ctx* ctx, int layer, float* host_g, size_t n);
 int acc_param_count(const acc_ctx* ctx, int layer, size_t* n);
 
-/* ---- cost model (dynamic information, Sec. 4.2; Eq. 2 and Eq. 5) ------------------- */
+/* ---- cost model (dynamic information, Sec. 3.2; Eq. 2 and Eq. 5) ------------------- */
 /* Measures the link (D2H / H2D copies of two sizes on the side streams) and every step's
  * kernels (events on the compute stream, three iterations on a synthetic batch, weights
  * untouched) at each minibatch of ks[] that trains in the pool without swapping.  If some
  * of ks[] are too large for that, the largest minibatch that does fit is measured too and
- * the planner scales its times in proportion (Eq. 1, Sec. 4.3.1).  Needs resources;
+ * the planner scales its times in proportion (Eq. 1, Sec. 3.3.1).  Needs resources;
  * ACC_EPOOL if not even one image fits. */
 int acc_calibrate(acc_ctx* ctx, const int* ks, int nk);
 /* Synthetic cost model for planning without a GPU: step time = launch_s + flops /
@@ -174,7 +178,7 @@ int acc_set_step_times(acc_ctx* ctx, const double* seconds, int n);
  * seconds[nk][n_steps] row-major, link[3] = D2H bytes/s, H2D bytes/s, latency per copy (s).
  * get: returns nk (0 if nothing was measured) or ACC_EINVAL if max_k / max_seconds are too
  * small; any output pointer may be null.  Between two measured minibatches the planner
- * interpolates linearly in k; beyond the largest it scales in proportion (Sec. 4.3.1:
+ * interpolates linearly in k; beyond the largest it scales in proportion (Sec. 3.3.1:
  * throughput saturates), below the smallest it scales down to no less than the launch cost. */
 int acc_get_calibration(const acc_ctx* ctx, int* ks, int max_k, double* seconds, size_t max_seconds,
                         double* link);
@@ -183,7 +187,7 @@ int acc_set_calibration(acc_ctx* ctx, const int* ks, int nk, const double* secon
 /* ---- planning (Algorithm 1, Eq. 4-6, body of Algorithm 2) ------------------------- */
 int acc_plan_swaps(acc_ctx* ctx, int minibatch, size_t budget_bytes, int mode,
                    acc_plan_summary* out);
-/* ---- efficiency-optimal minibatch (Sec. 5.1: Eq. 7, Algorithm 2; Sec. 5.2: Eq. 9) --- */
+/* ---- efficiency-optimal minibatch (Sec. 4.1: Eq. 7, Algorithm 2; Sec. 4.2: Eq. 9) --- */
 typedef struct {
   int32_t k_best;           /* minibatch with the highest predicted images/s              */
   int32_t k_trainable_max;  /* k_max: largest minibatch in [k_lo, k_hi] that trains at all  */
@@ -248,12 +252,18 @@ typedef struct {
 } acc_timeline_entry;
 int acc_get_timeline(acc_ctx* ctx, int which, acc_timeline_entry* out, int max_entries);
 
-/* ---- execution --------------------------------------------------------------------- */
-/* One forward / backward / SGD step at the planned minibatch.  images: fp32 NCHW,
+/* ---- execution (runtime memory manager, Sec. 5; the 2N steps of Sec. 3.1) ------------- */
+/* One iteration as Sec. 2 describes its last stage and Sec. 5 its runtime: the 2N steps in
+ * order on the compute stream, offloads (then release) on the swap-out stream, allocate and
+ * prefetch on the swap-in stream, the input batch being the first layer's prefetch
+ * (Algorithm 1, j = 1); then the weight update.
+ * One forward / backward / SGD step at the planned minibatch.  images: fp32 NCHW,
  * pinned host (ACC_LOC_HOST) or device (ACC_LOC_DEVICE); labels: int32, host.  Blocks
  * until the step is done; *loss_out is the mean cross-entropy at the pre-update weights. */
 int acc_train_step(acc_ctx* ctx, const float* images, int images_loc, const int32_t* labels,
                    float lr, float* loss_out);
+/* What the last iteration did (Sec. 6.2.2 and 6.2.3 verify the memory and the transfer model
+ * on such figures: bytes in the pool, bytes over the link, copy durations). */
 int acc_get_stats(acc_ctx* ctx, acc_stats* out);
 /* on = 0: weight gradients run on the compute stream even if the context has a stream for
  * them (for measurements); on != 0 (default): they use it. */

@@ -4,7 +4,7 @@
 //
 // What it computes is the quantity the paper's runtime must leave unchanged:
 // swapping feature maps out and back in moves bytes and never alters values
-// (abstract: no accuracy loss; Sec. 4.1: the four operations allocate / release /
+// (abstract: no accuracy loss; Sec. 3.1: the four operations allocate / release /
 // offload / prefetch are copies), so the result of a training iteration is the
 // textbook forward / backward / SGD step of the network.
 //
@@ -499,7 +499,7 @@ int train_step(const int32_t* recs, int nl, int in_c, int in_h, int in_w, int k,
     std::vector<T>().swap(gout[i]);
   }
 
-  // plain SGD on every parameter (Sec. 5.2 discusses only the learning rate; no
+  // plain SGD on every parameter (Sec. 4.2 discusses only the learning rate; no
   // momentum or weight decay is part of the step)
   for (int i = 0; i < nl; ++i) {
     if (grads && grads[i] && !gpar[i].empty())

@@ -1,8 +1,8 @@
 """Plain-Python checker of a swap plan (TEST INFRASTRUCTURE, like the rest of oracle/).
 
 It takes what the library exports about a plan - the tensor table, the per-step read and
-write lists (the global memory-object access pattern of Sec. 4.2) and the instruction list
-for the three streams of Sec. 6 - and re-derives from the paper's definitions, with no code
+write lists (the global memory-object access pattern of Sec. 3.2) and the instruction list
+for the three streams of Sec. 5 - and re-derives from the paper's definitions, with no code
 shared with the planner:
 
   * the memory model, Eq. 4: at every instant the bytes allocated minus the bytes released

@@ -1,6 +1,6 @@
 // Context, runtime memory manager and executor behind the C ABI (include/accudnn.h).
 //
-// The runtime of Sec. 6 of the paper: one buffer pool of the size of the budget, pinned
+// The runtime of Sec. 5 of the paper: one buffer pool of the size of the budget, pinned
 // host backing store, and three streams (compute, swap-out, swap-in).  The four operations
 // allocate / release / offload / prefetch are resolved at plan time into pool offsets and
 // event waits (plan.h); train_step() only walks the instruction list, so the host never
@@ -1140,7 +1140,7 @@ extern "C" int acc_calibrate(acc_ctx* c, const int* ks, int nk) {
   // dynamic information 1: per-step compute time, taken from real iterations at every
   // requested minibatch that trains in this pool without swapping.  A larger minibatch is
   // not run here: its step times follow from the largest measured one in proportion to
-  // the minibatch (Eq. 1; throughput has saturated by then, Sec. 4.3.1), so if any request
+  // the minibatch (Eq. 1; throughput has saturated by then, Sec. 3.3.1), so if any request
   // is too large the largest minibatch that does fit is measured as well.
   const bool was_prof = c->profiling;
   std::vector<int> ok_ks;

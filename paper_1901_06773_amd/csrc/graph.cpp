@@ -1,5 +1,5 @@
-// Static analyzer (Sec. 4.2, "static information"): walks the layer records once and
-// produces the 2N-step unfolding of Sec. 4.1 with its memory-object access pattern,
+// Static analyzer (Sec. 3.2, "static information"): walks the layer records once and
+// produces the 2N-step unfolding of Sec. 3.1 with its memory-object access pattern,
 // object sizes proportional to the minibatch, and FLOPs per step (Eq. 1).
 //
 // Fusions chosen for a bandwidth-bound GPU: BN+ReLU and BN+add+ReLU are one step each,

@@ -1,5 +1,5 @@
-// Static information of the planner (Sec. 4.2 of the paper): the network unfolded into
-// 2N steps (Sec. 4.1), the memory objects each step reads and writes, their sizes as a
+// Static information of the planner (Sec. 3.2 of the paper): the network unfolded into
+// 2N steps (Sec. 3.1), the memory objects each step reads and writes, their sizes as a
 // linear function of the minibatch, FLOPs per step (Eq. 1), and their lifetimes.  The
 // global memory-object access pattern (GMAP) is the per-step read/write lists below.
 // Host code only; no device calls.

@@ -13,7 +13,7 @@ double CostModel::step_time(const Graph& g, int step, int k) const {
   if (!fixed.empty() && step < (int)fixed.size()) return fixed[step];
   if (!ks.empty()) {
     // measured times; between two measured minibatches interpolate linearly in k, beyond the
-    // largest one scale in proportion (throughput saturated, Sec. 4.3.1), below the smallest
+    // largest one scale in proportion (throughput saturated, Sec. 3.3.1), below the smallest
     // scale down but never under the launch cost
     const int n = (int)ks.size();
     if (k >= ks[n - 1]) return table[n - 1][step] * ((double)k / ks[n - 1]);

@@ -1,6 +1,6 @@
 // Performance model, Algorithm 1 and the body of Algorithm 2 of the paper, on the host.
 //
-// A plan is an instruction list for three streams (compute, swap-out, swap-in; Sec. 6)
+// A plan is an instruction list for three streams (compute, swap-out, swap-in; Sec. 5)
 // with pool offsets fixed ahead of time.  Memory reuse is ordered by events that are part
 // of the plan: a block may be written again only after the last use of its previous
 // occupant (a kernel or an offload copy) has finished.  The same list is interpreted twice:

@@ -1,5 +1,5 @@
 """Checks of the performance model against the machine, in the manner of the paper's model
-validation (Sec. 7.2: throughput against the minibatch per layer type, the predicted against
+validation (Sec. 6.2: throughput against the minibatch per layer type, the predicted against
 the observed course of one iteration, memory in use and bytes swapped over the iteration).
 
 Everything here reads what the library already records (the calibration table, the plan, the

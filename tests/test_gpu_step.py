@@ -200,7 +200,7 @@ def bit_equal(a, b, what):
 
 @pytest.mark.parametrize("name", list(NETS))
 def test_swapping_everything_is_bit_exact(name):
-    """Naive strategy (Sec. 4.1): every feature map out and back in, in a pool just
+    """Naive strategy (Sec. 3.1): every feature map out and back in, in a pool just
     above the layer-wise peak, against the run that keeps everything resident."""
     make, k = NETS[name]
     net = make()
@@ -543,7 +543,7 @@ def test_weight_gradient_stream_changes_no_bit(name):
             bit_equal(out["weights"], ref["weights"], f"weights {kw}")
 
 
-# ------------------------------------------------------------------ model validation (Sec. 7.2)
+# ------------------------------------------------------------------ model validation (Sec. 6.2)
 @pytest.mark.parametrize("case", ["mini_naive", "resnet50_dynamic"])
 def test_observed_timeline_obeys_the_plan_and_tracks_the_prediction(case):
     """A step run with events around every step and copy: on the device no instruction starts

@@ -109,7 +109,7 @@ PUB = published()
 
 
 def test_memory_stays_under_the_figures_the_paper_prints_for_caffe():
-    """Sec. 7.3 A: ResNet-152 at minibatch 32 takes more than 24 GB resident and 2.5 GB with
+    """Sec. 6.3 A: ResNet-152 at minibatch 32 takes more than 24 GB resident and 2.5 GB with
     every map swapped in the paper's Caffe; the fused step here must need less of both, and
     the same order of reduction (network-wide to layer-wide)."""
     b = B()
