@@ -144,7 +144,7 @@ typedef struct acc_ctx acc_ctx;
 int acc_create(const acc_layer* layers, int n_layers, int in_c, int in_h, int in_w, int dtype,
                const acc_resources* res, acc_ctx** out);
 void acc_destroy(acc_ctx* ctx);
-const char* acc_last_error(const acc_ctx* ctx);   /* ctx may be NULL: last create error */
+const char* acc_last_error(const acc_ctx* ctx);   /* ctx may be NULL: this thread's last error of acc_create or of a call without a context */
 const char* acc_step_kind_name(int kind);
 
 /* Parameters and their gradients are the memory objects that never leave the GPU (Sec. 3.1:
@@ -316,6 +316,21 @@ int acc_op_bn_fwd(const void* x, const float* gamma, const float* beta, const vo
 int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const float* gamma,
                   const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
                   void* g_out, int rows, int c, void* workspace, int dtype, void* stream);
+
+/* ---- for callers that cannot allocate --------------------------------------------- */
+/* acc_op_bn_fwd() without the workspace argument, for code that may not call hipMalloc or
+ * hand a workspace through: kernels under HIP graph capture, serving loops, harnesses that
+ * forbid allocation.  The reduction workspace is a device array built into the library
+ * (ACC_NOALLOC_BN_MAX_C channels: 32.03 MiB per GPU, held until the process ends); the call
+ * allocates and frees nothing, on the host or on the device.  Same arguments, kernels and
+ * results as acc_op_bn_fwd(); stream must belong to the current device.  c above
+ * ACC_NOALLOC_BN_MAX_C is ACC_EINVAL (text in acc_last_error(NULL)) and nothing is launched.
+ * All calls on one GPU share the array: calls that overlap there (different streams with no
+ * event between them, or different threads) race; nothing needs to be cleared between calls. */
+#define ACC_NOALLOC_BN_MAX_C 2048
+int acc_op_bn_fwd_noalloc(const void* x, const float* gamma, const float* beta, const void* res,
+                          void* y, float* mean, float* istd, int rows, int c, int relu, float eps,
+                          int dtype, void* stream);
 
 #ifdef __cplusplus
 }

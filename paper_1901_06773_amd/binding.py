@@ -143,6 +143,7 @@ _PROTOS = {
     "acc_op_bn_workspace": (_SZ, [_I]),
     "acc_op_bn_fwd": (_I, [_VP] * 7 + [_I, _I, _I, _F, _VP, _I, _VP]),
     "acc_op_bn_bwd": (_I, [_VP] * 10 + [_I, _I, _VP, _I, _VP]),
+    "acc_op_bn_fwd_noalloc": (_I, [_VP] * 7 + [_I, _I, _I, _F, _I, _VP]),
 }
 for _name, (_res, _args) in _PROTOS.items():
     _fn = getattr(_lib, _name)
@@ -439,6 +440,19 @@ def op_bn_fwd(x, gamma, beta, res, y, mean, istd, relu, eps, ws):
                             _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_bn_fwd")
+
+
+def op_bn_fwd_noalloc(x, gamma, beta, res, y, mean, istd, relu, eps):
+    """acc_op_bn_fwd with the library's built-in workspace (no allocation anywhere)."""
+    import torch
+    c = x.shape[-1]
+    rows = x.numel() // c
+    rc = _lib.acc_op_bn_fwd_noalloc(x.data_ptr(), gamma.data_ptr(), beta.data_ptr(),
+                                    res.data_ptr() if res is not None else None, y.data_ptr(), mean.data_ptr(),
+                                    istd.data_ptr(), rows, c, 1 if relu else 0, float(eps), _dtype_of(x),
+                                    _stream_ptr(torch))
+    if rc != ACC_OK:
+        raise AccError(rc, _lib.acc_last_error(None).decode())
 
 
 def op_bn_bwd(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, ws):

@@ -31,6 +31,8 @@ double now_ms() {
 }
 }  // namespace
 
+void acc::set_thread_error(const char* text) { g_create_error = text ? text : ""; }
+
 struct acc_ctx {
   Graph g;
   CostModel cm;

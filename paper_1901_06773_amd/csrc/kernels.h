@@ -178,4 +178,7 @@ hipError_t fill_zero(float* p, size_t count, hipStream_t st);
 // y[n][hw][c] (dtype) = x[n][c][hw] (fp32)
 hipError_t nchw_to_nhwc(const float* x, void* y, int n, int c, int hw, int dtype, hipStream_t st);
 
+// Text that acc_last_error(NULL) returns on this thread (calls that have no context).
+void set_thread_error(const char* text);
+
 }  // namespace acc
