@@ -124,12 +124,19 @@ typedef struct {
 } acc_tensor_info;
 
 typedef struct {
-  double step_ms;           /* last train_step: events on the compute stream              */
+  double step_ms;           /* last train_step: host clock, entry to completion           */
   double host_issue_ms;     /* last train_step: host time to issue all work               */
-  uint64_t peak_pool_bytes; /* high-water mark actually touched (static part included)    */
+  uint64_t peak_pool_bytes; /* pool offset where the highest byte in use ends, static part
+                               included.  With ACC_DEBUG_POISON: measured (the highest word
+                               that anything wrote during the iteration); otherwise the end
+                               of the highest block of the plan                           */
   uint64_t bytes_out, bytes_in; /* offloaded / prefetched in the last step                */
   double d2h_ms, h2d_ms;    /* summed copy durations (only when profiling is enabled)     */
   uint64_t steps_run;
+  uint64_t touched_pool_bytes; /* ACC_DEBUG_POISON: bytes of the pool written at least once
+                               during the iteration, static part included; else 0         */
+  int32_t peak_is_measured; /* 1 if peak_pool_bytes comes from the poison scan            */
+  int32_t reserved;
 } acc_stats;
 
 typedef struct acc_ctx acc_ctx;
@@ -265,6 +272,36 @@ int acc_train_step(acc_ctx* ctx, const float* images, int images_loc, const int3
 /* What the last iteration did (Sec. 6.2.2 and 6.2.3 verify the memory and the transfer model
  * on such figures: bytes in the pool, bytes over the link, copy durations). */
 int acc_get_stats(acc_ctx* ctx, acc_stats* out);
+/* Verification mode of the swap engine (Sec. 5's four operations, checked at run time).
+ * ACC_DEBUG_POISON: before every iteration the dynamic part of the pool and the used part of
+ * the host arena are filled with a NaN pattern; every block is filled with a second NaN
+ * pattern at the moment the plan releases it (after the last step that uses its tensor, on
+ * the compute stream; after the offload copy of a swapped map, on the swap-out stream).  A
+ * kernel or copy that runs before the data it needs has arrived, or after its block has been
+ * given away, then reads NaNs, and the loss or some gradient is not finite; a correct plan
+ * gives the same bits as without the mode.  After the iteration the pool is scanned:
+ * acc_stats.peak_pool_bytes / touched_pool_bytes are then measured, and a write beyond the
+ * budget makes acc_train_step return ACC_EPOOL.  Slow (two passes over the pool per
+ * iteration); flags = 0 switches it off. */
+enum { ACC_DEBUG_POISON = 1 };
+int acc_set_debug(acc_ctx* ctx, int flags);
+/* Parity hook: after the forward step that produces the stored output of `layer`, the next
+ * iterations copy it to host_dst (bytes >= minibatch * elements per image * element size,
+ * checked at acc_train_step; device layout NHWC in the context's storage type), complete when
+ * acc_train_step returns.  Stored outputs are those of a convolution that feeds a batch norm,
+ * of conv + bias (+ ReLU), of bn + ReLU and bn + add + ReLU (at the ReLU layer), of max-pool,
+ * global average pooling and FC; a layer fused away (a bn before its ReLU) is ACC_EINVAL.
+ * host_dst = NULL stops capturing that layer; layer = -1 with NULL stops all.  The pointer
+ * must stay valid while it is registered (pinned memory keeps the copy asynchronous). */
+int acc_capture_output(acc_ctx* ctx, int layer, void* host_dst, size_t bytes);
+/* Parity hook, the other way round: after the forward step that produces the stored output of
+ * `layer` (and after a capture of it), the next iterations overwrite it with host_src (same
+ * layout and size rule).  The rest of the iteration then runs on those values: with the
+ * outputs of an independent forward pass injected, the backward pass takes its discrete
+ * decisions (ReLU masks, max-pool winners) from the same numbers as that pass, and its
+ * gradients can be compared layer by layer without the noise of decisions that differ where
+ * a value lies within rounding of zero.  Same registration rules as acc_capture_output. */
+int acc_inject_output(acc_ctx* ctx, int layer, const void* host_src, size_t bytes);
 /* on = 0: weight gradients run on the compute stream even if the context has a stream for
  * them (for measurements); on != 0 (default): they use it. */
 int acc_set_wgrad_overlap(acc_ctx* ctx, int on);
@@ -283,6 +320,17 @@ typedef struct {
   double flops;
 } acc_kernel_profile;
 int acc_get_kernel_profile(acc_ctx* ctx, acc_kernel_profile* out, int max_entries);
+/* One entry per convolution-kernel launch of the last train_step run at level 2 or 3, in issue
+ * order: the step and layer record it belongs to, its role (0 forward product, 1 data gradient,
+ * 2 weight gradient; FC layers use the same kernels), which kernel instance ran (index of
+ * acc_get_kernel_profile's names in V_* order), milliseconds between the events around the
+ * launch and its algorithmic flops.  Returns the number of launches (which may exceed
+ * max_entries: then only the first max_entries were written). */
+typedef struct {
+  int32_t step, layer, role, variant;
+  double ms, flops;
+} acc_launch_profile;
+int acc_get_launch_profile(acc_ctx* ctx, acc_launch_profile* out, int max_entries);
 /* per-step kernel time of the last profiled train_step, milliseconds; n = step count */
 int acc_get_step_times_ms(acc_ctx* ctx, double* ms, int n);
 
@@ -316,6 +364,7 @@ int acc_op_bn_fwd(const void* x, const float* gamma, const float* beta, const vo
 int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const float* gamma,
                   const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
                   void* g_out, int rows, int c, void* workspace, int dtype, void* stream);
+
 
 /* ---- for callers that cannot allocate --------------------------------------------- */
 /* acc_op_bn_fwd() without the workspace argument, for code that may not call hipMalloc or

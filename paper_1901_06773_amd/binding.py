@@ -24,6 +24,7 @@ ACC_OK, ACC_EINVAL, ACC_EUNTRAINABLE, ACC_EPOOL, ACC_EHOSTMEM, ACC_EHIP, ACC_EST
 PLAN_NONE, PLAN_NAIVE_ALL, PLAN_DYNAMIC = 0, 1, 2
 LOC_HOST, LOC_DEVICE = 0, 1
 F32, BF16 = 0, 1
+DEBUG_POISON = 1
 STATUS_NAMES = {0: "ACC_OK", -1: "ACC_EINVAL", -2: "ACC_EUNTRAINABLE", -3: "ACC_EPOOL",
                 -4: "ACC_EHOSTMEM", -5: "ACC_EHIP", -6: "ACC_ESTATE"}
 
@@ -81,7 +82,8 @@ class acc_tensor_info(C.Structure):
 class acc_stats(C.Structure):
     _fields_ = [("step_ms", C.c_double), ("host_issue_ms", C.c_double), ("peak_pool_bytes", C.c_uint64),
                 ("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64), ("d2h_ms", C.c_double),
-                ("h2d_ms", C.c_double), ("steps_run", C.c_uint64)]
+                ("h2d_ms", C.c_double), ("steps_run", C.c_uint64), ("touched_pool_bytes", C.c_uint64),
+                ("peak_is_measured", C.c_int32), ("reserved", C.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -99,6 +101,11 @@ class acc_timeline_entry(C.Structure):
 
 class acc_kernel_profile(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("reserved", C.c_int32),
+                ("ms", C.c_double), ("flops", C.c_double)]
+
+
+class acc_launch_profile(C.Structure):
+    _fields_ = [("step", C.c_int32), ("layer", C.c_int32), ("role", C.c_int32), ("variant", C.c_int32),
                 ("ms", C.c_double), ("flops", C.c_double)]
 
 
@@ -133,9 +140,13 @@ _PROTOS = {
     "acc_train_step": (_I, [_VP, _VP, _I, _VP, _F, C.POINTER(_F)]),
     "acc_get_stats": (_I, [_VP, C.POINTER(acc_stats)]),
     "acc_set_profiling": (_I, [_VP, _I]),
+    "acc_set_debug": (_I, [_VP, _I]),
+    "acc_capture_output": (_I, [_VP, _I, _VP, _SZ]),
+    "acc_inject_output": (_I, [_VP, _I, _VP, _SZ]),
     "acc_set_wgrad_overlap": (_I, [_VP, _I]),
     "acc_get_step_times_ms": (_I, [_VP, C.POINTER(_D), _I]),
     "acc_get_kernel_profile": (_I, [_VP, C.POINTER(acc_kernel_profile), _I]),
+    "acc_get_launch_profile": (_I, [_VP, C.POINTER(acc_launch_profile), _I]),
     "acc_op_conv_workspace": (_SZ, [_I] * 9),
     "acc_op_conv_fwd": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_I, _VP]),
     "acc_op_conv_dgrad": (_I, [_VP, _VP, _VP] + [_I] * 10 + [_VP, _SZ, _I, _VP]),
@@ -357,6 +368,48 @@ class Context:
         """Weight gradients on their own stream beside the data gradients (default), or on the compute stream."""
         self._check(_lib.acc_set_wgrad_overlap(self._h, 1 if on else 0))
 
+    def set_debug(self, poison: bool):
+        """Verification mode: NaN-poison everything the plan has released or not yet brought back,
+        and measure the pool's high-water mark after every step."""
+        self._check(_lib.acc_set_debug(self._h, DEBUG_POISON if poison else 0))
+
+    def capture_outputs(self, layers: Sequence[int], shapes: dict, k: int) -> dict:
+        """Registers pinned buffers for the stored outputs of `layers` (shapes: layer -> (c, h, w));
+        returns {layer: torch tensor [k, h, w, c] in the storage type}, filled by every train_step."""
+        torch = self.torch
+        dt = torch.bfloat16 if self.dtype == BF16 else torch.float32
+        out = {}
+        for l in layers:
+            c, h, w = shapes[l]
+            buf = torch.empty((k, h, w, c), dtype=dt, pin_memory=True)
+            self._check(_lib.acc_capture_output(self._h, int(l), buf.data_ptr(), buf.numel() * buf.element_size()))
+            out[l] = buf
+        self._keep.append(out)
+        return out
+
+    def inject_outputs(self, values: dict, buffers: Optional[dict] = None):
+        """values: layer -> numpy array [k, h, w, c] float32 (device layout); every train_step from now
+        on overwrites the stored output of those layers with them right after it is produced.
+        buffers: pinned tensors of that shape to stage them in (e.g. those of capture_outputs, once
+        the captures are stopped); new ones are allocated otherwise."""
+        torch = self.torch
+        dt = torch.bfloat16 if self.dtype == BF16 else torch.float32
+        keep = {}
+        for l, v in values.items():
+            src = torch.from_numpy(np.ascontiguousarray(v, np.float32))
+            if buffers is not None:
+                buf = buffers[l]
+                buf.copy_(src.reshape(buf.shape))
+            else:
+                buf = src.to(dt).pin_memory()
+            self._check(_lib.acc_inject_output(self._h, int(l), buf.data_ptr(), buf.numel() * buf.element_size()))
+            keep[l] = buf
+        self._keep.append(keep)
+
+    def stop_captures(self):
+        self._check(_lib.acc_capture_output(self._h, -1, None, 0))
+        self._check(_lib.acc_inject_output(self._h, -1, None, 0))
+
     def set_profiling(self, level: int):
         """0 off, 1 per step and copy, 2 per convolution kernel launch, 3 both."""
         self._check(_lib.acc_set_profiling(self._h, int(level)))
@@ -366,6 +419,14 @@ class Context:
         n = self._check(_lib.acc_get_kernel_profile(self._h, arr, 16))
         return [dict(name=arr[i].name.decode(), launches=arr[i].launches, ms=arr[i].ms, flops=arr[i].flops)
                 for i in range(n)]
+
+    def launch_profile(self) -> list:
+        """One dict per convolution-kernel launch of the last step profiled at level 2 or 3."""
+        n = self._check(_lib.acc_get_launch_profile(self._h, None, 0))
+        arr = (acc_launch_profile * max(n, 1))()
+        n = self._check(_lib.acc_get_launch_profile(self._h, arr, n))
+        return [dict(step=arr[i].step, layer=arr[i].layer, role=("fwd", "dgrad", "wgrad")[arr[i].role],
+                     variant=arr[i].variant, ms=arr[i].ms, flops=arr[i].flops) for i in range(n)]
 
     def step_times_ms(self) -> np.ndarray:
         n = self.step_count()

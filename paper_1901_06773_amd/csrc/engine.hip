@@ -66,7 +66,7 @@ struct acc_ctx {
   bool profiling = false;
   bool kernel_profiling = false;
   bool calibrating = false;     // input batch is synthesised on the device
-  struct KProbe { int variant; double flops; hipEvent_t a, b; };
+  struct KProbe { int variant; double flops; hipEvent_t a, b; int step, role; double ms; };
   std::vector<KProbe> kprobes;  // one per convolution kernel launch of the last profiled step
   size_t kprobes_used = 0;
   hipEvent_t empty_pair[2 * 9] = {};  // event pairs with nothing between them: what a probe itself costs
@@ -76,7 +76,15 @@ struct acc_ctx {
   std::vector<double> step_ms;
   std::vector<size_t> cur_off;  // per tensor, while executing
   acc_stats stats{};
-  float* h_loss = nullptr;      // pinned scalar
+  float* h_loss = nullptr;      // pinned: [0] loss, then (as 64-bit words 1..2) what the poison scan found
+  // verification switches (acc_set_debug) and parity hooks (acc_capture_output)
+  int debug_flags = 0;
+  struct Capture { int tensor; void* dst; size_t cap; };
+  std::vector<std::vector<Capture>> capture_at;   // per forward step: outputs to copy out after it
+  std::vector<std::vector<Capture>> inject_at;    // per forward step: outputs to overwrite after it (dst = source)
+  struct Block { size_t off, bytes; };
+  std::vector<std::vector<Block>> poison_after_step;   // per step: blocks released once it has run
+  std::vector<Block> poison_after_d2h;                 // per offload: the block its map leaves behind
 
   int fail(int code, const std::string& what) { err = what; return code; }
   int hipfail(hipError_t e, const char* what) {
@@ -84,16 +92,19 @@ struct acc_ctx {
     return ACC_EHIP;
   }
   // hands out an event pair for one kernel launch (kernel-level profiling only)
-  LaunchProbe* next_probe(LaunchProbe* lp, double flops) {
+  LaunchProbe* next_probe(LaunchProbe* lp, double flops, int step, int role) {
     if (!kernel_profiling) return nullptr;
     if (kprobes_used == kprobes.size()) {
-      KProbe kp{-1, 0.0, nullptr, nullptr};
+      KProbe kp{-1, 0.0, nullptr, nullptr, -1, 0, 0.0};
       if (hipEventCreate(&kp.a) != hipSuccess || hipEventCreate(&kp.b) != hipSuccess) return nullptr;
       kprobes.push_back(kp);
     }
     KProbe& kp = kprobes[kprobes_used++];
     kp.flops = flops;
     kp.variant = -1;
+    kp.step = step;
+    kp.role = role;
+    kp.ms = 0.0;
     lp->before = kp.a;
     lp->after = kp.b;
     return lp;
@@ -388,6 +399,22 @@ int install_plan(acc_ctx* c, Plan&& p, acc_plan_summary* out, double t0) {
   c->plan = std::move(p);
   c->obs_start.clear(); c->obs_end.clear();   // observations belong to the plan they ran under
   c->stats = acc_stats{};
+  {
+    // Where the plan releases memory (for the poison mode): a tensor's block is free once the
+    // last step that touches it has run; the block a swapped map is produced in is free once
+    // its offload has finished, and the block it comes back into after its last use.
+    const Plan& P = c->plan;
+    const int ns = (int)c->g.steps.size();
+    c->poison_after_step.assign(ns, {});
+    c->poison_after_d2h.assign(P.n_d2h, {0, 0});
+    for (int t = 0; t < (int)c->g.tensors.size(); ++t) {
+      const Tensor& T = c->g.tensors[t];
+      if (!P.tbytes[t] || T.last < 0 || T.last >= ns) continue;
+      c->poison_after_step[T.last].push_back({P.swapped[t] ? P.off2[t] : P.off1[t], P.tbytes[t]});
+    }
+    for (const Instr& in : P.instrs)
+      if (in.op == I_OFFLOAD) c->poison_after_d2h[in.seq] = {P.off1[in.arg], P.tbytes[in.arg]};
+  }
   if (out) {
     const Plan& P = c->plan;
     std::memset(out, 0, sizeof *out);
@@ -565,6 +592,42 @@ namespace {
 
 hipError_t fill_pseudo_input(acc_ctx* c, float* p, size_t count);
 
+// Poison patterns of the verification mode: a word that is a NaN as fp32, as two bf16 values
+// and (two of them) as a double, so that a kernel that reads memory nobody has written for
+// it yields NaN.  kNeverWritten marks the dynamic region before the iteration, kReleased a
+// block whose tensor has had its last use.
+constexpr uint32_t kNeverWritten = 0x7FF87FF8u, kReleased = 0x7FF97FF9u;
+
+__global__ void fill_word_kernel(uint32_t* __restrict__ p, size_t words, uint32_t v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// out[0] = 1 + index of the last word that differs from `untouched` (0 if none), out[1] = how
+// many words differ.  out must be zero before the launch.
+__global__ void written_extent_kernel(const uint32_t* __restrict__ p, size_t words, uint32_t untouched,
+                                      unsigned long long* __restrict__ out) {
+  unsigned long long hi = 0, cnt = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
+    if (p[i] != untouched) { hi = i + 1; ++cnt; }
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long h2 = __shfl_xor(hi, o), c2 = __shfl_xor(cnt, o);
+    hi = h2 > hi ? h2 : hi;
+    cnt += c2;
+  }
+  if ((threadIdx.x & 63) == 0 && cnt) {
+    atomicMax(out, hi);
+    atomicAdd(out + 1, cnt);
+  }
+}
+
+hipError_t fill_words(void* p, size_t bytes, uint32_t v, hipStream_t st) {
+  if (!bytes) return hipSuccess;
+  const size_t words = bytes / 4;
+  const size_t blocks = std::min<size_t>((words + 255) / 256, 256 * 16);
+  hipLaunchKernelGGL(fill_word_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t*)p, words, v);
+  return hipGetLastError();
+}
+
 // launches the kernels of one step on the compute stream
 // Adds up the parts of the last conv weight gradient on the stream it ran on; the compute
 // stream then waits for that stream (the update reads the result).
@@ -594,14 +657,14 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
                    : dt == ACC_BF16 ? (const void*)(c->d_params16 + g.params[s.layer].offset) : (const void*)w;
   auto igemm = [&](const ConvGeom& cg, double flops) {
     LaunchProbe lp;
-    LaunchProbe* pp = c->next_probe(&lp, flops);
+    LaunchProbe* pp = c->next_probe(&lp, flops, j, s.phase == 1 ? 1 : 0);
     const hipError_t e = conv_igemm(cg, st, pp);
     if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
     return e;
   };
   auto wgrad = [&](const WgradGeom& wg, double flops, ReduceJob* deferred, hipStream_t on = nullptr) {
     LaunchProbe lp;
-    LaunchProbe* pp = c->next_probe(&lp, flops);
+    LaunchProbe* pp = c->next_probe(&lp, flops, j, 2);
     const hipError_t e = conv_wgrad(wg, on ? on : st, pp, deferred);
     if (pp) c->kprobes[c->kprobes_used - 1].variant = lp.variant;
     return e;
@@ -856,6 +919,27 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
       for (size_t i = 0; i < nc; ++i) { HIPCHK(c, hipEventCreate(&c->prof_copy_a[i])); HIPCHK(c, hipEventCreate(&c->prof_copy_b[i])); }
     }
   }
+  if (!c->calibrating) {
+    // a label indexes the logits: one outside [0, classes) must not reach the loss kernel
+    for (int i = 0; i < P.k; ++i)
+      if (labels[i] < 0 || labels[i] >= g.classes) return c->fail(ACC_EINVAL, "label outside [0, classes)");
+  }
+  for (const auto* table : {&c->capture_at, &c->inject_at})
+    for (const auto& list : *table)
+      for (const acc_ctx::Capture& cp : list)
+        if (cp.cap < (size_t)P.k * g.tensors[cp.tensor].bytes_per_image)
+          return c->fail(ACC_EINVAL, "a capture / injection buffer is smaller than the layer's output at this minibatch");
+  const bool poison = (c->debug_flags & ACC_DEBUG_POISON) != 0;
+  unsigned long long* d_scan = (unsigned long long*)((char*)c->d_loss + 16);
+  if (poison) {
+    // nothing in the dynamic region or in the host arena is valid before the iteration
+    hipError_t e = fill_words(c->dyn, c->dyn_cap, kNeverWritten, c->s_c);
+    if (e == hipSuccess) e = fill_zero((float*)d_scan, 4, c->s_c);
+    if (e != hipSuccess) return c->hipfail(e, "poison fill");
+    HIPCHK(c, hipStreamSynchronize(c->s_c));
+    uint32_t* hw = (uint32_t*)c->res.host;
+    std::fill(hw, hw + P.host_bytes / 4, kNeverWritten);
+  }
   uint64_t bytes_out = 0, bytes_in = 0;
   c->bn_ready_slabs.assign(ns, 0);
   std::fill(c->wgrad_in_flight.begin(), c->wgrad_in_flight.end(), 0);   // (a failed step may have left some set)
@@ -918,6 +1002,19 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
           return c->hipfail(e, buf);
         }
         if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_b[in.arg], c->s_c));
+        if (in.arg < (int)c->capture_at.size())
+          for (const acc_ctx::Capture& cp : c->capture_at[in.arg])
+            HIPCHK(c, hipMemcpyAsync(cp.dst, c->dyn + c->cur_off[cp.tensor], (size_t)P.k * g.tensors[cp.tensor].bytes_per_image,
+                                     hipMemcpyDeviceToHost, c->s_c));
+        if (in.arg < (int)c->inject_at.size())
+          for (const acc_ctx::Capture& ip : c->inject_at[in.arg])
+            HIPCHK(c, hipMemcpyAsync(c->dyn + c->cur_off[ip.tensor], ip.dst, (size_t)P.k * g.tensors[ip.tensor].bytes_per_image,
+                                     hipMemcpyHostToDevice, c->s_c));
+        if (poison)
+          for (const acc_ctx::Block& b : c->poison_after_step[in.arg]) {
+            const hipError_t ep = fill_words(c->dyn + b.off, b.bytes, kReleased, c->s_c);
+            if (ep != hipSuccess) return c->hipfail(ep, "poison fill");
+          }
         if (in.record) HIPCHK(c, hipEventRecord(c->ev_step[in.arg], c->s_c));
         if (++n_compute % kStepWindow == 0) HIPCHK(c, hipEventRecord(c->ev_window[n_compute / kStepWindow - 1], c->s_c));
         break;
@@ -928,6 +1025,11 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
         HIPCHK(c, hipMemcpyAsync((char*)c->res.host + P.host_off[in.arg], c->dyn + P.off1[in.arg], P.tbytes[in.arg],
                                  hipMemcpyDeviceToHost, c->s_o));
         if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_copy_b[in.seq], c->s_o));
+        if (poison) {
+          const acc_ctx::Block& b = c->poison_after_d2h[in.seq];
+          const hipError_t ep = fill_words(c->dyn + b.off, b.bytes, kReleased, c->s_o);
+          if (ep != hipSuccess) return c->hipfail(ep, "poison fill");
+        }
         HIPCHK(c, hipEventRecord(c->ev_d2h[in.seq], c->s_o));
         bytes_out += P.tbytes[in.arg];
         break;
@@ -957,7 +1059,25 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   if (loss_out) *loss_out = *c->h_loss;
   c->stats.step_ms = t_done - t_host0;
   c->stats.host_issue_ms = t_issued - t_host0;
-  c->stats.peak_pool_bytes = g.static_bytes() + P.dyn_peak;
+  // without the poison mode: where the plan's highest block ends (an offset, not a sum of sizes)
+  c->stats.peak_pool_bytes = g.static_bytes() + P.dyn_top;
+  c->stats.touched_pool_bytes = 0;
+  c->stats.peak_is_measured = 0;
+  if (poison) {
+    // the highest byte of the pool that anything wrote during the iteration, and how many bytes
+    // were written at all: every word that no longer holds the pattern of before the iteration
+    hipLaunchKernelGGL(written_extent_kernel, dim3(256 * 8), dim3(256), 0, c->s_c, (const uint32_t*)c->dyn,
+                       c->dyn_cap / 4, kNeverWritten, d_scan);
+    HIPCHK(c, hipGetLastError());
+    unsigned long long* h_scan = (unsigned long long*)((char*)c->h_loss + 16);
+    HIPCHK(c, hipMemcpyAsync(h_scan, d_scan, 16, hipMemcpyDeviceToHost, c->s_c));
+    HIPCHK(c, hipStreamSynchronize(c->s_c));
+    c->stats.peak_pool_bytes = g.static_bytes() + (uint64_t)h_scan[0] * 4;
+    c->stats.touched_pool_bytes = g.static_bytes() + (uint64_t)h_scan[1] * 4;
+    c->stats.peak_is_measured = 1;
+    if (c->stats.peak_pool_bytes > P.budget)
+      return c->fail(ACC_EPOOL, "the iteration wrote beyond the budget (found by the poison scan)");
+  }
   c->stats.bytes_out = bytes_out;
   c->stats.bytes_in = bytes_in;
   c->stats.steps_run += 1;
@@ -969,11 +1089,12 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
     std::sort(gaps, gaps + 9);
     c->probe_overhead_ms = gaps[4];
     for (size_t i = 0; i < c->kprobes_used; ++i) {
-      const acc_ctx::KProbe& kp = c->kprobes[i];
+      acc_ctx::KProbe& kp = c->kprobes[i];
       if (kp.variant < 0 || kp.variant >= V_COUNT) continue;
       float ms = 0;
       HIPCHK(c, hipEventElapsedTime(&ms, kp.a, kp.b));
-      c->k_ms[kp.variant] += std::max(0.0, (double)ms - c->probe_overhead_ms);
+      kp.ms = std::max(0.0, (double)ms - c->probe_overhead_ms);
+      c->k_ms[kp.variant] += kp.ms;
       c->k_flops[kp.variant] += kp.flops;
       c->k_launches[kp.variant] += 1;
     }
@@ -1037,6 +1158,41 @@ extern "C" int acc_get_stats(acc_ctx* c, acc_stats* out) {
   return ACC_OK;
 }
 
+extern "C" int acc_set_debug(acc_ctx* c, int flags) {
+  if (!c) return ACC_EINVAL;
+  if (flags & ~ACC_DEBUG_POISON) return c->fail(ACC_EINVAL, "unknown debug flag");
+  if (flags && !c->have_res) return c->fail(ACC_ESTATE, "context has no device resources");
+  c->debug_flags = flags;
+  return ACC_OK;
+}
+
+namespace {
+int register_hook(acc_ctx* c, std::vector<std::vector<acc_ctx::Capture>>* table, int layer, void* host, size_t bytes) {
+  if (!c) return ACC_EINVAL;
+  if (!c->have_res) return c->fail(ACC_ESTATE, "context has no device resources");
+  const int ns = (int)c->g.steps.size();
+  if (layer == -1 && !host) { table->clear(); return ACC_OK; }
+  if (layer < 0 || layer >= (int)c->g.layers.size()) return c->fail(ACC_EINVAL, "bad layer");
+  const int t = c->g.act_of_layer[layer];
+  if (t < 0) return c->fail(ACC_EINVAL, "the output of this layer is not stored (fused into the next layer's step)");
+  const int j = c->g.tensors[t].producer;
+  if (j < 0 || j >= c->g.n_fwd) return c->fail(ACC_EINVAL, "the output of this layer has no forward step");
+  if ((int)table->size() != ns) table->assign(ns, {});
+  auto& list = (*table)[j];
+  list.erase(std::remove_if(list.begin(), list.end(), [&](const acc_ctx::Capture& cp) { return cp.tensor == t; }), list.end());
+  if (host) list.push_back({t, host, bytes});
+  return ACC_OK;
+}
+}  // namespace
+
+extern "C" int acc_capture_output(acc_ctx* c, int layer, void* host_dst, size_t bytes) {
+  return register_hook(c, c ? &c->capture_at : nullptr, layer, host_dst, bytes);
+}
+
+extern "C" int acc_inject_output(acc_ctx* c, int layer, const void* host_src, size_t bytes) {
+  return register_hook(c, c ? &c->inject_at : nullptr, layer, const_cast<void*>(host_src), bytes);
+}
+
 extern "C" int acc_set_wgrad_overlap(acc_ctx* c, int on) {
   if (!c) return ACC_EINVAL;
   c->wgrad_overlap = on != 0;
@@ -1060,6 +1216,25 @@ extern "C" int acc_get_kernel_profile(acc_ctx* c, acc_kernel_profile* out, int m
     out[n].launches = (int32_t)c->k_launches[v];
     out[n].ms = c->k_ms[v];
     out[n].flops = c->k_flops[v];
+    ++n;
+  }
+  return n;
+}
+
+extern "C" int acc_get_launch_profile(acc_ctx* c, acc_launch_profile* out, int max_entries) {
+  if (!c || max_entries < 0 || (!out && max_entries > 0)) return ACC_EINVAL;
+  int n = 0;
+  for (size_t i = 0; i < c->kprobes_used; ++i) {
+    const acc_ctx::KProbe& kp = c->kprobes[i];
+    if (kp.variant < 0 || kp.variant >= V_COUNT) continue;
+    if (n < max_entries) {
+      out[n].step = kp.step;
+      out[n].layer = kp.step >= 0 ? c->g.steps[kp.step].layer : -1;
+      out[n].role = kp.role;
+      out[n].variant = kp.variant;
+      out[n].ms = kp.ms;
+      out[n].flops = kp.flops;
+    }
     ++n;
   }
   return n;

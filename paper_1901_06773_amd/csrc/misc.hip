@@ -382,7 +382,9 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(const T* __restrict
   se = block_sum(se, sh);
   const float lse = mx + logf(se);
   const int lab = labels[i];
-  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lse - Elem<T>::load(zi + lab);
+  // a label outside [0, classes) reads nothing: the row's loss is NaN and its gradient has no one-hot term
+  const bool lab_ok = (unsigned)lab < (unsigned)classes;
+  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lab_ok ? lse - Elem<T>::load(zi + lab) : NAN;
   if (dz) {
     const float inv_n = 1.f / (float)n;
     for (int j = threadIdx.x; j < classes; j += THREADS)

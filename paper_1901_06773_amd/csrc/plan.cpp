@@ -237,6 +237,7 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
     live += P.tbytes[t];
     if (live > P.dyn_peak) P.dyn_peak = live;
     if (!top && off + P.tbytes[t] > P.dyn_extent) P.dyn_extent = off + P.tbytes[t];
+    if (off + P.tbytes[t] > P.dyn_top) P.dyn_top = off + P.tbytes[t];
     return true;
   };
   auto long_lived = [&](int t) { return g.tensors[t].is_map && !P.swapped[t]; };
@@ -261,12 +262,12 @@ static bool build_plan_once(const Graph& g, int k, size_t budget, const std::vec
   auto alloc_step = [&](int j, bool forced) -> bool {
     const Step& s = g.steps[j];
     Arena snap = arena;
-    const size_t live0 = live, peak0 = P.dyn_peak, ext0 = P.dyn_extent;
+    const size_t live0 = live, peak0 = P.dyn_peak, ext0 = P.dyn_extent, top0 = P.dyn_top;
     const size_t n_instr0 = P.instrs.size();
     const int n_h2d0 = P.n_h2d;
     std::vector<std::pair<int, int>> undo;   // tensor, previous state
     auto rollback = [&]() {
-      arena = snap; live = live0; P.dyn_peak = peak0; P.dyn_extent = ext0;
+      arena = snap; live = live0; P.dyn_peak = peak0; P.dyn_extent = ext0; P.dyn_top = top0;
       P.instrs.resize(n_instr0); P.n_h2d = n_h2d0;
       for (auto& u : undo) {
         st[u.first] = u.second;

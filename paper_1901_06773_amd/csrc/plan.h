@@ -56,6 +56,7 @@ struct Plan {
   int n_d2h = 0, n_h2d = 0;
   size_t dyn_peak = 0;                     // high-water sum of live dynamic bytes
   size_t dyn_extent = 0;                   // highest pool offset + size used by bottom-up blocks
+  size_t dyn_top = 0;                      // highest pool offset + size of any block (top-down ones included)
   size_t host_bytes = 0;
   size_t bytes_swapped = 0;
   int n_swapped = 0;
