@@ -115,6 +115,9 @@ def main():
         sys.exit(1)
 
     torch.cuda.set_device(0)
+    # pinned staging for the headline's batches, taken before the large arena (pinned memory is capped per process)
+    k_stage = noswap_max_k if args.k == "auto" else int(args.k)
+    pin_stage = torch.empty((2, max(k_stage, 1)) + chw, dtype=torch.float32).pin_memory()
     t0 = time.time()
     ctx = B.Context(net.as_array(), chw, pool_bytes=budget, host_bytes=host_need + (64 << 20), dtype=dtype)
     ctx.set_weights(S.init_params(net))
@@ -145,7 +148,12 @@ def main():
         if key not in cache:
             img, lab = S.make_batch(net, k, step)
             t = torch.from_numpy(img)
-            cache[key] = (t.pin_memory() if pinned else t.cuda(), lab)
+            if pinned:
+                slot = pin_stage[step % 2][:k]
+                slot.copy_(t)
+                cache[key] = (slot, lab)
+            else:
+                cache[key] = (t.cuda(), lab)
         return cache[key]
 
     def forget(k):
@@ -184,10 +192,12 @@ def main():
     value = k / sec
     stats = ctx.stats()
     # the same with the batch in pinned host memory: its copy to the device is the first layer's prefetch
-    sec_host, _ = run(ctx, k, args.steps, 1, pinned=True)
-    pcie_inclusive = dict(images_per_s=k / sec_host, ms_per_step=sec_host * 1e3,
-                          note="same plan and steps, the batch handed over in pinned host memory "
-                               f"({k * chw[0] * chw[1] * chw[2] * 4 / 1e6:.1f} MB per step over the host link, on the swap-in stream)")
+    pcie_inclusive = None
+    if k <= pin_stage.shape[1]:
+        sec_host, _ = run(ctx, k, args.steps, 1, pinned=True)
+        pcie_inclusive = dict(images_per_s=k / sec_host, ms_per_step=sec_host * 1e3,
+                              note="same plan and steps, the batch handed over in pinned host memory "
+                                   f"({k * chw[0] * chw[1] * chw[2] * 4 / 1e6:.1f} MB per step over the host link, on the swap-in stream)")
 
     # ---- roofline of the dominant kernel: events directly around every convolution launch,
     # and per-step / per-copy times.  The library refuses event timing for plans that swap
