@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaccudnn.so")
 OBJ = os.path.join(HERE, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["conv_igemm.hip", "conv_wgrad.hip", "bn.hip", "misc.hip", "graph.cpp", "plan.cpp",
+SOURCES = ["conv_igemm.hip", "conv_igemm_bf16.hip", "conv_wgrad.hip", "bn.hip", "misc.hip", "graph.cpp", "plan.cpp",
            "engine.hip", "ops_api.cpp", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

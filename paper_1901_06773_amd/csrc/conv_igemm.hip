@@ -22,6 +22,7 @@
 // a ResNet-152 step at minibatch 41 when used from three tiles per CU on, 97.5 from six on.
 #include "kernels.h"
 #include "dtype.h"
+#include "igemm_side.h"
 
 namespace acc {
 namespace {
@@ -127,51 +128,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   __shared__ __attribute__((aligned(1024))) float Bs[2 * BN * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
-    const ReduceJob& j = g.side;
-    const int reduce_blocks = (int)((j.count + 1023) / 1024);
-    int id = (int)blockIdx.x - main_grid;
-    if (id >= reduce_blocks) {
-      // side job: one 32 x 32 (co, ci) block of one tap of a flipped, transposed filter
-      const FlipJob& f = g.flip;
-      id -= reduce_blocks;
-      const int bx = (f.cin + 31) / 32, by = (f.cout + 31) / 32;
-      const int tap = id / (bx * by), rem = id - tap * (bx * by);
-      if (tap >= f.r * f.s) return;
-      const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
-      const int kr = f.r - 1 - tap / f.s, kt = f.s - 1 - tap % f.s;
-      const int src_tap = kr * f.s + kt;
-      T (*tile)[33] = reinterpret_cast<T (*)[33]>(As);
-      const T* fw = static_cast<const T*>(f.w);
-      T* fwt = static_cast<T*>(f.wt);
-      const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-      for (int i = ty; i < 32; i += 8) {
-        const int co = co0f + i, ci = ci0f + tx;
-        tile[i][tx] = (co < f.cout && ci < f.cin) ? fw[((size_t)co * f.r * f.s + src_tap) * f.cin + ci] : T(0);
-      }
-      __syncthreads();
-      for (int i = ty; i < 32; i += 8) {
-        const int ci = ci0f + i, co = co0f + tx;
-        if (ci < f.cin && co < f.cout) fwt[((size_t)ci * f.r * f.s + tap) * f.cout + co] = tile[tx][i];
-      }
-      return;
-    }
-    // side job: 1024 elements of a weight gradient, parts added in their fixed order
-    const size_t i4 = ((size_t)id * 256 + threadIdx.x) * 4;
-    if (i4 >= j.count) return;
-    if (i4 + 4 <= j.count && (j.count & 3) == 0) {
-      float4 sum = *reinterpret_cast<const float4*>(j.part + i4);
-      for (int k = 1; k < j.splits; ++k) {
-        const float4 v = *reinterpret_cast<const float4*>(j.part + (size_t)k * j.count + i4);
-        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
-      }
-      *reinterpret_cast<float4*>(j.dw + i4) = sum;
-    } else {
-      for (size_t i = i4; i < j.count && i < i4 + 4; ++i) {
-        float sum = j.part[i];
-        for (int k = 1; k < j.splits; ++k) sum += j.part[(size_t)k * j.count + i];
-        j.dw[i] = sum;
-      }
-    }
+    igemm_side_jobs<T>(g, (int)blockIdx.x - main_grid, As);
     return;
   }
 
@@ -613,7 +570,8 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
 
 const char* conv_variant_name(int v) {
   static const char* names[V_COUNT] = {"igemm_kernel<fast>", "igemm_kernel<generic>", "wgrad_kernel<fast>",
-                                       "wgrad_kernel<generic>", "igemm_kernel<direct>", "wgrad_kernel<direct>"};
+                                       "wgrad_kernel<generic>", "igemm_kernel<direct>", "wgrad_kernel<direct>",
+                                       "wgrad_bf16_kernel", "igemm_bf16_kernel"};
   return (v >= 0 && v < V_COUNT) ? names[v] : "?";
 }
 
@@ -634,6 +592,11 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe) {
   if (M >= (1L << 31) || K >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31))
     return hipErrorInvalidValue;
   if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
+  if ((g.bias || g.relu) && (g.accumulate || g.stats || g.bnb.sums)) return hipErrorInvalidValue;
+  if (conv_igemm_bf16_takes(g, M, K)) {    // bf16 storage, large layers: 128 x 128 tiles
+    probe->variant = V_IGEMM_BF16;
+    return conv_igemm_bf16(g, (int)M, (int)K, st, probe);
+  }
   const long es = (long)dt_size(g.dtype);
   // The direct loader addresses both operands through buffer descriptors: 32-bit ranges, the
   // last bytes kept free for the offset that stands for "outside"; 16-byte loads want aligned

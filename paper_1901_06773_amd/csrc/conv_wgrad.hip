@@ -71,6 +71,55 @@ __device__ __forceinline__ int gather_pixel(const WgradGeom& g, int m, int kr, i
   return (img * g.h + iy) * g.wd + ix;
 }
 
+// Side jobs of a weight-gradient launch (workgroups appended behind the tiles): first the
+// blocks that add up 1024 elements each of an earlier weight gradient's parts, in their fixed
+// order; then the blocks that write one 32 x 32 (co, ci) block each of one tap of the flipped,
+// transposed filter.  scratch: at least 32 x 33 elements of LDS.
+template <class T>
+__device__ __forceinline__ void side_jobs(const WgradGeom& g, int id, float* scratch) {
+  const ReduceJob& rj = g.side;
+  const int reduce_blocks = (int)((rj.count + 1023) / 1024);
+  if (id < reduce_blocks) {
+    const size_t i4 = ((size_t)id * 256 + threadIdx.x) * 4;
+    if (i4 >= rj.count) return;
+    if (i4 + 4 <= rj.count && (rj.count & 3) == 0) {
+      float4 sum = *reinterpret_cast<const float4*>(rj.part + i4);
+      for (int k = 1; k < rj.splits; ++k) {
+        const float4 v = *reinterpret_cast<const float4*>(rj.part + (size_t)k * rj.count + i4);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+      }
+      *reinterpret_cast<float4*>(rj.dw + i4) = sum;
+    } else {
+      for (size_t i = i4; i < rj.count && i < i4 + 4; ++i) {
+        float sum = rj.part[i];
+        for (int k = 1; k < rj.splits; ++k) sum += rj.part[(size_t)k * rj.count + i];
+        rj.dw[i] = sum;
+      }
+    }
+    return;
+  }
+  id -= reduce_blocks;
+  if (!g.flip_wt) return;
+  const int bx = (g.cin + 31) / 32, by = (g.cout + 31) / 32;
+  const int tap = id / (bx * by), rem = id - tap * (bx * by);
+  const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
+  const int kr = g.r - 1 - tap / g.s, kt = g.s - 1 - tap % g.s;
+  const int src_tap = kr * g.s + kt;
+  T (*tile)[33] = reinterpret_cast<T (*)[33]>(scratch);
+  const T* fw = static_cast<const T*>(g.flip_w);
+  T* fwt = static_cast<T*>(g.flip_wt);
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int i = ty; i < 32; i += 8) {
+    const int co = co0f + i, ci = ci0f + tx;
+    tile[i][tx] = (co < g.cout && ci < g.cin) ? fw[((size_t)co * g.r * g.s + src_tap) * g.cin + ci] : T(0);
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int ci = ci0f + i, co = co0f + tx;
+    if (ci < g.cin && co < g.cout) fwt[((size_t)ci * g.r * g.s + tap) * g.cout + co] = tile[tx][i];
+  }
+}
+
 // L_FAST, L_DIRECT: cin % 64 == 0 (a tile's columns lie inside one tap), cout % 4 == 0, byte
 // offsets below 2^32.  L_DIRECT (fp32 storage only: bf16 operands are widened on their way
 // into LDS, which needs the registers) moves the chunks from global memory straight into LDS
@@ -91,50 +140,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
   __shared__ __attribute__((aligned(256))) float Bs[2 * BKM * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
-    int id = blockIdx.x - main_grid;
-    const ReduceJob& rj = g.side;
-    const int reduce_blocks = (int)((rj.count + 1023) / 1024);
-    if (id < reduce_blocks) {
-      // side job: 1024 elements of an earlier weight gradient, parts added in their fixed order
-      const size_t i4 = ((size_t)id * 256 + threadIdx.x) * 4;
-      if (i4 >= rj.count) return;
-      if (i4 + 4 <= rj.count && (rj.count & 3) == 0) {
-        float4 sum = *reinterpret_cast<const float4*>(rj.part + i4);
-        for (int k = 1; k < rj.splits; ++k) {
-          const float4 v = *reinterpret_cast<const float4*>(rj.part + (size_t)k * rj.count + i4);
-          sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
-        }
-        *reinterpret_cast<float4*>(rj.dw + i4) = sum;
-      } else {
-        for (size_t i = i4; i < rj.count && i < i4 + 4; ++i) {
-          float sum = rj.part[i];
-          for (int k = 1; k < rj.splits; ++k) sum += rj.part[(size_t)k * rj.count + i];
-          rj.dw[i] = sum;
-        }
-      }
-      return;
-    }
-    id -= reduce_blocks;
-    if (!g.flip_wt) return;
-    // side job: one 32 x 32 (co, ci) block of one tap of the flipped, transposed filter
-    const int bx = (g.cin + 31) / 32, by = (g.cout + 31) / 32;
-    const int tap = id / (bx * by), rem = id - tap * (bx * by);
-    const int co0f = (rem / bx) * 32, ci0f = (rem - (rem / bx) * bx) * 32;
-    const int kr = g.r - 1 - tap / g.s, kt = g.s - 1 - tap % g.s;
-    const int src_tap = kr * g.s + kt;
-    T (*tile)[33] = reinterpret_cast<T (*)[33]>(As);
-    const T* fw = static_cast<const T*>(g.flip_w);
-    T* fwt = static_cast<T*>(g.flip_wt);
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int i = ty; i < 32; i += 8) {
-      const int co = co0f + i, ci = ci0f + tx;
-      tile[i][tx] = (co < g.cout && ci < g.cin) ? fw[((size_t)co * g.r * g.s + src_tap) * g.cin + ci] : T(0);
-    }
-    __syncthreads();
-    for (int i = ty; i < 32; i += 8) {
-      const int ci = ci0f + i, co = co0f + tx;
-      if (ci < g.cin && co < g.cout) fwt[((size_t)ci * g.r * g.s + tap) * g.cout + co] = tile[tx][i];
-    }
+    side_jobs<T>(g, (int)blockIdx.x - main_grid, As);
     return;
   }
 
@@ -482,6 +488,191 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// bf16 storage on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16).  The instruction wants eight
+// consecutive values of the reduction index per lane; here that index is the minibatch position
+// m, and memory is contiguous along channels.  So every thread loads an 8 x 8 block (eight rows
+// of m, sixteen bytes = eight channels each), transposes it in registers (32 byte permutes) and
+// writes eight 16-byte vectors "channel c, rows m..m+7" into LDS, where a fragment read is one
+// ds_read_b128 per lane again.  A workgroup of 4 waves owns a 128 x 128 tile of dw, each wave
+// 64 x 64 (2 x 2 MFMA blocks: 16 MFMAs per 16 fragment reads and chunk of 64 rows), two LDS
+// stages of 32 KB, the global loads of the next chunk in flight during the MFMAs of this one.
+// Waves 0-1 stage dy, waves 2-3 gather x.  LDS layout per stage and operand: [8 row groups][128
+// channels] of 16 bytes, a channel's position inside its group of eight XORed with
+// (group >> 1) & 7: the eight vectors a thread writes with one instruction land on different
+// banks, and so do the 32 consecutive channels a half-wave reads.
+// Needs cin % 8 == 0 (the eight channels a thread stages lie inside one filter tap; the tap is the
+// thread's own, a tile's 128 columns may span several) and cout % 8 == 0.
+constexpr int WB_BM = 128, WB_BN = 128, WB_BK = 64;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ v16f mfma32x32x16bf(const v4u& a, const v4u& b, v16f c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+#else
+  return c;  // the host pass never runs this
+#endif
+}
+
+__device__ __forceinline__ int wb_slot(int kg, int ch) {   // 16-byte slot of (row group, channel) inside a stage
+  const int o = ch >> 3;
+  return kg * WB_BM + (o << 3) + ((ch & 7) ^ ((o >> 1) & 7));
+}
+
+__global__ __launch_bounds__(256) void wgrad_bf16_kernel(WgradGeom g, int Mrows, int J, int tiles_j, int tiles,
+                                                          int splits, int chunks_per_split, float* out,
+                                                          size_t split_stride, int main_grid) {
+  __shared__ __attribute__((aligned(1024))) v4u As[2 * 8 * WB_BM];
+  __shared__ __attribute__((aligned(1024))) v4u Bs[2 * 8 * WB_BN];
+  if ((int)blockIdx.x >= main_grid) {
+    side_jobs<bf16_t>(g, (int)blockIdx.x - main_grid, reinterpret_cast<float*>(As));
+    return;
+  }
+#if defined(__HIP_DEVICE_COMPILE__)
+  const int per_xcd = main_grid >> 3;
+  const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (work >= tiles * splits) return;
+  const int split = work / tiles, tile = work - split * tiles;
+  const int tile_co = tile / tiles_j, tile_j = tile - tile_co * tiles_j;
+  const int co0 = tile_co * WB_BM, j0 = tile_j * WB_BN;
+  const int chunk_lo = split * chunks_per_split;
+  const int n_chunks_all = (Mrows + WB_BK - 1) / WB_BK;
+  const int n_chunks = min(chunk_lo + chunks_per_split, n_chunks_all) - chunk_lo;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+
+  v16f acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  // ---- staging role of the thread: operand (uniform per wave), row group, group of eight channels
+  const bool role_b = tid >= 128;
+  const int u = tid & 127, oct = u & 15, kg = u >> 4;
+  const int jt = j0 + oct * 8;                 // first of the thread's eight columns of dw
+  const bool b_col_ok = jt < J;
+  const int tap = (b_col_ok ? jt : 0) / g.cin, ci0 = (b_col_ok ? jt : 0) - tap * g.cin;
+  const int kr = tap / g.s, kt = tap - kr * g.s;
+  const bool plain = g.r == 1 && g.s == 1 && g.stride == 1 && g.pad == 0;
+  constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;   // beyond the descriptor's range: reads as zero
+  const bool a_col_ok = co0 + oct * 8 < g.cout;
+  const uint32_t a_lane = (uint32_t)(co0 + oct * 8) * 2u, b_lane = (uint32_t)ci0 * 2u;
+  __amdgpu_buffer_rsrc_t rs = role_b
+      ? __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.x), 0, (int)(uint32_t)((size_t)g.n_img * g.h * g.wd * g.cin * 2), 0x00020000)
+      : __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(g.dy), 0, (int)(uint32_t)((size_t)Mrows * g.cout * 2), 0x00020000);
+  v4u R[8];
+  auto load = [&](int kc) {
+    const int m0 = (chunk_lo + kc) * WB_BK + kg * 8;
+    if (!role_b) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int m = m0 + r;
+        const uint32_t voff = (m < Mrows && a_col_ok) ? (uint32_t)m * (uint32_t)(g.cout * 2) + a_lane : OUTSIDE;
+        R[r] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, 0, 0);
+      }
+    } else {
+      int p = 0, q = 0, org = 0;
+      if (!plain) {
+        const int pq = g.p * g.q;
+        const int mm = m0 < Mrows ? m0 : 0;
+        const int img = mm / pq, rem = mm - img * pq;
+        p = rem / g.q;
+        q = rem - p * g.q;
+        org = img * g.h * g.wd;
+      }
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int m = m0 + r;
+        int pix = m;
+        if (!plain) {
+          const int iy = p * g.stride + kr - g.pad, ix = q * g.stride + kt - g.pad;
+          pix = ((unsigned)iy < (unsigned)g.h && (unsigned)ix < (unsigned)g.wd) ? org + iy * g.wd + ix : -1;
+          if (++q == g.q) { q = 0; if (++p == g.p) { p = 0; org += g.h * g.wd; } }
+        }
+        const uint32_t voff = (m < Mrows && pix >= 0 && b_col_ok) ? (uint32_t)pix * (uint32_t)(g.cin * 2) + b_lane : OUTSIDE;
+        R[r] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, 0, 0);
+      }
+    }
+  };
+  // 8 x 8 transpose of 16-bit values: vector c = channel c of the thread's eight, rows 0..7
+  v4u* stage_base = (role_b ? Bs : As);
+  const int slot0 = kg * WB_BM + (oct << 3);
+  const int sw = (oct >> 1) & 7;
+  auto transpose_store = [&](int buf) {
+    v4u* dst = stage_base + buf * (8 * WB_BM) + slot0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      v4u v;
+      v.x = __builtin_amdgcn_perm(R[1][c >> 1], R[0][c >> 1], sel);
+      v.y = __builtin_amdgcn_perm(R[3][c >> 1], R[2][c >> 1], sel);
+      v.z = __builtin_amdgcn_perm(R[5][c >> 1], R[4][c >> 1], sel);
+      v.w = __builtin_amdgcn_perm(R[7][c >> 1], R[6][c >> 1], sel);
+      dst[c ^ sw] = v;
+    }
+  };
+  // fragment slots of the lane: rows of dw (channels of dy) wm0 + 32*bi + lane%32, columns
+  // (channels of x) wn0 + 32*bj + lane%32; row group 2*s + lane/32 in MFMA step s
+  int a_at[2], b_at[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    a_at[i] = wb_slot(lane >> 5, wm0 + 32 * i + (lane & 31));
+    b_at[i] = wb_slot(lane >> 5, wn0 + 32 * i + (lane & 31));
+  }
+  auto compute = [&](int buf) {
+    const v4u* as = As + buf * (8 * WB_BM);
+    const v4u* bs = Bs + buf * (8 * WB_BN);
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      v4u a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = as[a_at[i] + s4 * 2 * WB_BM];
+        b[i] = bs[b_at[i] + s4 * 2 * WB_BN];
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma32x32x16bf(a[i], b[j], acc[i][j]);
+    }
+  };
+  if (n_chunks > 0) {
+    load(0);
+    transpose_store(0);
+    __syncthreads();
+    for (int kc = 0; kc < n_chunks; ++kc) {
+      const bool more = kc + 1 < n_chunks;
+      if (more) load(kc + 1);
+      compute(kc & 1);
+      if (more) transpose_store((kc + 1) & 1);
+      __syncthreads();
+    }
+  }
+  float* dst = out + (size_t)split * split_stride;
+  (void)ci0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int jcol = j0 + wn0 + 32 * j + (lane & 31);
+      if (jcol >= J) continue;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = co0 + wm0 + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (co < g.cout) dst[(size_t)co * J + jcol] = acc[i][j][v];
+      }
+    }
+#else
+  (void)Bs; (void)&mfma32x32x16bf; (void)&wb_slot;
+#endif
+}
+
 // dw[i] = part[0][i] + part[1][i] + ... in that order
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* part, float* dw, size_t count,
                                                              int splits) {
@@ -522,9 +713,28 @@ struct WgradCfg {
 // register-staged loader's LDS allows; measured with the direct loader at minibatch 41:
 // 512 -> 86, 768 -> 96, 1024 -> 99, 1280 -> 88 TFLOP/s, and the larger part count of 1024
 // costs the reduction what it gains here), at least 8 chunks of 32 rows each.
-WgradCfg choose(long Mrows, int cin, int cout, int r, int s) {
+// bf16 storage on the bf16 matrix cores: channel counts the 128 x 128 tile of wgrad_bf16_kernel takes
+inline bool bf16_mfma_shape(int dtype, int cin, int cout) { return dtype == DT_BF16 && cin % 8 == 0 && cout % 8 == 0; }
+
+WgradCfg choose(long Mrows, int cin, int cout, int r, int s, int dtype) {
   WgradCfg c;
   const long J = (long)r * s * cin;
+  if (bf16_mfma_shape(dtype, cin, cout)) {
+    // 128 x 128 tiles, chunks of 64 rows; two workgroups per CU (64 KB of LDS each): one round of 512,
+    // at least four chunks per part
+    c.tiles_co = (cout + WB_BM - 1) / WB_BM;
+    c.tiles_j = (int)((J + WB_BN - 1) / WB_BN);
+    const long tiles = (long)c.tiles_co * c.tiles_j;
+    const long chunks = (Mrows + WB_BK - 1) / WB_BK;
+    long splits = 512 / tiles;
+    const long max_splits = chunks / 4 > 0 ? chunks / 4 : 1;
+    if (splits > max_splits) splits = max_splits;
+    if (splits > 1024) splits = 1024;
+    if (splits < 1) splits = 1;
+    c.chunks_per_split = (int)((chunks + splits - 1) / splits);
+    c.splits = (int)((chunks + c.chunks_per_split - 1) / c.chunks_per_split);
+    return c;
+  }
   c.tiles_co = (cout + BM - 1) / BM;
   c.tiles_j = (int)((J + BN - 1) / BN);
   const long tiles = (long)c.tiles_co * c.tiles_j;
@@ -541,8 +751,13 @@ WgradCfg choose(long Mrows, int cin, int cout, int r, int s) {
 
 }  // namespace
 
-size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s) {
-  const WgradCfg c = choose((long)n_img * p * q, cin, cout, r, s);
+size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s, int dtype) {
+  if (dtype < 0) {   // whichever storage type needs more
+    const size_t a = wgrad_workspace_bytes(n_img, p, q, cin, cout, r, s, DT_F32);
+    const size_t b = wgrad_workspace_bytes(n_img, p, q, cin, cout, r, s, DT_BF16);
+    return a > b ? a : b;
+  }
+  const WgradCfg c = choose((long)n_img * p * q, cin, cout, r, s, dtype);
   if (c.splits <= 1) return 0;
   return (size_t)c.splits * cout * r * s * cin * sizeof(float);
 }
@@ -566,11 +781,11 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
   const long J = (long)g.r * g.s * g.cin;
   if (Mrows >= (1L << 31) || (long)g.n_img * g.h * g.wd >= (1L << 31) || J * g.cout >= (1L << 31))
     return hipErrorInvalidValue;
-  const WgradCfg c = choose(Mrows, g.cin, g.cout, g.r, g.s);
+  if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
+  const WgradCfg c = choose(Mrows, g.cin, g.cout, g.r, g.s, g.dtype);
   if (c.splits > 1 && !g.workspace) return hipErrorInvalidValue;
   const long work = (long)c.tiles_co * c.tiles_j * c.splits;
   if (work > (1L << 30)) return hipErrorInvalidValue;
-  if (g.dtype != DT_F32 && g.dtype != DT_BF16) return hipErrorInvalidValue;
   const long es = (long)dt_size(g.dtype);
   const bool fast = (g.cout % 4 == 0) && (g.cin % 64 == 0) && Mrows * g.cout * es < (1L << 32) &&
                     (long)g.n_img * g.h * g.wd * g.cin * es < (1L << 32);
@@ -596,16 +811,25 @@ hipError_t conv_wgrad(const WgradGeom& g, hipStream_t st, LaunchProbe* probe, Re
 #define ACC_WGRAD_LAUNCH(F, T)                                                                             \
   hipLaunchKernelGGL((wgrad_kernel<F, T>), grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j, tiles, \
                      c.splits, c.chunks_per_split, out, count, main_grid)
+  // bf16 matrix cores: the shapes choose() cut into 128 x 128 tiles; byte offsets inside 32-bit buffer
+  // ranges (the last bytes stay free for the offset that stands for "outside"), 16-byte aligned operands
+  const bool mfma16 = bf16_mfma_shape(g.dtype, g.cin, g.cout);
+  if (mfma16 && !(Mrows * g.cout * es <= 0xFFFFFF00L && (long)g.n_img * g.h * g.wd * g.cin * es <= 0xFFFFFF00L &&
+                  (reinterpret_cast<uintptr_t>(g.x) & 15) == 0 && (reinterpret_cast<uintptr_t>(g.dy) & 15) == 0))
+    return hipErrorInvalidValue;   // (the split count, and with it the workspace, was sized for this kernel)
   if (g.dtype == DT_F32) {
     if (direct) ACC_WGRAD_LAUNCH(L_DIRECT, float);
     else if (fast) ACC_WGRAD_LAUNCH(L_FAST, float);
     else ACC_WGRAD_LAUNCH(L_GENERIC, float);
+  } else if (mfma16) {
+    hipLaunchKernelGGL(wgrad_bf16_kernel, grid, dim3(256), 0, st, g, (int)Mrows, (int)J, c.tiles_j, tiles, c.splits,
+                       c.chunks_per_split, out, count, main_grid);
   } else {
     if (fast) ACC_WGRAD_LAUNCH(L_FAST, bf16_t); else ACC_WGRAD_LAUNCH(L_GENERIC, bf16_t);
   }
 #undef ACC_WGRAD_LAUNCH
   if (probe && probe->after) (void)hipEventRecord(probe->after, st);
-  if (probe) probe->variant = direct ? V_WGRAD_DIRECT : fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
+  if (probe) probe->variant = mfma16 ? V_WGRAD_BF16 : direct ? V_WGRAD_DIRECT : fast ? V_WGRAD_FAST : V_WGRAD_GENERIC;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (c.splits > 1) {

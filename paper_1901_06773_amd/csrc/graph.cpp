@@ -43,11 +43,11 @@ size_t Graph::bytes(int t, int k) const {
   if (T.wgrad_layer >= 0) {
     const acc_layer& l = layers[T.wgrad_layer];
     if (l.kind == ACC_FC) {
-      b = wgrad_workspace_bytes(k, 1, 1, l.cin, l.cout, 1, 1);
+      b = wgrad_workspace_bytes(k, 1, 1, l.cin, l.cout, 1, 1, dtype);
     } else {
       int h, w, ho, wo;
       conv_dims(T.wgrad_layer, &h, &w, &ho, &wo);
-      b = wgrad_workspace_bytes(k, ho, wo, l.cin, l.cout, l.r, l.s);
+      b = wgrad_workspace_bytes(k, ho, wo, l.cin, l.cout, l.r, l.s, dtype);
     }
     if (b == 0) b = 256;   // keep the object in the access pattern even when no split is used
   } else {

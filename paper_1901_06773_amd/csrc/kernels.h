@@ -96,7 +96,12 @@ struct LaunchProbe {
   hipEvent_t before = nullptr, after = nullptr;
 };
 hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe = nullptr);
-enum { V_IGEMM_FAST = 0, V_IGEMM_GENERIC, V_WGRAD_FAST, V_WGRAD_GENERIC, V_IGEMM_DIRECT, V_WGRAD_DIRECT, V_COUNT };
+// The 128 x 128 kernel for bf16 storage (conv_igemm_bf16.hip): whether it takes this launch (a
+// function of the shape and the alignment only), and the launch itself; conv_igemm() routes to it.
+bool conv_igemm_bf16_takes(const ConvGeom& g, long M, long K);
+hipError_t conv_igemm_bf16(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchProbe* probe);
+enum { V_IGEMM_FAST = 0, V_IGEMM_GENERIC, V_WGRAD_FAST, V_WGRAD_GENERIC, V_IGEMM_DIRECT, V_WGRAD_DIRECT, V_WGRAD_BF16,
+       V_IGEMM_BF16, V_COUNT };
 const char* conv_variant_name(int v);
 
 // dw[co][(r,t,ci)] = sum_{img,p,q} dy[img,p,q,co] * x[img, p*stride+r-pad, q*stride+t-pad, ci]
@@ -117,7 +122,9 @@ struct WgradGeom {
   // Optional side job: extra workgroups add up the parts of an earlier weight gradient.
   ReduceJob side;
 };
-size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s);
+// dtype: DT_F32 / DT_BF16 (the two storage types cut the minibatch range differently), or -1 = the
+// larger of the two
+size_t wgrad_workspace_bytes(int n_img, int p, int q, int cin, int cout, int r, int s, int dtype);
 // If `deferred` is given and the gradient is split over the minibatch, the reduction of the
 // parts is not launched but described there (the caller appends it to a later launch or
 // runs reduce_parts); otherwise dw is complete when the stream reaches the end of this call.

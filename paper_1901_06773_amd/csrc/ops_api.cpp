@@ -31,7 +31,7 @@ extern "C" size_t acc_op_conv_workspace(int n, int h, int w, int cin, int cout, 
   if (!conv_ok(n, h, w, cin, cout, r, s, stride, pad)) return 0;
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(w, s, stride, pad);
   // the sub-filters of a strided data gradient are aligned one by one
-  return al256(wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s)) + al256((size_t)cout * cin * r * s * sizeof(float)) +
+  return al256(wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s, -1)) + al256((size_t)cout * cin * r * s * sizeof(float)) +
          (stride > 1 ? kMaxDgradParts * 256 : 0);
 }
 
@@ -111,7 +111,7 @@ extern "C" int acc_op_conv_wgrad(const void* x, const void* dy, float* dw, int n
   if (!x || !dy || !dw || !dtype_ok(dtype) || !conv_ok(n, h, wd, cin, cout, r, s, stride, pad)) return ACC_EINVAL;
   if (!al16({x, dy, dw, workspace})) return ACC_EINVAL;
   const int ho = out_dim(h, r, stride, pad), wo = out_dim(wd, s, stride, pad);
-  const size_t need = wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s);
+  const size_t need = wgrad_workspace_bytes(n, ho, wo, cin, cout, r, s, dtype);
   if (need && (!workspace || workspace_bytes < need)) return ACC_EINVAL;
   WgradGeom g{};
   g.x = x; g.dy = dy; g.dw = dw; g.dtype = dtype;

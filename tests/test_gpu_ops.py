@@ -302,6 +302,17 @@ BF16_CASES = [
     (2, 16, 16, 32, 16, 3, 1, 1),      # 32 channels: per-element path in bf16
     (2, 12, 10, 20, 24, 3, 1, 1),      # ragged channels
     (2, 23, 23, 8, 16, 7, 2, 3),       # stem-like
+    # input channels a multiple of 128: the weight gradient runs on the bf16 matrix cores (128 x 128 tiles)
+    (4, 14, 14, 256, 128, 3, 1, 1),    # filter taps and padding; 784 rows = 12 chunks of 64 and a ragged one
+    (6, 14, 14, 128, 200, 3, 1, 1),    # output channels end inside the second row of tiles
+    (8, 28, 28, 128, 128, 3, 2, 1),    # strided 3x3
+    (9, 7, 7, 512, 512, 1, 2, 0),      # strided 1x1
+    (41, 14, 14, 256, 256, 3, 1, 1),   # benchmark-sized layer: the minibatch range is cut into parts
+    # at least 256 tiles of 128 x 128: forward and data gradient run in the 128 x 128 bf16 kernel
+    (16, 56, 56, 64, 128, 1, 1, 0),    # one chunk of K, 392 row tiles
+    (44, 28, 28, 128, 128, 3, 1, 1),   # taps and padding; 34496 rows: the last row tile is half full
+    (44, 56, 56, 128, 128, 1, 2, 0),   # strided gather forward, scattering data gradient
+    (44, 28, 28, 128, 200, 1, 1, 0),   # output channels end inside the second column of tiles
 ]
 
 
