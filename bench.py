@@ -66,6 +66,8 @@ def log(*a):
 
 
 def main():
+    import faulthandler
+    faulthandler.enable()
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by data parallelism, see DESIGN.md); "
@@ -100,10 +102,13 @@ def main():
     trainable, host_need = [], 256
     for k in sorted(set(sweep_ks + swap_point_ks)):
         try:
-            s = probe.plan_swaps(k, budget, B.PLAN_NAIVE_ALL)
+            s_all = probe.plan_swaps(k, budget, B.PLAN_NAIVE_ALL)
             if k in sweep_ks:
                 trainable.append(k)
-            host_need = max(host_need, s["host_bytes"])
+            # what the planner's own choice swaps (with the uncalibrated model; the calibrated one may differ a
+            # little: 10 % on top), never more than every map; pinned memory is capped per process on the box
+            s_dyn = probe.plan_swaps(k, budget, mode if mode != B.PLAN_NONE else B.PLAN_DYNAMIC)
+            host_need = max(host_need, min(s_all["host_bytes"], int(s_dyn["host_bytes"] * 1.1)))
         except B.AccError as e:
             log(f"k={k}: not trainable under {args.budget_gib} GiB ({e})")
             swap_point_ks = [x for x in swap_point_ks if x != k]
@@ -175,7 +180,11 @@ def main():
     # ---- sweep (configs[3]): short runs, to find the throughput-optimal minibatch
     sweep = []
     for k in trainable:
-        summ = ctx.plan_swaps(k, budget, mode)
+        try:
+            summ = ctx.plan_swaps(k, budget, mode)
+        except B.AccError as e:
+            log(f"sweep: k={k} skipped ({e})")
+            continue
         sec, loss = run(ctx, k, 3, 1)
         sweep.append(dict(k=k, images_per_s=k / sec, ms_per_step=sec * 1e3, n_swapped=summ["n_swapped"],
                           n_maps=summ["n_maps"], gib_swapped_each_way=summ["bytes_swapped"] / GiB,
@@ -224,7 +233,11 @@ def main():
     # ---- the swap engine at work: minibatches above the no-swap maximum, same context
     swap_points = []
     for ks in swap_point_ks:
-        sp_summ = ctx.plan_swaps(ks, budget, B.PLAN_DYNAMIC)
+        try:
+            sp_summ = ctx.plan_swaps(ks, budget, B.PLAN_DYNAMIC)
+        except B.AccError as e:
+            log(f"swap point: k={ks} skipped ({e})")
+            continue
         if sp_summ["n_swapped"] == 0:
             continue
         sp_sec, _ = run(ctx, ks, 3, 1)
@@ -380,7 +393,8 @@ def main():
                   layer_peak_gib=summ["layer_peak_bytes"] / GiB, noswap_peak_gib=summ["noswap_peak_bytes"] / GiB,
                   predicted_ms=summ["t_iter"] * 1e3, predicted_stall_ms=summ["t_stall"] * 1e3,
                   predicted_compute_ms=summ["t_compute"] * 1e3, plan_ms=summ["plan_ms"],
-                  host_issue_ms=stats["host_issue_ms"]),
+                  host_issue_ms=stats["host_issue_ms"], host_wait_ms=stats["host_wait_ms"],
+                  host_busy_ms=stats["host_issue_ms"] - stats["host_wait_ms"]),
         step_ms_by_kind=by_kind, hbm_bound_steps=hbm, sweep=sweep, noswap_max_k=noswap_max_k, tuner=tuner, loss=loss,
         paper_context="AccUDNN on an NVIDIA M40 (Caffe + cuDNN): ResNet-152, 12 GB budget, k=54, 24 images/s "
                       "(Table 1); 8.3 GB at k=32 with 64% of maps offloaded (Sec. 6.3)")

@@ -125,7 +125,8 @@ typedef struct {
 
 typedef struct {
   double step_ms;           /* last train_step: host clock, entry to completion           */
-  double host_issue_ms;     /* last train_step: host time to issue all work               */
+  double host_issue_ms;     /* last train_step: host time from entry until all work is issued,
+                               host_wait_ms included                                     */
   uint64_t peak_pool_bytes; /* pool offset where the highest byte in use ends, static part
                                included.  With ACC_DEBUG_POISON: measured (the highest word
                                that anything wrote during the iteration); otherwise the end
@@ -137,6 +138,10 @@ typedef struct {
                                during the iteration, static part included; else 0         */
   int32_t peak_is_measured; /* 1 if peak_pool_bytes comes from the poison scan            */
   int32_t reserved;
+  double host_wait_ms;      /* of host_issue_ms: time the host stood still because it was a full
+                               window of steps or copies ahead of the GPU (it issues no further
+                               ahead than that); host_issue_ms - host_wait_ms is what issuing
+                               the iteration costs the host                               */
 } acc_stats;
 
 typedef struct acc_ctx acc_ctx;

@@ -83,7 +83,7 @@ class acc_stats(C.Structure):
     _fields_ = [("step_ms", C.c_double), ("host_issue_ms", C.c_double), ("peak_pool_bytes", C.c_uint64),
                 ("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64), ("d2h_ms", C.c_double),
                 ("h2d_ms", C.c_double), ("steps_run", C.c_uint64), ("touched_pool_bytes", C.c_uint64),
-                ("peak_is_measured", C.c_int32), ("reserved", C.c_int32)]
+                ("peak_is_measured", C.c_int32), ("reserved", C.c_int32), ("host_wait_ms", C.c_double)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

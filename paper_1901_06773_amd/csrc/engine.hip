@@ -128,7 +128,10 @@ constexpr int kStepWindow = 32, kWindows = 3, kCopyWindow = 64;
 // iteration: such runs (ResNet-152, minibatch 224 and 256, all maps swapped, 36-41 GiB each
 // way) ended in a crash of the process at its next HIP call, cause unknown; the same
 // plans run fine untimed, and timed runs up to 20 GiB of swapped maps are fine.
-constexpr size_t kMaxTimedSwapBytes = (size_t)24 << 30;
+#ifndef ACC_MAX_TIMED_SWAP_BYTES
+#define ACC_MAX_TIMED_SWAP_BYTES ((size_t)24 << 30)   // (a host-only test build lifts it)
+#endif
+constexpr size_t kMaxTimedSwapBytes = ACC_MAX_TIMED_SWAP_BYTES;
 
 #define HIPCHK(ctx, expr)                                  \
   do {                                                     \
@@ -954,13 +957,20 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   }
   HIPCHK(c, hipEventRecord(c->ev_begin, c->s_c));
   int n_compute = 0;
+  double t_waited = 0.0;     // host time spent blocked on the flow-control windows (the GPU is behind, not the host)
+  auto window_wait = [&](hipEvent_t e) {
+    const double t0w = now_ms();
+    const hipError_t r = hipEventSynchronize(e);
+    t_waited += now_ms() - t0w;
+    return r;
+  };
   for (const Instr& in : P.instrs) {
     if ((in.op == I_LOAD_INPUT || in.op == I_PREFETCH) && in.seq >= kCopyWindow)
-      HIPCHK(c, hipEventSynchronize(c->ev_h2d[in.seq - kCopyWindow]));
+      HIPCHK(c, window_wait(c->ev_h2d[in.seq - kCopyWindow]));
     if (in.op == I_OFFLOAD && in.seq >= kCopyWindow)
-      HIPCHK(c, hipEventSynchronize(c->ev_d2h[in.seq - kCopyWindow]));
+      HIPCHK(c, window_wait(c->ev_d2h[in.seq - kCopyWindow]));
     if (in.op == I_COMPUTE && n_compute % kStepWindow == 0 && n_compute / kStepWindow >= kWindows)
-      HIPCHK(c, hipEventSynchronize(c->ev_window[n_compute / kStepWindow - kWindows]));
+      HIPCHK(c, window_wait(c->ev_window[n_compute / kStepWindow - kWindows]));
     switch (in.op) {
       case I_LOAD_INPUT: {
         void* dst = c->dyn + c->cur_off[in.arg];
@@ -1059,6 +1069,7 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
   if (loss_out) *loss_out = *c->h_loss;
   c->stats.step_ms = t_done - t_host0;
   c->stats.host_issue_ms = t_issued - t_host0;
+  c->stats.host_wait_ms = t_waited;
   // without the poison mode: where the plan's highest block ends (an offset, not a sum of sizes)
   c->stats.peak_pool_bytes = g.static_bytes() + P.dyn_top;
   c->stats.touched_pool_bytes = 0;

@@ -494,26 +494,79 @@ def test_bf16_step_equals_its_layers_put_together():
     print(f"worst relative l2 distance of a gradient tensor: {worst:.2e}")
 
 
-@pytest.mark.parametrize("name", ["config1_unit", "mini_resnet_w8", "mini_resnet_w32", "wide_chain"])
-def test_bf16_loss_is_within_two_percent_of_the_fp32_oracle(name):
+def _output_shapes(net):
+    """(c, h, w) of every layer's output."""
+    out = []
+    for l in net.layers:
+        c, h, w = (net.in_c, net.in_h, net.in_w) if l.in0 < 0 else out[l.in0]
+        if l.kind in (S.CONV, S.MAXPOOL):
+            co = l.cout if l.kind == S.CONV else c
+            out.append((co, O.out_dim(h, l.r, l.stride, l.pad), O.out_dim(w, l.s, l.stride, l.pad)))
+        elif l.kind == S.GAP:
+            out.append((c, 1, 1))
+        elif l.kind == S.FC:
+            out.append((l.cout, 1, 1))
+        elif l.kind == S.SOFTMAX_CE:
+            out.append((1, 1, 1))
+        else:
+            out.append((c, h, w))
+    return out
+
+
+@pytest.mark.parametrize("name", ["config1_unit", "mini_resnet_w8", "mini_resnet_w32", "wide_chain", "tall_chain", "resnet50"])
+def test_bf16_step_against_the_fp32_oracle(name):
     """Activations, their gradients and the weights the kernels read stored as bf16, fp32
-    accumulation, fp32 master weights and statistics: the loss within 2e-2 of the fp32
-    oracle's, every gradient finite and pointing the oracle's way (cosine above 0.8 per
-    tensor: the rounding noise explained above is large but not dominant)."""
-    make, k = NETS[name]
-    net = make()
+    accumulation, fp32 master weights and statistics, against the fp32 oracle (configs[4]'s
+    arithmetic; ResNet-50 at its full input size and minibatch 8 is the deep case).
+    End to end: the loss within 2e-2, every gradient finite.  Gradient tensors: compared in a
+    second iteration that runs on the oracle's forward activations (rounded to bf16 on their
+    way in, acc_inject_output), so that ReLU masks and max-pool winners are taken from the
+    same values on both sides: per tensor the relative l2 distance is printed; 2e-2 must hold
+    for nine tensors in ten and 1e-1 for all (the exceptions sit where a batch norm over few
+    positions cancels most of the incoming gradient: bf16 rounding of the stored gradient,
+    2^-9 per element, is amplified there).  Without the injection the gradients of the two
+    sides are 8-130 % apart at random initialisation, the fp32 paths' 1-5 % for the same reason
+    times the coarser rounding."""
+    if name in NETS:
+        make, k = NETS[name]
+        net = make()
+    else:
+        net, k = getattr(S, name)(), 8
+    chw = (net.in_c, net.in_h, net.in_w)
     params = S.init_params(net)
     img, lab = S.make_batch(net, k, 0)
-    o_loss, o_w, o_g = O.train_step(net.as_array(), (net.in_c, net.in_h, net.in_w), params, img, lab, 0.1)
+    shp = _output_shapes(net)
+    stored = [i for i, l in enumerate(net.layers) if l.kind in (S.CONV, S.RELU, S.MAXPOOL)]
+    sizes = {i: k * int(np.prod(shp[i])) for i in stored}
+    o_loss, o_w, o_g, o_acts = O.train_step(net.as_array(), chw, params, img, lab, 0.1, want_acts=stored, act_sizes=sizes)
     b = B()
-    g = run_gpu(net, params, k, b.PLAN_NONE, 512 * MiB, dtype=b.BF16)
-    l2_close(g["losses"][0], o_loss, f"{name} loss", 2e-2)
-    for i, (a, r) in enumerate(zip(g["grads"], o_g)):
+    probe = b.Context(net.as_array(), chw, dtype=b.BF16)
+    pool = int(probe.plan_swaps(k, 1 << 40, b.PLAN_NONE)["peak_bytes"] * 1.05) + 64 * MiB
+    probe.close()
+    ctx = b.Context(net.as_array(), chw, pool_bytes=pool, host_bytes=MiB, dtype=b.BF16)
+    ctx.set_weights(params)
+    ctx.plan_swaps(k, pool, b.PLAN_NONE)
+    pinned = torch.from_numpy(img).pin_memory()
+    loss = ctx.train_step(pinned, lab, 0.0)
+    l2_close(loss, o_loss, f"{name} loss", 2e-2)
+    for a in ctx.get_grads():
+        assert np.isfinite(a).all()
+    ctx.inject_outputs({i: o_acts[i].reshape(k, *shp[i]).transpose(0, 2, 3, 1) for i in stored})
+    loss2 = ctx.train_step(pinned, lab, 0.0)
+    grads = ctx.get_grads()
+    ctx.stop_captures()
+    ctx.close()
+    l2_close(loss2, o_loss, f"{name} loss on the oracle's activations", 2e-2)
+    errs = {}
+    for i, (a, r) in enumerate(zip(grads, o_g)):
         if r.size:
-            a = np.asarray(a, np.float64)
-            assert np.isfinite(a).all()
-            cos = float(np.dot(a, r) / (np.linalg.norm(a) * np.linalg.norm(r)))
-            assert cos > 0.8, f"{name} grad of layer {i} ({S.KIND_NAMES[net.layers[i].kind]}): cosine {cos:.3f}"
+            errs[i] = float(np.linalg.norm(np.asarray(a, np.float64) - r) / np.linalg.norm(r))
+    over = {i: e for i, e in errs.items() if e > 2e-2}
+    print(f"\n{name} k={k} bf16 against the fp32 oracle: loss {abs(loss - o_loss) / o_loss:.1e}; {len(errs)} gradient tensors, "
+          f"median {np.median(list(errs.values())):.1e}, max {max(errs.values()):.1e}; beyond 2e-2: "
+          + (", ".join(f"layer {i} ({S.KIND_NAMES[net.layers[i].kind]}) {e:.1e}" for i, e in over.items()) or "none"))
+    assert len(over) <= 0.1 * len(errs), over
+    assert max(errs.values()) <= 1e-1, over
 
 
 def test_bf16_maps_take_half_the_memory_and_swap_bit_exactly():
