@@ -173,6 +173,8 @@ __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
     float* __restrict__ mean, float* __restrict__ istd, float* __restrict__ coef, long rows, int c,
     float eps, int slabs, int stride) {
   const int ch = blockIdx.x * FIN_CH + threadIdx.x / 64, lane = threadIdx.x & 63;
+  // the channel's parameters are fetched beside the partial sums, not after them
+  const float gam = gamma[ch < c ? ch : 0], bet = beta[ch < c ? ch : 0];
   double sum, ss;
   sum_partials(part, c, slabs, ch, lane, &sum, &ss, stride);
   if (lane != 0 || ch >= c) return;
@@ -183,10 +185,10 @@ __global__ __launch_bounds__(THREADS) void bn_fwd_finish_kernel(
   const double is = 1.0 / sqrt(var + (double)eps);
   mean[ch] = (float)mu;
   istd[ch] = (float)is;
-  const double scale = (double)gamma[ch] * is;
+  const double scale = (double)gam * is;
   coef[ch] = (float)scale;
   coef[c + ch] = (float)mu;
-  coef[2 * c + ch] = beta[ch];
+  coef[2 * c + ch] = bet;
 }
 
 // backward: dbeta, dgamma; coef[0] = a = gamma*istd, coef[1] = dbeta/m, coef[2] = dgamma/m
@@ -195,13 +197,14 @@ __global__ __launch_bounds__(THREADS) void bn_bwd_finish_kernel(
     float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef, long rows, int c,
     int slabs, int stride) {
   const int ch = blockIdx.x * FIN_CH + threadIdx.x / 64, lane = threadIdx.x & 63;
+  const float gam = gamma[ch < c ? ch : 0], is = istd[ch < c ? ch : 0];
   double db, dg;
   sum_partials(part, c, slabs, ch, lane, &db, &dg, stride);
   if (lane != 0 || ch >= c) return;
   dbeta[ch] = (float)db;
   dgamma[ch] = (float)dg;
   const double m = (double)rows;
-  coef[ch] = gamma[ch] * istd[ch];
+  coef[ch] = gam * is;
   coef[c + ch] = (float)(db / m);
   coef[2 * c + ch] = (float)(dg / m);
 }
