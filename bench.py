@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--serial", action="store_true",
                     help="weight gradients on the compute stream instead of their own (every kernel runs alone: "
                          "the setting in which single kernels are timed)")
+    ap.add_argument("--graph", default="auto", choices=["auto", "on", "off"],
+                    help="replay iterations that swap nothing from a HIP graph (acc_set_graph); auto: whichever is "
+                         "faster in two short runs at the headline minibatch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-noswap-reference", action="store_true")
     ap.add_argument("--cpu-sample-k", type=int, default=12)
@@ -197,6 +200,17 @@ def main():
 
     # ---- headline: W warm-up steps, then exactly K timed steps, inputs resident in HBM
     summ = ctx.plan_swaps(k, budget, mode)
+    graph_choice = dict(requested=args.graph, used=False)
+    if summ["n_swapped"] == 0 and args.graph != "off":
+        if args.graph == "auto":
+            sec_eager, _ = run(ctx, k, 5, 2)
+            ctx.set_graph(True)
+            sec_graph, _ = run(ctx, k, 5, 2)
+            graph_choice.update(eager_ms=sec_eager * 1e3, graph_ms=sec_graph * 1e3)
+            graph_choice["used"] = sec_graph < sec_eager
+        else:
+            graph_choice["used"] = True
+        ctx.set_graph(graph_choice["used"])
     sec, loss = run(ctx, k, args.steps, args.warmup)
     value = k / sec
     stats = ctx.stats()
@@ -386,7 +400,7 @@ def main():
         config=dict(workload=f"{args.net} {'fp32' if args.dtype == 'f32' else 'bf16 (fp32 master weights and statistics)'} training step, 224x224x3 N(0,1) images, 1000 classes, "
                              f"minibatch {k}, device-memory budget {args.budget_gib} GiB, planner mode {args.mode}",
                     minibatch=k, budget_gib=args.budget_gib, strides="v1", optimizer="plain SGD lr 0.1",
-                    wgrad_stream=not args.serial),
+                    wgrad_stream=not args.serial, graph_replay=graph_choice),
         roofline=roofline, cpu_baseline=cpu, pcie_inclusive=pcie_inclusive, conv=conv, swap=swap, swap_points=swap_points,
         noswap_reference=noswap,
         plan=dict(n_maps=summ["n_maps"], n_swapped=summ["n_swapped"], peak_gib=summ["peak_bytes"] / GiB,

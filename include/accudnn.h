@@ -310,6 +310,14 @@ int acc_inject_output(acc_ctx* ctx, int layer, const void* host_src, size_t byte
 /* on = 0: weight gradients run on the compute stream even if the context has a stream for
  * them (for measurements); on != 0 (default): they use it. */
 int acc_set_wgrad_overlap(acc_ctx* ctx, int on);
+/* on != 0: an iteration whose plan swaps nothing is recorded once into a HIP graph (stream capture
+ * of the compute stream and, through its fork / join events, of the weight-gradient stream) and
+ * replayed from then on: one graph launch instead of about a thousand kernel launches and event
+ * calls per iteration.  The input copies and the update kernel (the learning rate is its argument)
+ * stay outside the recording.  Same kernels, same order, same bits.  Plans that swap, profiling,
+ * the verification mode and capture / injection hooks run the ordinary way whatever this says; a
+ * new plan or a change of acc_set_wgrad_overlap discards the recording.  Default: off. */
+int acc_set_graph(acc_ctx* ctx, int on);
 /* level 0: off.  1: timing events around every step and every copy.  2: timing events
  * directly around every convolution kernel launch (while this is on, weight gradients run on
  * the compute stream, so that every kernel is timed alone).  3: both.  Events cost host time. */

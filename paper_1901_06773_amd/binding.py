@@ -141,6 +141,7 @@ _PROTOS = {
     "acc_get_stats": (_I, [_VP, C.POINTER(acc_stats)]),
     "acc_set_profiling": (_I, [_VP, _I]),
     "acc_set_debug": (_I, [_VP, _I]),
+    "acc_set_graph": (_I, [_VP, _I]),
     "acc_capture_output": (_I, [_VP, _I, _VP, _SZ]),
     "acc_inject_output": (_I, [_VP, _I, _VP, _SZ]),
     "acc_set_wgrad_overlap": (_I, [_VP, _I]),
@@ -409,6 +410,10 @@ class Context:
     def stop_captures(self):
         self._check(_lib.acc_capture_output(self._h, -1, None, 0))
         self._check(_lib.acc_inject_output(self._h, -1, None, 0))
+
+    def set_graph(self, on: bool):
+        """Record the compute part of an iteration that swaps nothing into a HIP graph and replay it."""
+        self._check(_lib.acc_set_graph(self._h, 1 if on else 0))
 
     def set_profiling(self, level: int):
         """0 off, 1 per step and copy, 2 per convolution kernel launch, 3 both."""

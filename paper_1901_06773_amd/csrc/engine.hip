@@ -77,6 +77,18 @@ struct acc_ctx {
   std::vector<size_t> cur_off;  // per tensor, while executing
   acc_stats stats{};
   float* h_loss = nullptr;      // pinned: [0] loss, then (as 64-bit words 1..2) what the poison scan found
+  // The compute part of an iteration that swaps nothing, captured once per plan into a HIP graph
+  // and replayed (acc_set_graph): everything between the input copies and the update kernel.
+  bool use_graph = false;
+  bool capturing = false;             // run_step is recording into the graph: the update kernel stays outside
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  void drop_graph() {
+    if (graph_exec) (void)hipGraphExecDestroy(graph_exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    graph_exec = nullptr;
+    graph = nullptr;
+  }
   // verification switches (acc_set_debug) and parity hooks (acc_capture_output)
   int debug_flags = 0;
   struct Capture { int tensor; void* dst; size_t cap; };
@@ -293,6 +305,7 @@ extern "C" void acc_destroy(acc_ctx* c) {
     (void)hipStreamSynchronize(c->s_i);
     if (c->s_w) (void)hipStreamSynchronize(c->s_w);
     c->drop_events();
+    c->drop_graph();
     for (auto* v : {&c->ev_fork, &c->ev_wdone})
       for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     for (auto& kp : c->kprobes) { (void)hipEventDestroy(kp.a); (void)hipEventDestroy(kp.b); }
@@ -386,7 +399,9 @@ int install_plan(acc_ctx* c, Plan&& p, acc_plan_summary* out, double t0) {
     HIPCHK(c, hipStreamSynchronize(c->s_c));
     HIPCHK(c, hipStreamSynchronize(c->s_o));
     HIPCHK(c, hipStreamSynchronize(c->s_i));
+    if (c->s_w) HIPCHK(c, hipStreamSynchronize(c->s_w));
     c->drop_events();
+    c->drop_graph();                      // a graph holds the pool offsets of the plan it was captured under
     const int ns = (int)c->g.steps.size();
     c->ev_step.assign(ns, nullptr);
     for (const Instr& in : p.instrs)
@@ -888,6 +903,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
     }
     case K_SGD:
       if (hipError_t e = flush_pending_reduce(c); e != hipSuccess) return e;
+      if (c->capturing) return hipSuccess;   // the learning rate is an argument: the update is launched after the graph
       return sgd_update(c->d_params, c->d_grads, lr, g.param_elems, c->d_params16, st);
   }
   return hipErrorInvalidValue;
@@ -956,6 +972,23 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
     }
   }
   HIPCHK(c, hipEventRecord(c->ev_begin, c->s_c));
+  // Graph mode: an iteration that swaps nothing is the same sequence of launches every time, with the
+  // same addresses; only the input copies (their source is the caller's) and the update kernel (the
+  // learning rate is its argument) stay outside the graph.
+  bool no_hooks = true;
+  for (const auto* table : {&c->capture_at, &c->inject_at})
+    for (const auto& list : *table) no_hooks = no_hooks && list.empty();
+  const bool graph_mode = c->use_graph && P.n_swapped == 0 && P.n_d2h == 0 && !c->profiling && !c->kernel_profiling &&
+                          !poison && !c->calibrating && no_hooks;
+  bool graph_started = false, graph_replayed = false;
+  auto abort_capture = [&]() {
+    hipGraph_t dead = nullptr;
+    (void)hipStreamEndCapture(c->s_c, &dead);
+    if (dead) (void)hipGraphDestroy(dead);
+    c->capturing = false;
+    c->drop_graph();
+    (void)hipGetLastError();
+  };
   int n_compute = 0;
   double t_waited = 0.0;     // host time spent blocked on the flow-control windows (the GPU is behind, not the host)
   auto window_wait = [&](hipEvent_t e) {
@@ -993,6 +1026,35 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
         break;
       }
       case I_COMPUTE: {
+        if (graph_mode) {
+          if (!graph_started) {
+            graph_started = true;
+            // every input copy has been issued (they head the list); the graph starts behind them
+            for (int q = 0; q < P.n_h2d; ++q) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_h2d[q], 0));
+            if (c->graph_exec) {
+              HIPCHK(c, hipGraphLaunch(c->graph_exec, c->s_c));
+              graph_replayed = true;
+            } else {
+              HIPCHK(c, hipStreamBeginCapture(c->s_c, hipStreamCaptureModeThreadLocal));
+              c->capturing = true;
+            }
+          }
+          if (graph_replayed) break;
+          hipError_t e = hipSuccess;
+          for (int jw : g.steps[in.arg].joins)
+            if (c->s_w && c->wgrad_in_flight[jw] && e == hipSuccess) {
+              e = hipStreamWaitEvent(c->s_c, c->ev_wdone[jw], 0);
+              c->wgrad_in_flight[jw] = 0;
+            }
+          if (e == hipSuccess) e = run_step(c, in.arg, lr);
+          if (e != hipSuccess) {
+            abort_capture();
+            char buf[96];
+            snprintf(buf, sizeof buf, "step %d (%s), while capturing", in.arg, step_kind_name(g.steps[in.arg].kind));
+            return c->hipfail(e, buf);
+          }
+          break;
+        }
         if (in.wait_d2h >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_d2h[in.wait_d2h], 0));
         if (in.wait_h2d >= 0) HIPCHK(c, hipStreamWaitEvent(c->s_c, c->ev_h2d[in.wait_h2d], 0));
         if (c->profiling) HIPCHK(c, hipEventRecord(c->prof_a[in.arg], c->s_c));
@@ -1057,6 +1119,22 @@ extern "C" int acc_train_step(acc_ctx* c, const float* images, int images_loc, c
         break;
       }
     }
+  }
+  if (graph_mode && graph_started) {
+    if (c->capturing) {
+      // every weight gradient was joined by the last step; close, instantiate and run the recording
+      hipError_t e = hipStreamEndCapture(c->s_c, &c->graph);
+      c->capturing = false;
+      if (e == hipSuccess) e = hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0);
+      if (e != hipSuccess) {
+        c->drop_graph();
+        (void)hipGetLastError();
+        return c->hipfail(e, "graph capture");
+      }
+      HIPCHK(c, hipGraphLaunch(c->graph_exec, c->s_c));
+    }
+    const hipError_t eu = sgd_update(c->d_params, c->d_grads, lr, g.param_elems, c->d_params16, c->s_c);
+    if (eu != hipSuccess) return c->hipfail(eu, "sgd_update");
   }
   HIPCHK(c, hipMemcpyAsync(c->h_loss, c->d_loss, sizeof(float), hipMemcpyDeviceToHost, c->s_c));
   HIPCHK(c, hipEventRecord(c->ev_end, c->s_c));
@@ -1206,7 +1284,16 @@ extern "C" int acc_inject_output(acc_ctx* c, int layer, const void* host_src, si
 
 extern "C" int acc_set_wgrad_overlap(acc_ctx* c, int on) {
   if (!c) return ACC_EINVAL;
+  if (c->wgrad_overlap != (on != 0)) c->drop_graph();   // the recording holds the streams' fork and join
   c->wgrad_overlap = on != 0;
+  return ACC_OK;
+}
+
+extern "C" int acc_set_graph(acc_ctx* c, int on) {
+  if (!c) return ACC_EINVAL;
+  if (on && !c->have_res) return c->fail(ACC_ESTATE, "context has no device resources");
+  c->use_graph = on != 0;
+  if (!on) c->drop_graph();
   return ACC_OK;
 }
 

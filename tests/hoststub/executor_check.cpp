@@ -100,6 +100,31 @@ int main(int argc, char** argv) {
     acc_set_profiling(c, 0);
     steps(1, "serial step");
     printf("k=64 swapped %d of %d maps\n", s.n_swapped, s.n_maps);
+  } else if (scenario == "graph") {
+    // an iteration that swaps nothing, recorded into a graph on its first run and replayed afterwards;
+    // a new plan discards the recording; profiling runs the ordinary way in between
+    acc_set_graph(c, 1);
+    for (int k : {32, 41}) {
+      if (acc_plan_swaps(c, k, budget, ACC_PLAN_DYNAMIC, &s) != ACC_OK) { rc = fail("plan", c); break; }
+      if (s.n_swapped != 0) { rc = fail("expected a plan without swaps", c); break; }
+      const long l0 = stub_counters().launches, g0 = stub_counters().graph_launches;
+      steps(1, "capturing step");
+      const long l1 = stub_counters().launches;
+      steps(3, "replayed step");
+      const long l2 = stub_counters().launches, g2 = stub_counters().graph_launches;
+      printf("k=%d: capture issued %ld launches, three replays %ld launches and %ld graph launches in all\n", k, l1 - l0, l2 - l1, g2 - g0);
+      if (g2 - g0 != 4 || l2 - l1 != 3) rc = 1;          // per replay: the graph and the update kernel
+      acc_set_profiling(c, 1);
+      steps(1, "timed step beside the recording");
+      acc_set_profiling(c, 0);
+      steps(1, "replayed step after a timed one");
+      if (stub_counters().graph_launches - g2 != 1) rc = 1;
+    }
+    if (!rc && acc_plan_swaps(c, 64, budget, ACC_PLAN_DYNAMIC, &s) == ACC_OK) {
+      const long g0 = stub_counters().graph_launches;
+      steps(2, "swapping step with graph mode on");
+      if (stub_counters().graph_launches != g0) rc = 1;  // plans that swap never use the graph
+    }
   } else if (scenario == "selftest") {
     // the stand-in must see planted mistakes: a wait on an event nobody recorded, a wait on last
     // iteration's record, a timing read on an untimed event, a copy that leaves the pool
@@ -132,12 +157,12 @@ int main(int argc, char** argv) {
          g.events_created, g.events_destroyed, stub_live_events(), g.max_live_events, g.records, g.stream_waits, g.host_waits,
          g.elapsed_reads, g.copies, g.copy_bytes / (double)GiB, g.launches);
   printf("violations: dead_event_uses %ld waits_on_unrecorded %ld waits_on_stale %ld elapsed_on_untimed %ld copies_out_of_range %ld "
-         "pointers_outside_pool %ld null_streams %ld leaked_events %ld (waits on own stream: %ld)\n",
+         "pointers_outside_pool %ld null_streams %ld sync_in_capture %ld leaked_events %ld (waits on own stream: %ld)\n",
          g.dead_event_uses, g.waits_on_unrecorded, g.waits_on_stale, g.elapsed_on_untimed, g.copies_out_of_range,
-         g.pointers_outside_pool, g.null_streams, stub_live_events(), g.waits_on_own_stream);
+         g.pointers_outside_pool, g.null_streams, g.sync_in_capture, stub_live_events(), g.waits_on_own_stream);
   if (g.first_complaint[0]) printf("first complaint: %s\n", g.first_complaint);
   const long bad = g.dead_event_uses + g.waits_on_unrecorded + g.waits_on_stale + g.elapsed_on_untimed + g.copies_out_of_range +
-                   g.pointers_outside_pool + g.null_streams + stub_live_events();
+                   g.pointers_outside_pool + g.null_streams + g.sync_in_capture + stub_live_events();
   for (int i = 0; i < 4; ++i) stub_free_stream(st[i]);
   if (rc) return rc;
   printf(bad ? "RESULT: violations\n" : "RESULT: clean\n");

@@ -66,5 +66,17 @@ hipError_t hipHostFree(void* p);
 hipError_t hipGetLastError();
 const char* hipGetErrorString(hipError_t e);
 
+struct stub_graph;
+typedef stub_graph* hipGraph_t;
+typedef stub_graph* hipGraphExec_t;
+typedef struct hipGraphNode_st* hipGraphNode_t;
+enum hipStreamCaptureMode { hipStreamCaptureModeGlobal = 0, hipStreamCaptureModeThreadLocal = 1, hipStreamCaptureModeRelaxed = 2 };
+hipError_t hipStreamBeginCapture(hipStream_t s, hipStreamCaptureMode mode);
+hipError_t hipStreamEndCapture(hipStream_t s, hipGraph_t* graph);
+hipError_t hipGraphInstantiate(hipGraphExec_t* exec, hipGraph_t graph, hipGraphNode_t* error_node, char* log, size_t log_bytes);
+hipError_t hipGraphLaunch(hipGraphExec_t exec, hipStream_t s);
+hipError_t hipGraphExecDestroy(hipGraphExec_t exec);
+hipError_t hipGraphDestroy(hipGraph_t graph);
+
 void stub_count_launch(const char* kernel, hipStream_t s);
 #define hipLaunchKernelGGL(kernel, grid, block, shmem, stream, ...) stub_count_launch(#kernel, (stream))

@@ -30,6 +30,7 @@ std::set<stub_event*> g_events;
 char* g_pool = nullptr; size_t g_pool_bytes = 0;
 char* g_arena = nullptr; size_t g_arena_bytes = 0;
 int g_epoch = 1;
+bool g_capture = false;
 
 bool in_pool(const void* p, size_t bytes) {
   const char* q = static_cast<const char*>(p);
@@ -93,7 +94,12 @@ hipError_t hipEventRecord(hipEvent_t e, hipStream_t s) {
   ++g.records;
   return hipSuccess;
 }
-hipError_t hipEventSynchronize(hipEvent_t e) { need_fresh(e, "hipEventSynchronize"); ++g.host_waits; return hipSuccess; }
+hipError_t hipEventSynchronize(hipEvent_t e) {
+  need_fresh(e, "hipEventSynchronize");
+  if (g_capture) { ++g.sync_in_capture; complain("hipEventSynchronize while a stream is capturing"); }
+  ++g.host_waits;
+  return hipSuccess;
+}
 hipError_t hipEventElapsedTime(float* ms, hipEvent_t a, hipEvent_t b) {
   need_fresh(a, "hipEventElapsedTime (first event)");
   need_fresh(b, "hipEventElapsedTime (second event)");
@@ -114,7 +120,11 @@ hipError_t hipStreamWaitEvent(hipStream_t s, hipEvent_t e, unsigned) {
   ++g.stream_waits;
   return hipSuccess;
 }
-hipError_t hipStreamSynchronize(hipStream_t s) { if (!s) ++g.null_streams; return hipSuccess; }
+hipError_t hipStreamSynchronize(hipStream_t s) {
+  if (!s) ++g.null_streams;
+  if (g_capture) { ++g.sync_in_capture; complain("hipStreamSynchronize while a stream is capturing"); }
+  return hipSuccess;
+}
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t bytes, hipMemcpyKind kind, hipStream_t s) {
   if (!s) { ++g.null_streams; complain("hipMemcpyAsync on the null stream"); }
   else s->ops++;
@@ -133,6 +143,30 @@ hipError_t hipMemcpyAsync(void* dst, const void* src, size_t bytes, hipMemcpyKin
   }
   return hipSuccess;
 }
+struct stub_graph { int nodes; };
+hipError_t hipStreamBeginCapture(hipStream_t s, hipStreamCaptureMode) {
+  if (!s || g_capture) { ++g.null_streams; complain("hipStreamBeginCapture: null stream or nested capture"); return hipErrorInvalidValue; }
+  g_capture = true;
+  return hipSuccess;
+}
+hipError_t hipStreamEndCapture(hipStream_t, hipGraph_t* graph) {
+  if (!g_capture) return hipErrorInvalidValue;
+  g_capture = false;
+  *graph = new stub_graph{0};
+  return hipSuccess;
+}
+hipError_t hipGraphInstantiate(hipGraphExec_t* exec, hipGraph_t graph, hipGraphNode_t*, char*, size_t) {
+  if (!graph) return hipErrorInvalidValue;
+  *exec = new stub_graph{graph->nodes};
+  return hipSuccess;
+}
+hipError_t hipGraphLaunch(hipGraphExec_t exec, hipStream_t s) {
+  if (!exec || !s) { ++g.null_streams; complain("hipGraphLaunch: null graph or stream"); return hipErrorInvalidValue; }
+  ++g.graph_launches;
+  return hipSuccess;
+}
+hipError_t hipGraphExecDestroy(hipGraphExec_t exec) { delete exec; return hipSuccess; }
+hipError_t hipGraphDestroy(hipGraph_t graph) { delete graph; return hipSuccess; }
 hipError_t hipHostMalloc(void** p, size_t bytes, unsigned) { *p = calloc(1, bytes); return *p ? hipSuccess : hipErrorOutOfMemory; }
 hipError_t hipHostFree(void* p) { free(p); return hipSuccess; }
 hipError_t hipGetLastError() { return hipSuccess; }

@@ -5,11 +5,11 @@
 struct StubCounters {
   long events_created = 0, events_destroyed = 0, max_live_events = 0;
   long records = 0, stream_waits = 0, host_waits = 0, elapsed_reads = 0;
-  long copies = 0, launches = 0;
+  long copies = 0, launches = 0, graph_launches = 0;
   unsigned long long copy_bytes = 0;
   // what must stay zero
   long dead_event_uses = 0, waits_on_unrecorded = 0, waits_on_stale = 0, elapsed_on_untimed = 0;
-  long copies_out_of_range = 0, pointers_outside_pool = 0, null_streams = 0;
+  long copies_out_of_range = 0, pointers_outside_pool = 0, null_streams = 0, sync_in_capture = 0;
   long waits_on_own_stream = 0;   // reported, not an error
   char first_complaint[160] = {0};
 };

@@ -739,6 +739,68 @@ def test_tuned_minibatch_is_the_fastest_measured_one():
     assert rates[k_swap] < rates[k_best]          # on this link a swap costs more than the larger minibatch gains
 
 
+# ------------------------------------------------------------------ graph replay
+@pytest.mark.parametrize("name", ["mini_resnet_w32", "mini_resnet_basic", "mini_vgg", "wide_chain", "config1_unit"])
+@pytest.mark.parametrize("wgrad_stream", [True, False])
+def test_graph_replay_changes_no_bit(name, wgrad_stream):
+    """acc_set_graph: the compute part of an iteration that swaps nothing is recorded into a HIP graph
+    in its first run and replayed afterwards.  Five iterations on changing batches and learning rates
+    (the first records, four replay), with the program's own eager work and synchronisations between
+    the replays (gradients and weights are read back after every step), against the ordinary run:
+    every loss, every gradient and every weight of every step, bit for bit.  Then a new plan at another
+    minibatch (the recording is discarded and made again), one profiled step in between (runs the
+    ordinary way), and a plan that swaps (never uses the graph)."""
+    make, k = NETS[name]
+    net = make()
+    params = S.init_params(net)
+    b = B()
+    chw = (net.in_c, net.in_h, net.in_w)
+
+    def run(graph, kk, mode, budget, steps, profiled_at=None):
+        ctx = b.Context(net.as_array(), chw, pool_bytes=512 * MiB, host_bytes=256 * MiB, wgrad_stream=wgrad_stream)
+        ctx.set_weights(params)
+        ctx.set_graph(graph)
+        ctx.plan_swaps(kk, budget, mode)
+        out = []
+        for s in range(steps):
+            img, lab = S.make_batch(net, kk, s)
+            if profiled_at == s:
+                ctx.set_profiling(1)
+            loss = ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.1 / (s + 1))
+            ctx.set_profiling(0)
+            out.append((loss, ctx.get_grads(), ctx.get_weights()))
+        # a second plan in the same context
+        ctx.plan_swaps(kk + 1, budget, mode)
+        for s in range(2):
+            img, lab = S.make_batch(net, kk + 1, 10 + s)
+            loss = ctx.train_step(torch.from_numpy(img).cuda(), lab, 0.05)
+            out.append((loss, ctx.get_grads(), ctx.get_weights()))
+        ctx.close()
+        return out
+
+    for mode, budget in ((b.PLAN_NONE, 512 * MiB),):
+        ref = run(False, k, mode, budget, 5)
+        got = run(True, k, mode, budget, 5, profiled_at=3)
+        for s, ((l0, g0, w0), (l1, g1, w1)) in enumerate(zip(ref, got)):
+            assert np.float32(l0).view(np.uint32) == np.float32(l1).view(np.uint32), f"loss of step {s}"
+            bit_equal(g1, g0, f"gradients of step {s}")
+            bit_equal(w1, w0, f"weights of step {s}")
+    # with graph mode on, a plan that swaps runs the ordinary way and keeps its bits
+    probe = b.Context(net.as_array(), chw)
+    s0 = probe.plan_swaps(k, 1 << 40, b.PLAN_NAIVE_ALL)
+    tight = tight_pool(probe, k, s0)
+    probe.close()
+    ctx = b.Context(net.as_array(), chw, pool_bytes=tight, host_bytes=256 * MiB, wgrad_stream=wgrad_stream)
+    ctx.set_weights(params)
+    ctx.set_graph(True)
+    ctx.plan_swaps(k, tight, b.PLAN_NAIVE_ALL)
+    img, lab = S.make_batch(net, k, 0)
+    loss = ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.1)
+    assert np.float32(loss).view(np.uint32) == np.float32(ref[0][0]).view(np.uint32)
+    bit_equal(ctx.get_weights(), ref[0][2], "weights of the swapped step")
+    ctx.close()
+
+
 # ------------------------------------------------------------------ model validation (Sec. 6.2)
 @pytest.mark.parametrize("case", ["mini_naive", "resnet50_dynamic"])
 def test_observed_timeline_obeys_the_plan_and_tracks_the_prediction(case):

@@ -75,6 +75,13 @@ def test_event_timing_above_the_limit_is_refused_before_anything_is_issued(binar
     assert "RESULT: clean" in log
 
 
+def test_graph_mode_records_once_per_plan_and_replays(binaries):
+    built, out = binaries
+    rc, log = run(built["limit"], spec_file(out, S.resnet152()), "graph")
+    assert rc == 0 and "RESULT: clean" in log and "ERROR" not in log, log[-3000:]
+    assert "three replays 3 launches and 4 graph launches in all" in log
+
+
 @pytest.mark.parametrize("net", ["resnet152", "resnet34", "vgg16"])
 def test_planner_chosen_swaps_are_clean_on_the_host(binaries, net):
     built, out = binaries
