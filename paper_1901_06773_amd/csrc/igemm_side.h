@@ -43,7 +43,17 @@ __device__ __forceinline__ void igemm_side_jobs(const ConvGeom& g, int id, void*
   if (i4 >= j.count) return;
   if (i4 + 4 <= j.count && (j.count & 3) == 0) {
     float4 sum = *reinterpret_cast<const float4*>(j.part + i4);
-    for (int k = 1; k < j.splits; ++k) {
+    // eight parts fetched at a time, added in their order: with hundreds of parts (few tiles, many
+    // cuts of the minibatch range) one load waiting for the sum before it is a chain of latencies
+    int k = 1;
+    for (; k + 8 <= j.splits; k += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(j.part + (size_t)(k + u) * j.count + i4);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w; }
+    }
+    for (; k < j.splits; ++k) {
       const float4 v = *reinterpret_cast<const float4*>(j.part + (size_t)k * j.count + i4);
       sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
     }
