@@ -739,6 +739,63 @@ def test_tuned_minibatch_is_the_fastest_measured_one():
     assert rates[k_swap] < rates[k_best]          # on this link a swap costs more than the larger minibatch gains
 
 
+def test_capture_injection_and_launch_profile_hooks():
+    """The parity hooks of the ABI on the single bottleneck block: a captured output is what the oracle
+    computes; a fused-away layer, a bad layer and a buffer that is too small are refused; an injected
+    output replaces the library's own for the rest of the iteration (injecting zeros for the block's last
+    ReLU output makes every image's logits equal to the FC bias, so the loss is ln 10 exactly); the
+    per-launch profile names every convolution of the step with its role and flops."""
+    net = S.bottleneck_unit()
+    k = 2
+    b = B()
+    chw = (net.in_c, net.in_h, net.in_w)
+    params = S.init_params(net)
+    img, lab = S.make_batch(net, k, 0)
+    relus = [i for i, l in enumerate(net.layers) if l.kind == S.RELU]
+    convs = [i for i, l in enumerate(net.layers) if l.kind == S.CONV]
+    bns = [i for i, l in enumerate(net.layers) if l.kind == S.BN]
+    want = convs + relus
+    shp = _output_shapes(net)
+    sizes = {i: k * int(np.prod(shp[i])) for i in want}
+    o_loss, _, _, o_acts = O.train_step(net.as_array(), chw, params, img, lab, 0.0, want_acts=want, act_sizes=sizes)
+    ctx = b.Context(net.as_array(), chw, pool_bytes=64 * MiB, host_bytes=MiB)
+    ctx.set_weights(params)
+    ctx.plan_swaps(k, 64 * MiB, b.PLAN_NONE)
+    lib = b.lib()
+    buf = torch.empty(1 << 20, dtype=torch.uint8).pin_memory()
+    assert lib.acc_capture_output(ctx._h, bns[0], buf.data_ptr(), buf.numel()) == b.ACC_EINVAL      # fused into its ReLU's step
+    assert lib.acc_capture_output(ctx._h, len(net.layers), buf.data_ptr(), buf.numel()) == b.ACC_EINVAL
+    assert lib.acc_capture_output(ctx._h, convs[0], buf.data_ptr(), 16) == b.ACC_OK                  # too small: refused at the step
+    with pytest.raises(b.AccError) as e:
+        ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.0)
+    assert e.value.status == b.ACC_EINVAL
+    ctx.stop_captures()
+    caps = ctx.capture_outputs(want, shp, k)
+    loss = ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.0)
+    close(loss, o_loss, "loss")
+    for i in want:
+        c, h, w = shp[i]
+        close(caps[i].numpy().transpose(0, 3, 1, 2), o_acts[i].reshape(k, c, h, w), f"captured output of layer {i}")
+    ctx.stop_captures()
+    last = relus[-1]
+    ctx.inject_outputs({last: np.zeros((k, shp[last][1], shp[last][2], shp[last][0]), np.float32)})
+    loss0 = ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.0)
+    assert abs(loss0 - np.log(net.classes)) < 1e-6          # FC bias is zero at initialisation: uniform softmax
+    ctx.stop_captures()
+    ctx.set_profiling(2)
+    ctx.train_step(torch.from_numpy(img).pin_memory(), lab, 0.0)
+    prof = ctx.launch_profile()
+    ctx.set_profiling(0)
+    ctx.close()
+    by_role = {r: [p for p in prof if p["role"] == r and net.layers[p["layer"]].kind == S.CONV] for r in ("fwd", "dgrad", "wgrad")}
+    assert sorted(p["layer"] for p in by_role["fwd"]) == convs and sorted(p["layer"] for p in by_role["wgrad"]) == convs
+    assert sorted(p["layer"] for p in by_role["dgrad"]) == convs[1:]          # the first layer needs no data gradient
+    for p in prof:
+        l = net.layers[p["layer"]]
+        if l.kind == S.CONV:
+            assert p["flops"] == 2.0 * k * shp[p["layer"]][1] * shp[p["layer"]][2] * l.cout * l.cin * l.r * l.s and p["ms"] >= 0
+
+
 # ------------------------------------------------------------------ graph replay
 @pytest.mark.parametrize("name", ["mini_resnet_w32", "mini_resnet_basic", "mini_vgg", "wide_chain", "config1_unit"])
 @pytest.mark.parametrize("wgrad_stream", [True, False])
