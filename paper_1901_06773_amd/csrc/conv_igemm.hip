@@ -446,8 +446,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     sq += __shfl_xor(sq, 32);
     if (lane < 32 && n < g.n_out) {
       const size_t slab = (size_t)tile_m * 2 + (wave >> 1);
-      g.stats[slab * g.n_out + n] = (double)sum;
-      g.stats[((size_t)g.stats_stride + slab) * g.n_out + n] = (double)sq;
+      g.stats[slab * g.n_out + n] = sum;
+      g.stats[((size_t)g.stats_stride + slab) * g.n_out + n] = sq;
     }
   }
   if (!ACT && g.bnb.sums) {
@@ -483,8 +483,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     s1 += __shfl_xor(s1, 32);
     if (lane < 32 && col) {
       const size_t slab = (size_t)tile_m * 2 + (wave >> 1);
-      g.bnb.sums[slab * g.n_out + n] = (double)s0;
-      g.bnb.sums[((size_t)g.bnb.stride + slab) * g.n_out + n] = (double)s1;
+      g.bnb.sums[slab * g.n_out + n] = s0;
+      g.bnb.sums[((size_t)g.bnb.stride + slab) * g.n_out + n] = s1;
     }
   }
   if (n >= g.n_out) return;

@@ -710,9 +710,9 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
         const long rows = (long)k * cg.p * cg.q;
         const long slabs = conv_stat_slabs(rows);
         const long stride = (long)k * 2 * (((long)cg.p * cg.q + 63) / 64);
-        const bool fused = slabs <= kBnMaxSlabs && (size_t)2 * stride * l->cout * sizeof(double) <= c->plan.tbytes[s.stats];
+        const bool fused = slabs <= kBnMaxSlabs && (size_t)2 * stride * l->cout * sizeof(float) <= c->plan.tbytes[s.stats];
         c->bn_ready_slabs[s.stats_for] = fused ? (int)slabs : 0;
-        if (fused) { cg.stats = (double*)ptr(s.stats); cg.stats_stride = (int)stride; }
+        if (fused) { cg.stats = (float*)ptr(s.stats); cg.stats_stride = (int)stride; }
       }
       return igemm(cg, conv_flops);
     }
@@ -720,7 +720,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
       BnSums ready{nullptr, 0, 0};
       if (s.stats >= 0 && c->bn_ready_slabs[j] > 0) {
-        ready.part = (const double*)ptr(s.stats);
+        ready.part = (const float*)ptr(s.stats);
         ready.slabs = c->bn_ready_slabs[j];
         ready.stride = (int)((long)k * 2 * (((long)T(s.x).h * T(s.x).w + 63) / 64));
       }
@@ -780,7 +780,7 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
       float* stat = c->d_stats + g.params[s.layer].stat_offset;
       if (s.bnb >= 0 && c->bn_ready_slabs[j] > 0) {
         // the data gradient before this step masked dy and left the sums
-        BnSums ready{(const double*)ptr(s.bnb), c->bn_ready_slabs[j],
+        BnSums ready{(const float*)ptr(s.bnb), c->bn_ready_slabs[j],
                      (int)((long)k * 2 * (((long)T(s.x).h * T(s.x).w + 63) / 64))};
         return bn_backward(ptr(s.x), ptr(s.dy), nullptr, w, stat, stat + l->cin, ptr(s.dx), dw, dw + l->cin, nullptr,
                            (long)k * T(s.x).h * T(s.x).w, l->cin, ptr(s.ws), dt, st, &ready);
@@ -885,11 +885,11 @@ hipError_t run_step(acc_ctx* c, int j, float lr) {
           const long rows = (long)k * h * wd;
           const long slabs = conv_stat_slabs(rows);
           const long stride = (long)k * 2 * (((long)h * wd + 63) / 64);
-          const bool fused = slabs <= kBnMaxSlabs && (size_t)2 * stride * l->cin * sizeof(double) <= c->plan.tbytes[s.bnb];
+          const bool fused = slabs <= kBnMaxSlabs && (size_t)2 * stride * l->cin * sizeof(float) <= c->plan.tbytes[s.bnb];
           c->bn_ready_slabs[s.bnb_for] = fused ? (int)slabs : 0;
           if (fused) {
             const float* stat = c->d_stats + g.params[bb.layer].stat_offset;
-            cg.bnb = BnBackwardSums{ptr(bb.x), ptr(s.x), stat, stat + l->cin, (double*)ptr(s.bnb), (int)stride};
+            cg.bnb = BnBackwardSums{ptr(bb.x), ptr(s.x), stat, stat + l->cin, (float*)ptr(s.bnb), (int)stride};
           }
         }
       } else {  // 1x1, pad 0: dense product on the strided positions, zeros elsewhere

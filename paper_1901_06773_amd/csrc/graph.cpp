@@ -285,13 +285,13 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
   }
   n_fwd = (int)steps.size();
   // A convolution whose output feeds the next step's batch norm hands it the per-channel sums
-  // of every block of 32 rows (fp32 storage): part[2][stride][cout] doubles with
+  // of every block of 32 rows (fp32 storage): part[2][stride][cout] floats with
   // stride = k * 2 * ceil(Ho*Wo / 64) >= 2 * ceil(k*Ho*Wo / 64) blocks.
   if (dtype == ACC_F32)
     for (int j = 0; j + 1 < n_fwd; ++j) {
       if (steps[j].kind != K_CONV_F || steps[j + 1].kind != K_BN_F || steps[j + 1].x != steps[j].y) continue;
       const Tensor& y = tensors[steps[j].y];
-      const size_t per_image = (size_t)2 * 2 * (((size_t)y.h * y.w + 63) / 64) * y.c * sizeof(double);
+      const size_t per_image = (size_t)2 * 2 * (((size_t)y.h * y.w + 63) / 64) * y.c * sizeof(float);
       const int t = new_tensor(T_WORK, 0, 0, 0, per_image, 0, steps[j].layer);
       steps[j].stats_for = j + 1;
       steps[j].stats = t;
@@ -464,7 +464,7 @@ bool Graph::build(const acc_layer* recs, int n, int ic, int ih, int iw, int dt, 
       // convolution kernel 5 % slower for it.)
       if (cl.stride != 1 || bb.dy != cb.dx || !bb.relu || bb.res >= 0 || bb.g_inplace || bb.y != cb.x) continue;
       const Tensor& bx = tensors[bb.x];
-      const size_t per_image = (size_t)2 * 2 * (((size_t)bx.h * bx.w + 63) / 64) * bx.c * sizeof(double);
+      const size_t per_image = (size_t)2 * 2 * (((size_t)bx.h * bx.w + 63) / 64) * bx.c * sizeof(float);
       const int t = new_tensor(T_WORK, 0, 0, 0, per_image, 0, bb.layer);
       cb.bnb_for = j + 1;
       cb.bnb = t;

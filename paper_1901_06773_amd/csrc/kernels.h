@@ -35,14 +35,14 @@ struct FlipJob {
 // convolution's input: the result is the gradient of that output, so the launch masks it with
 // [y > 0] before storing it and leaves, per block of 32 rows and per channel, the sums of the
 // masked gradient g and of g * xhat (xhat = (x - mean) * istd) in sums[2][stride][n_out]
-// (doubles; stride >= conv_stat_slabs(rows)).  x, y: the batch norm's input and output, laid
+// (floats; stride >= conv_stat_slabs(rows)).  x, y: the batch norm's input and output, laid
 // out like the launch's dense output.  sums == nullptr: off.
 struct BnBackwardSums {
   const void* x;
   const void* y;
   const float* mean;
   const float* istd;
-  double* sums;
+  float* sums;
   int stride;
 };
 
@@ -74,8 +74,8 @@ struct ConvGeom {
   // Optional (fp32 storage, plain dense output): per-channel sums of the result and of its
   // square over every block of 32 rows, as the batch norm that follows wants them:
   // stats[0][b][n] = sum, stats[1][b][n] = sum of squares, b < conv_stat_slabs(rows), layout
-  // double[2][stats_stride][n_out] with stats_stride >= conv_stat_slabs(rows).
-  double* stats;
+  // float[2][stats_stride][n_out] with stats_stride >= conv_stat_slabs(rows).
+  float* stats;
   int stats_stride;
   BnBackwardSums bnb;   // fp32 storage, plain dense output, no accumulation
 };
@@ -83,9 +83,10 @@ struct ConvGeom {
 constexpr int kBnMaxSlabs = 1024;
 // Number of 32-row blocks conv_igemm writes sums for (2 per 64-row tile).
 inline long conv_stat_slabs(long rows) { return ((rows + 63) / 64) * 2; }
-// Partial sums some other kernel has left for a batch norm: part[2][stride][c], `slabs` of them valid.
+// Partial sums a convolution launch has left for a batch norm: float part[2][stride][c], `slabs` of
+// them valid (each the fp32 sum over one block of 32 rows).
 struct BnSums {
-  const double* part;
+  const float* part;
   int slabs, stride;
 };
 
