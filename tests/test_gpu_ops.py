@@ -154,10 +154,13 @@ def test_bn_fwd_bwd(case, variant):
 
 
 @pytest.mark.parametrize("case,variant", [((41, 256, 56, 56), "add_relu"), ((41, 1024, 14, 14), "add_relu"),
-                                          ((41, 64, 112, 112), "relu")])
+                                          ((41, 64, 112, 112), "relu"), ((41, 256, 14, 14), "relu"),
+                                          ((41, 2048, 7, 7), "add_relu")])
 def test_bn_full_size(case, variant):
     """The batch-norm shapes of ResNet-152 that move the most bytes, at the benchmark's
-    minibatch (thousands of row slabs, every column slice), element by element."""
+    minibatch (thousands of row slabs, every column slice), element by element; and two of the
+    small ones, whose finishing pass runs inside the apply launch (256 slabs: two batches of
+    partial loads per workgroup; 2048 channels: 64 column slices)."""
     bn_case(case, variant)
 
 
