@@ -115,20 +115,30 @@ enum { L_GENERIC = 0, L_DIRECT = 2 };
 // finds no LDS beside it.
 __host__ __device__ constexpr int direct_chunk_bytes(int) { return 128; }
 
-template <int LOADER, class T, bool ACT>
-__global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
-                                                     int main_grid) {
+// KS = 2: a workgroup of 8 waves, two groups of 4 that each keep the whole 64 x 64 tile and take every
+// second K-chunk (own LDS stages, 64 KB per workgroup); group 1 hands its accumulators over through LDS
+// at the end and group 0 writes the tile.  For launches with at most one tile per compute unit (the 7 x 7
+// layers of a ResNet at small minibatches), where the 4-wave kernel leaves every SIMD with a single wave:
+// 512->512 3x3 at 7 x 7, minibatch 41 (256 tiles) 98 -> 85 us, 2048->512 1x1 47 -> 42 us.  With two tiles
+// per compute unit it gains nothing (256->256 3x3 at 14 x 14: 82.7 -> 82.3 us; 1024->256 1x1 40.5 -> 41.7):
+// the two groups pass the same barriers, so they wait together where two workgroups would not.
+template <int LOADER, class T, bool ACT, int KS = 1>
+__global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int K, int n_tiles_n, int n_tiles,
+                                                          int main_grid) {
   constexpr bool DIRECT = LOADER == L_DIRECT;
+  static_assert(KS == 1 || (KS == 2 && DIRECT && !ACT), "the split serves the direct loader only");
   constexpr int ES = sizeof(T);
   constexpr int DCHUNK = direct_chunk_bytes(ES);
   constexpr int BK = (DIRECT ? DCHUNK : CHUNK_BYTES) / ES;       // elements of K per chunk
   constexpr int LDD = DCHUNK / 4;            // LDS row pitch of L_DIRECT in words
   constexpr int PITCH = DIRECT ? LDD : LD;
-  __shared__ __attribute__((aligned(1024))) float As[2 * BM * PITCH];
-  __shared__ __attribute__((aligned(1024))) float Bs[2 * BN * PITCH];
+  __shared__ __attribute__((aligned(1024))) float As[KS * 2 * BM * PITCH];
+  __shared__ __attribute__((aligned(1024))) float Bs[KS * 2 * BN * PITCH];
 
   if ((int)blockIdx.x >= main_grid) {
-    igemm_side_jobs<T>(g, (int)blockIdx.x - main_grid, As);
+    // the side jobs are written for 256 threads (the second group's waves leave; a barrier counts
+    // the waves that are still there)
+    if (KS == 1 || threadIdx.x < 256) igemm_side_jobs<T>(g, (int)blockIdx.x - main_grid, As);
     return;
   }
 
@@ -140,8 +150,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   const int tile_m = tile / n_tiles_n, tile_n = tile - tile_m * n_tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // thread, wave: within the group of 4 waves; ugrp: the group (wave-uniform)
+  const int tid = KS == 1 ? (int)threadIdx.x : (int)(threadIdx.x & 255), lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+#if defined(__HIP_DEVICE_COMPILE__)
+  const int ugrp = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));
+#else
+  const int ugrp = 0;
+#endif
 
   v16f acc;
 #pragma unroll
@@ -261,7 +277,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
   bool have_old = false;
   if constexpr (DIRECT && !ACT) {
     const int n_pre = n0 + wn0 + (lane & 31);
-    if (g.accumulate && g.out_stride == 1 && g.out_h == g.p && g.out_w == g.q && n_pre < g.n_out) {
+    if (g.accumulate && g.out_stride == 1 && g.out_h == g.p && g.out_w == g.q && n_pre < g.n_out && ugrp == 0) {
       have_old = true;
       const int mb = m0 + wm0 + 4 * (lane >> 5);
       const int left = m0 + BM <= M ? 64 : M - mb;
@@ -316,8 +332,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
         const_cast<void*>(g.w), 0, (int)(uint32_t)((size_t)g.n_out * K * ES), 0x00020000);
     typedef __attribute__((address_space(3))) void* lds_ptr;
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
-    const uint32_t lds_a = (uint32_t)(size_t)As + uwave * 1024, lds_b = (uint32_t)(size_t)Bs + uwave * 1024;
+    const uint32_t lds_a = (uint32_t)(size_t)As + ugrp * (2 * BM * DCHUNK) + uwave * 1024;
+    const uint32_t lds_b = (uint32_t)(size_t)Bs + ugrp * (2 * BN * DCHUNK) + uwave * 1024;
     int kr = 0, kt = 0, c0 = 0;     // tap and channel offset of the chunk whose loads are issued next (uniform)
+    auto advance = [&]() {
+      c0 += BK;
+      if (c0 == g.c) {
+        c0 = 0;
+        if (++kt == g.s) { kt = 0; ++kr; }
+      }
+    };
     auto issue = [&](int kc, int buf) {
       const int tap = kr * g.s + kt;
       const int soff_a = ((kr * g.wd + kt) * g.c + c0) * ES;
@@ -332,17 +356,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       for (int i = 0; i < BI; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, (lds_ptr)(size_t)(lds_b + buf * (BN * DCHUNK) + i * 4096),
                                                  16, b_voff[i], soff_b, 0, 0);
-      c0 += BK;
-      if (c0 == g.c) {
-        c0 = 0;
-        if (++kt == g.s) { kt = 0; ++kr; }
-      }
+#pragma unroll
+      for (int s = 0; s < KS; ++s) advance();   // a group's next chunk is KS further on
     };
     // fragment of a row: 16-byte column c16 sits in slot c16 ^ (row % CPR)
     const int ra_ = wm0 + (lane & 31), rb_ = wn0 + (lane & 31);
     auto compute_direct = [&](int buf) {
-      const float* as = As + buf * (BM * LDD) + ra_ * LDD;
-      const float* bs = Bs + buf * (BN * LDD) + rb_ * LDD;
+      const float* as = As + (ugrp * 2 + buf) * (BM * LDD) + ra_ * LDD;
+      const float* bs = Bs + (ugrp * 2 + buf) * (BN * LDD) + rb_ * LDD;
       // all eight fragment reads of the chunk first, so that the matrix cores never wait for LDS
       constexpr int NG = CPR / 2;              // groups of two 16-byte columns (lanes 0-31 / 32-63)
       float4 af[NG], bf[NG];
@@ -369,6 +390,40 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
     // The barrier that opens chunk kc says two things: every wave's part of chunk kc has
     // landed in LDS (each wave waits for its own loads first), and every wave is done with
     // chunk kc-1, whose stage the loads of chunk kc+1 may now overwrite.
+    if constexpr (KS == 2) {
+      // group u takes the chunks u, u + 2, ...: `mine` of them; both groups pass the same barriers
+      // (those of group 0, which has the odd chunk), a group without a chunk left only waits
+      const int mine = (n_chunks + 1 - ugrp) >> 1, rounds = (n_chunks + 1) >> 1;
+      if (ugrp) advance();
+      if (mine > 0) issue(ugrp, 0);
+      int j = 0;
+      for (; j + 2 <= rounds; j += 2) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (j + 1 < mine) issue(ugrp + 2 * (j + 1), 1);
+        if (j < mine) compute_direct(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (j + 2 < mine) issue(ugrp + 2 * (j + 2), 0);
+        if (j + 1 < mine) compute_direct(1);
+      }
+      if (j < rounds) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (j < mine) compute_direct(0);
+      }
+      // group 1's sums go to group 0 through LDS (16 KB over stage 0 of As, which nobody reads any more)
+      __syncthreads();
+      float* red = As + (wave * 16) * 64 + lane;
+      if (ugrp == 1) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[v * 64] = acc[v];
+      }
+      __syncthreads();
+      if (ugrp == 1) return;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] += red[v * 64];
+    } else {
     issue(0, 0);
     int kc = 0;
     for (; kc + 2 <= n_chunks; kc += 2) {     // whole pairs of chunks: stage 0, then stage 1
@@ -385,6 +440,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(ConvGeom g, int M, int K, in
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
       compute_direct(0);
+    }
     }
 #endif
   } else {
@@ -578,9 +634,18 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
   if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
   if (probe->before) (void)hipEventRecord(probe->before, st);
   const dim3 grid((unsigned)(main_grid + side_blocks));
+  // at most one tile per compute unit and at least eight chunks of K: two groups of waves per tile
+  // (a function of the shape only)
+  constexpr int BKE = direct_chunk_bytes((int)sizeof(T)) / (int)sizeof(T);
+  const bool split = LOADER == L_DIRECT && sizeof(T) == 4 && !(g.bias || g.relu) && tiles <= 256 && K >= 8 * BKE;
   if (g.bias || g.relu)
     hipLaunchKernelGGL((igemm_kernel<LOADER, T, true>), grid, dim3(256), 0, st, g, M, K, tn, (int)tiles, main_grid);
-  else
+  else if constexpr (LOADER == L_DIRECT && sizeof(T) == 4) {
+    if (split)
+      hipLaunchKernelGGL((igemm_kernel<LOADER, T, false, 2>), grid, dim3(512), 0, st, g, M, K, tn, (int)tiles, main_grid);
+    else
+      hipLaunchKernelGGL((igemm_kernel<LOADER, T, false>), grid, dim3(256), 0, st, g, M, K, tn, (int)tiles, main_grid);
+  } else
     hipLaunchKernelGGL((igemm_kernel<LOADER, T, false>), grid, dim3(256), 0, st, g, M, K, tn, (int)tiles, main_grid);
   if (probe->after) (void)hipEventRecord(probe->after, st);
   return hipGetLastError();
