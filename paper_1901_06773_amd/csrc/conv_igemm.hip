@@ -605,7 +605,7 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
 }
 
 template <int LOADER, class T>
-hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchProbe* probe) {
+hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, LaunchProbe* probe) {
   const int tm = (M + BM - 1) / BM, tn = (g.n_out + BN - 1) / BN;
   const long tiles = (long)tm * tn;
   if (tiles <= 0 || tiles > (1L << 30)) return hipErrorInvalidValue;
@@ -632,12 +632,13 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
     side_blocks += (long)((g.flip.cin + 31) / 32) * ((g.flip.cout + 31) / 32) * g.flip.r * g.flip.s;
   }
   if (main_grid + side_blocks > (1L << 30)) return hipErrorInvalidValue;
-  if (probe->before) (void)hipEventRecord(probe->before, st);
   const dim3 grid((unsigned)(main_grid + side_blocks));
   // at most one tile per compute unit and at least eight chunks of K: two groups of waves per tile
   // (a function of the shape only)
   constexpr int BKE = direct_chunk_bytes((int)sizeof(T)) / (int)sizeof(T);
   const bool split = LOADER == L_DIRECT && sizeof(T) == 4 && !(g.bias || g.relu) && tiles <= 256 && K >= 8 * BKE;
+  if (split) probe->variant = V_IGEMM_DIRECT_2G;
+  if (probe->before) (void)hipEventRecord(probe->before, st);
   if (g.bias || g.relu)
     hipLaunchKernelGGL((igemm_kernel<LOADER, T, true>), grid, dim3(256), 0, st, g, M, K, tn, (int)tiles, main_grid);
   else if constexpr (LOADER == L_DIRECT && sizeof(T) == 4) {
@@ -656,7 +657,7 @@ hipError_t launch(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchP
 const char* conv_variant_name(int v) {
   static const char* names[V_COUNT] = {"igemm_kernel<fast>", "igemm_kernel<generic>", "wgrad_kernel<fast>",
                                        "wgrad_kernel<generic>", "igemm_kernel<direct>", "wgrad_kernel<direct>",
-                                       "wgrad_bf16_kernel", "igemm_bf16_kernel"};
+                                       "wgrad_bf16_kernel", "igemm_bf16_kernel", "igemm_kernel<direct, two groups>"};
   return (v >= 0 && v < V_COUNT) ? names[v] : "?";
 }
 

@@ -102,7 +102,7 @@ hipError_t conv_igemm(const ConvGeom& g, hipStream_t st, LaunchProbe* probe = nu
 bool conv_igemm_bf16_takes(const ConvGeom& g, long M, long K);
 hipError_t conv_igemm_bf16(const ConvGeom& g, int M, int K, hipStream_t st, const LaunchProbe* probe);
 enum { V_IGEMM_FAST = 0, V_IGEMM_GENERIC, V_WGRAD_FAST, V_WGRAD_GENERIC, V_IGEMM_DIRECT, V_WGRAD_DIRECT, V_WGRAD_BF16,
-       V_IGEMM_BF16, V_COUNT };
+       V_IGEMM_BF16, V_IGEMM_DIRECT_2G, V_COUNT };
 const char* conv_variant_name(int v);
 
 // dw[co][(r,t,ci)] = sum_{img,p,q} dy[img,p,q,co] * x[img, p*stride+r-pad, q*stride+t-pad, ci]
