@@ -749,7 +749,14 @@ WgradCfg choose(long Mrows, int cin, int cout, int r, int s, int dtype) {
   c.tiles_j = (int)((J + BN - 1) / BN);
   const long tiles = (long)c.tiles_co * c.tiles_j;
   const long chunks = (Mrows + BKM - 1) / BKM;
-  long splits = 768 / tiles;
+  // One round of workgroups: 512 (two per CU) for the shapes the staged loaders take.  Alone the kernel
+  // is faster with 768 (measured 86 / 96 / 99 / 88 TFLOP/s at 512 / 768 / 1024 / 1280 when the choice was
+  // made; 93 against 102 now), but it runs beside the data gradient and the batch norm of the next layer
+  // on a stream of its own, and there two workgroups per CU leave the others room: ResNet-152 at
+  // minibatch 41 1220 images/s against 1198 (384 / 448 / 512 / 576 / 640 / 768 / 1024: 1167 / 1216 / 1220 /
+  // 1207 / 1213 / 1198 / 1202).  The per-element loader (3-channel stem, nothing beside it) keeps 768.
+  const long target = cin % 64 ? 768 : 512;
+  long splits = target / tiles;
   const long max_splits = chunks / 8 > 0 ? chunks / 8 : 1;
   if (splits > max_splits) splits = max_splits;
   if (splits > 1024) splits = 1024;
