@@ -293,8 +293,10 @@ constexpr int SL_CH = SL_TPR * 4;
 constexpr int SL_ROWS = THREADS / SL_TPR;   // rows per trip
 constexpr int SL_BATCH = 16;                // 16-byte partial loads a thread has in flight
 constexpr int SL_U = 4;                     // rows of a thread in flight in the apply loop
-constexpr int SL_WGS = 512;                 // workgroups of a launch, about (fewer: too little in flight
-                                            // per compute unit; more: every one re-reads its slice's partials)
+constexpr int SL_WGS = 256;                 // workgroups of a launch, about: one per CU.  Every workgroup re-reads its
+                                            // slice's partials, and in the step the kernel shares the chip with a weight
+                                            // gradient (ResNet-152 at minibatch 41, images/s at 192 / 256 / 320 / 384 /
+                                            // 512 / 768 / 1024: 1215 / 1233 / 1216 / 1218 / 1223 / 1219 / 1218)
 constexpr int kSliceMaxSlabs = 512;         // beyond: the separate finishing launch
 constexpr int kSlicePhasesMax = 16;
 
