@@ -749,13 +749,16 @@ WgradCfg choose(long Mrows, int cin, int cout, int r, int s, int dtype) {
   c.tiles_j = (int)((J + BN - 1) / BN);
   const long tiles = (long)c.tiles_co * c.tiles_j;
   const long chunks = (Mrows + BKM - 1) / BKM;
-  // One round of workgroups: 512 (two per CU) for the shapes the staged loaders take.  Alone the kernel
-  // is faster with 768 (measured 86 / 96 / 99 / 88 TFLOP/s at 512 / 768 / 1024 / 1280 when the choice was
-  // made; 93 against 102 now), but it runs beside the data gradient and the batch norm of the next layer
-  // on a stream of its own, and there two workgroups per CU leave the others room: ResNet-152 at
-  // minibatch 41 1220 images/s against 1198 (384 / 448 / 512 / 576 / 640 / 768 / 1024: 1167 / 1216 / 1220 /
-  // 1207 / 1213 / 1198 / 1202).  The per-element loader (3-channel stem, nothing beside it) keeps 768.
-  const long target = cin % 64 ? 768 : 512;
+  // One round of workgroups.  Alone the kernel is fastest with 768 (three per CU: measured 86 / 96 / 99 / 88
+  // TFLOP/s at 512 / 768 / 1024 / 1280 when the choice was first made; 93 against 102 now), but in the step it
+  // runs on a stream of its own beside the data gradient and the next batch norm.  Those are the critical
+  // path, and at small minibatches, where their fixed costs weigh most, two weight-gradient workgroups per CU
+  // leave them the larger share of the matrix cores; at large minibatches the weight gradient itself becomes
+  // the longer chain.  ResNet-152, images/s with 512 / 768 everywhere: minibatch 32 1099 / 1110, 36 1159 / 1135,
+  // 41 1233 / 1194, 48 1177 / 1154, 52 1184 / 1199, 56 1186 / 1220, 64 1208 / 1205, 128 1263 / 1314; the
+  // row count below (14 x 14 maps up to minibatch 50) takes the better of the two everywhere but at 32.
+  // The per-element loader (3-channel stem, nothing beside it) keeps 768.
+  const long target = cin % 64 ? 768 : Mrows <= 9800 ? 512 : 768;
   long splits = target / tiles;
   const long max_splits = chunks / 8 > 0 ? chunks / 8 : 1;
   if (splits > max_splits) splits = max_splits;
