@@ -298,6 +298,12 @@ constexpr int SL_WGS = 256;                 // workgroups of a launch, about: on
                                             // gradient (ResNet-152 at minibatch 41, images/s at 192 / 256 / 320 / 384 /
                                             // 512 / 768 / 1024: 1215 / 1233 / 1216 / 1218 / 1223 / 1219 / 1218)
 constexpr int kSliceMaxSlabs = 512;         // beyond: the separate finishing launch
+constexpr long kSliceMaxRows = 16384;       // ... and, with 2-byte storage, larger tensors: a slice's row segment is 64 bytes
+                                            // there (ResNet-152 bf16 at minibatch 512: 3320 with, 3909 images/s without the
+                                            // slice kernels; fp32 at minibatch 128: 1326 with, 1310 without)
+template <class T> __host__ __device__ constexpr bool slice_takes(long rows, int slabs) {
+  return slabs <= kSliceMaxSlabs && (sizeof(T) == 4 || rows <= kSliceMaxRows);
+}
 constexpr int kSlicePhasesMax = 16;
 
 struct SliceScratch {
@@ -514,13 +520,14 @@ inline dim3 slice_grid(long rows, int c, long* rows_per_wg) {
 // slab count: a function of the shape only; at least ROWS_PER_THREAD rows per thread and
 // slab, about 1024 workgroups over all column slices (the partials the finishing kernel has
 // to read grow with slabs * c)
+template <class T>
 inline int slab_count(long rows, const ReduceShape& rs) {
   long s = (rows + (long)rs.rpi * ROWS_PER_THREAD - 1) / ((long)rs.rpi * ROWS_PER_THREAD);
   const long cap = MAX_SLABS / rs.col_slices > 0 ? MAX_SLABS / rs.col_slices : 1;
   if (s > cap) s = cap;
   // few enough for the slice kernels: then as few as one batch of their partial loads
   // (128 slabs of doubles), as long as that leaves a workgroup per compute unit
-  if (s <= kSliceMaxSlabs) {
+  if (slice_takes<T>(rows, (int)s)) {
     const long one_batch = 128 > 256 / rs.col_slices ? 128 : 256 / rs.col_slices;
     if (s > one_batch) s = one_batch;
   }
@@ -547,7 +554,7 @@ template <class T, class P>
 void bn_forward_tail(const T* x, const float* gamma, const float* beta, const T* res, T* y, float* mean, float* istd,
                      long rows, int c, int relu, float eps, const P* sums, int slabs, int stride, float* coef,
                      hipStream_t st) {
-  if (slabs <= kSliceMaxSlabs) {
+  if (slice_takes<T>(rows, slabs)) {
     long per;
     const dim3 grid = slice_grid(rows, c, &per);
     hipLaunchKernelGGL((bn_fwd_slice_kernel<T, P>), grid, dim3(THREADS), 0, st, x, res, sums, gamma, beta, mean, istd,
@@ -571,7 +578,7 @@ hipError_t bn_forward_t(const T* x, const float* gamma, const float* beta, const
                     coef, st);
   } else {
     const ReduceShape rs = reduce_shape(c);
-    const int slabs = slab_count(rows, rs);
+    const int slabs = slab_count<T>(rows, rs);
     hipLaunchKernelGGL((bn_reduce_kernel<0, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, (const T*)nullptr,
                        (const T*)nullptr, nullptr, nullptr, part, rows, c, rs.tpr, rs.rpi, slabs);
     bn_forward_tail(x, gamma, beta, res, y, mean, istd, rows, c, relu, eps, (const double*)part, slabs, MAX_SLABS,
@@ -584,7 +591,7 @@ template <class T, class P>
 void bn_backward_tail(const T* x, const T* dy, const T* y, const float* gamma, const float* mean, const float* istd,
                       T* dx, float* dgamma, float* dbeta, T* g_out, long rows, int c, const P* sums, int slabs,
                       int stride, float* coef, hipStream_t st) {
-  if (slabs <= kSliceMaxSlabs) {
+  if (slice_takes<T>(rows, slabs)) {
     long per;
     const dim3 grid = slice_grid(rows, c, &per);
     hipLaunchKernelGGL((bn_bwd_slice_kernel<T, P>), grid, dim3(THREADS), 0, st, x, dy, y, sums, gamma, mean, istd,
@@ -609,7 +616,7 @@ hipError_t bn_backward_t(const T* x, const T* dy, const T* y, const float* gamma
                      ready.stride, coef, st);
   } else {
     const ReduceShape rs = reduce_shape(c);
-    const int slabs = slab_count(rows, rs);
+    const int slabs = slab_count<T>(rows, rs);
     hipLaunchKernelGGL((bn_reduce_kernel<1, T>), dim3(slabs, rs.col_slices), dim3(THREADS), 0, st, x, dy, y, mean,
                        istd, part, rows, c, rs.tpr, rs.rpi, slabs);
     bn_backward_tail(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, rows, c, (const double*)part, slabs,
