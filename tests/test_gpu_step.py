@@ -658,6 +658,30 @@ def test_resnet34_under_4_gib_swaps_and_keeps_the_bits():
     assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 0
 
 
+def test_vgg16_at_full_size_swapping_everything_keeps_the_bits():
+    """VGG-16 of the paper's Table 1 at 224 x 224 (conv + bias + ReLU in one launch, 2 x 2 max-pools, the
+    25088 -> 4096 fully connected layer): every map offloaded and brought back, under 2.5 GiB at minibatch
+    16, against the resident run.  (The planner itself swaps nothing here: the backward step of the second
+    convolution alone needs nearly the whole resident peak, so swapping buys this network next to nothing.)"""
+    b = B()
+    net = S.vgg16()
+    k = 16
+    params = S.init_params(net)
+    chw = (net.in_c, net.in_h, net.in_w)
+    probe = b.Context(net.as_array(), chw)
+    plan = probe.plan_swaps(k, int(2.5 * GiB), b.PLAN_NAIVE_ALL)
+    resident = probe.plan_swaps(k, 1 << 40, b.PLAN_NONE)
+    probe.close()
+    assert plan["n_swapped"] == plan["n_maps"] > 0
+    out = run_gpu(net, params, k, b.PLAN_NAIVE_ALL, int(2.5 * GiB), steps=2, host=plan["host_bytes"] + 64 * MiB)
+    assert out["stats"]["bytes_out"] == plan["bytes_swapped"] > 0
+    assert out["stats"]["peak_pool_bytes"] <= int(2.5 * GiB)
+    ref = run_gpu(net, params, k, b.PLAN_NONE, int(resident["peak_bytes"] * 1.05) + 64 * MiB, steps=2)
+    for a, r in zip(out["losses"], ref["losses"]):
+        assert np.isfinite(a) and np.float32(a).view(np.uint32) == np.float32(r).view(np.uint32)
+    bit_equal(out["weights"], ref["weights"], "weights")
+
+
 def test_config_resnet152_bf16_under_24_gib():
     """configs[4]: ResNet-152 with bf16 storage, 24 GiB; at minibatch 320 (the resident maximum
     is 291) so that the resident reference run stays small."""
