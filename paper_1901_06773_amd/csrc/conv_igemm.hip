@@ -371,31 +371,53 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
     };
     // fragment of a row: 16-byte column c16 sits in slot c16 ^ (row % CPR)
     const int ra_ = wm0 + (lane & 31), rb_ = wn0 + (lane & 31);
-    auto compute_direct = [&](int buf) {
+    // One chunk out of LDS stage `buf`.  A group = two 16-byte columns of a row (lanes 0-31 / 32-63) = four
+    // MFMAs.  The reads of group g + 1 are issued between the MFMAs of group g, and the last group's MFMAs are
+    // held back (pa, pb) until the next chunk's barrier has been passed and its first reads are on their way:
+    // the matrix cores have work queued while the wave waits at the barrier and for LDS.  The products are
+    // added in the same order as ever.  (Measured against "all eight reads first, then sixteen MFMAs":
+    // 256->256 3x3 at 14 x 14, minibatch 41: 82.6 -> 79.8 us with the interleaved reads alone.)
+    float4 pa = make_float4(0.f, 0.f, 0.f, 0.f), pb = pa;
+    auto mm = [&](const float4& a, const float4& b, int half) {
+      if constexpr (ES == 4) {
+        if (half != 1) {
+          acc = mfma32x32x2(a.x, b.x, acc);
+          acc = mfma32x32x2(a.y, b.y, acc);
+        }
+        if (half != 0) {
+          acc = mfma32x32x2(a.z, b.z, acc);
+          acc = mfma32x32x2(a.w, b.w, acc);
+        }
+      } else {
+        if (half != 0) acc = mfma32x32x16bf(a, b, acc);
+      }
+    };
+    auto compute_direct = [&](int buf, bool prev) {
       const float* as = As + (ugrp * 2 + buf) * (BM * LDD) + ra_ * LDD;
       const float* bs = Bs + (ugrp * 2 + buf) * (BN * LDD) + rb_ * LDD;
-      // all eight fragment reads of the chunk first, so that the matrix cores never wait for LDS
-      constexpr int NG = CPR / 2;              // groups of two 16-byte columns (lanes 0-31 / 32-63)
+      constexpr int NG = CPR / 2;
       float4 af[NG], bf[NG];
-#pragma unroll
-      for (int g8 = 0; g8 < NG; ++g8) {
+      auto rd = [&](int g8) {
         const int c16 = g8 * 2 + (lane >> 5);
         af[g8] = *reinterpret_cast<const float4*>(as + ((c16 ^ (ra_ & (CPR - 1))) << 2));
         bf[g8] = *reinterpret_cast<const float4*>(bs + ((c16 ^ (rb_ & (CPR - 1))) << 2));
-      }
-      __builtin_amdgcn_sched_barrier(0);      // keeps the scheduler from sinking the reads between the MFMAs again
+      };
+      rd(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (prev) mm(pa, pb, 2);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int g8 = 0; g8 < NG; ++g8) {
-        if constexpr (ES == 4) {
-          acc = mfma32x32x2(af[g8].x, bf[g8].x, acc);
-          acc = mfma32x32x2(af[g8].y, bf[g8].y, acc);
-          acc = mfma32x32x2(af[g8].z, bf[g8].z, acc);
-          acc = mfma32x32x2(af[g8].w, bf[g8].w, acc);
-        } else {
-          acc = mfma32x32x16bf(af[g8], bf[g8], acc);
-        }
+      for (int g8 = 0; g8 + 1 < NG; ++g8) {
+        mm(af[g8], bf[g8], 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(g8 + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm(af[g8], bf[g8], 1);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);      // ... and from moving the next chunk's wait and barrier up among them
+      pa = af[NG - 1];
+      pb = bf[NG - 1];
+      __builtin_amdgcn_sched_barrier(0);      // nothing of the next chunk's wait and barrier moves up among them
     };
     // The barrier that opens chunk kc says two things: every wave's part of chunk kc has
     // landed in LDS (each wave waits for its own loads first), and every wave is done with
@@ -411,17 +433,18 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         if (j + 1 < mine) issue(ugrp + 2 * (j + 1), 1);
-        if (j < mine) compute_direct(0);
+        if (j < mine) compute_direct(0, j > 0);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         if (j + 2 < mine) issue(ugrp + 2 * (j + 2), 0);
-        if (j + 1 < mine) compute_direct(1);
+        if (j + 1 < mine) compute_direct(1, true);
       }
       if (j < rounds) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        if (j < mine) compute_direct(0);
+        if (j < mine) compute_direct(0, j > 0);
       }
+      if (mine > 0) mm(pa, pb, 2);
       // group 1's sums go to group 0 through LDS (16 KB over stage 0 of As, which nobody reads any more)
       __syncthreads();
       float* red = As + (wave * 16) * 64 + lane;
@@ -440,17 +463,18 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
       __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads are in LDS
       __syncthreads();
       issue(kc + 1, 1);
-      compute_direct(0);
+      compute_direct(0, kc > 0);
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
       if (kc + 2 < n_chunks) issue(kc + 2, 0);
-      compute_direct(1);
+      compute_direct(1, true);
     }
     if (kc < n_chunks) {                      // an odd number of chunks: the last one sits in stage 0
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
-      compute_direct(0);
+      compute_direct(0, kc > 0);
     }
+    mm(pa, pb, 2);                            // n_chunks >= 1
     }
 #endif
   } else {
