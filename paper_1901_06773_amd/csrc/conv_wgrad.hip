@@ -322,13 +322,48 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
     const int half = lane >> 5;
     const float* a_rd = As + half * 64 + ((wm0 + (lane & 31)) ^ (half << 5));
     const float* b_rd = Bs + half * 64 + ((wn0 + (lane & 31)) ^ (half << 5));
-    auto compute_direct = [&](int buf) {
+    // Groups of four MFMAs (eight rows of the chunk): the operands of group g + 1 are read between the MFMAs
+    // of group g, and the last group's MFMAs are held back (pa, pb) until the next chunk's barrier has been
+    // passed and its first reads are on their way.  Same order of additions.
+    constexpr int NG = BKM / 8;
+    float pa[4] = {0.f, 0.f, 0.f, 0.f}, pb[4] = {0.f, 0.f, 0.f, 0.f};
+    auto mm4 = [&](const float (&a)[4], const float (&b)[4], int half) {
+      if (half != 1) {
+        acc = mfma32x32x2(a[0], b[0], acc);
+        acc = mfma32x32x2(a[1], b[1], acc);
+      }
+      if (half != 0) {
+        acc = mfma32x32x2(a[2], b[2], acc);
+        acc = mfma32x32x2(a[3], b[3], acc);
+      }
+    };
+    auto compute_direct = [&](int buf, bool prev) {
       const float* as = a_rd + buf * (BKM * 64);
       const float* bs = b_rd + buf * (BKM * 64);
-      // (reading all 32 operands of the chunk ahead of its MFMAs, which pays in the forward
-      // kernel, measured slower here: 91.9 against 93.0 TFLOP/s)
+      float af[NG][4], bf[NG][4];
+      auto rd = [&](int g) {
 #pragma unroll
-      for (int kk = 0; kk < BKM; kk += 2) acc = mfma32x32x2(as[kk * 64], bs[kk * 64], acc);
+        for (int u = 0; u < 4; ++u) {
+          af[g][u] = as[(g * 8 + u * 2) * 64];
+          bf[g][u] = bs[(g * 8 + u * 2) * 64];
+        }
+      };
+      rd(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (prev) mm4(pa, pb, 2);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g + 1 < NG; ++g) {
+        mm4(af[g], bf[g], 0);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(g + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mm4(af[g], bf[g], 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { pa[u] = af[NG - 1][u]; pb[u] = bf[NG - 1][u]; }
+      __builtin_amdgcn_sched_barrier(0);
     };
     if (n_chunks > 0) {
       issue(0, 0);
@@ -337,17 +372,18 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradGeom g, int Mrows, int 
         __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's part of chunk kc is in LDS
         __syncthreads();                        // everybody's is, and chunk kc-1 has been read by all
         issue(kc + 1, 1);
-        compute_direct(0);
+        compute_direct(0, kc > 0);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
         if (kc + 2 < n_chunks) issue(kc + 2, 0);
-        compute_direct(1);
+        compute_direct(1, true);
       }
       if (kc < n_chunks) {                      // an odd number of chunks: the last one sits in stage 0
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        compute_direct(0);
+        compute_direct(0, kc > 0);
       }
+      mm4(pa, pb, 2);
     }
 #endif
   } else if constexpr (FAST) {
