@@ -375,8 +375,10 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
     // MFMAs.  The reads of group g + 1 are issued between the MFMAs of group g, and the last group's MFMAs are
     // held back (pa, pb) until the next chunk's barrier has been passed and its first reads are on their way:
     // the matrix cores have work queued while the wave waits at the barrier and for LDS.  The products are
-    // added in the same order as ever.  (Measured against "all eight reads first, then sixteen MFMAs":
-    // 256->256 3x3 at 14 x 14, minibatch 41: 82.6 -> 79.8 us with the interleaved reads alone.)
+    // added in the same order as ever.  The next chunk's global loads are issued after the held-back MFMAs, so
+    // that nothing stands between the barrier and queued matrix work.  (Measured against "all eight reads
+    // first, then sixteen MFMAs", 256->256 3x3 at 14 x 14, minibatch 41: 82.6 -> 79.8 us with the interleaved
+    // reads, 79.4 with the held-back group, 78.6 with the loads behind it; two held-back groups: 79.7.)
     float4 pa = make_float4(0.f, 0.f, 0.f, 0.f), pb = pa;
     auto mm = [&](const float4& a, const float4& b, int half) {
       if constexpr (ES == 4) {
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
         if (half != 0) acc = mfma32x32x16bf(a, b, acc);
       }
     };
-    auto compute_direct = [&](int buf, bool prev) {
+    auto compute_direct = [&](int buf, bool prev, int next_kc = -1) {
       const float* as = As + (ugrp * 2 + buf) * (BM * LDD) + ra_ * LDD;
       const float* bs = Bs + (ugrp * 2 + buf) * (BN * LDD) + rb_ * LDD;
       constexpr int NG = CPR / 2;
@@ -405,6 +407,8 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
       rd(0);
       __builtin_amdgcn_sched_barrier(0);
       if (prev) mm(pa, pb, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      if (next_kc >= 0) issue(next_kc, buf ^ 1);   // the next chunk's loads, once the matrix cores have work queued
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int g8 = 0; g8 + 1 < NG; ++g8) {
@@ -432,12 +436,10 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
       for (; j + 2 <= rounds; j += 2) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        if (j + 1 < mine) issue(ugrp + 2 * (j + 1), 1);
-        if (j < mine) compute_direct(0, j > 0);
+        if (j < mine) compute_direct(0, j > 0, j + 1 < mine ? ugrp + 2 * (j + 1) : -1);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        if (j + 2 < mine) issue(ugrp + 2 * (j + 2), 0);
-        if (j + 1 < mine) compute_direct(1, true);
+        if (j + 1 < mine) compute_direct(1, true, j + 2 < mine ? ugrp + 2 * (j + 2) : -1);
       }
       if (j < rounds) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -462,12 +464,10 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
     for (; kc + 2 <= n_chunks; kc += 2) {     // whole pairs of chunks: stage 0, then stage 1
       __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's loads are in LDS
       __syncthreads();
-      issue(kc + 1, 1);
-      compute_direct(0, kc > 0);
+      compute_direct(0, kc > 0, kc + 1);
       __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();
-      if (kc + 2 < n_chunks) issue(kc + 2, 0);
-      compute_direct(1, true);
+      compute_direct(1, true, kc + 2 < n_chunks ? kc + 2 : -1);
     }
     if (kc < n_chunks) {                      // an odd number of chunks: the last one sits in stage 0
       __builtin_amdgcn_s_waitcnt(0x0F70);
