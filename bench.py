@@ -61,7 +61,7 @@ def parse():
 # WRITE_SIZE runs of this script, scaled by what the same counters read for sgd_kernel
 # (profiles/resnet152_k41_hbm_traffic_pmc.txt).  A figure of that profile, not of this run: counters
 # need the profiler.  Known for the profiled workload only.
-PROFILED_TRAFFIC_BYTES = {("resnet152", 41, 8.0): 71.2e6}
+PROFILED_TRAFFIC_BYTES = {("resnet152", 41, 8.0): 71.3e6}
 
 
 def log(*a):
