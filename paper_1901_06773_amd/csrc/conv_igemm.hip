@@ -545,7 +545,8 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
     // [y > 0] and leave the sums of g and g * xhat over the wave's 32 rows for that batch
     // norm's backward pass (dense output: element (m, n) of x and y sits at m * n_out + n).
     // (Fetching y and x before the K loop instead, to hide their latency, measured slower with
-    // the weight-gradient stream beside: 1141 against 1164 images/s.)
+    // the weight-gradient stream beside: 1141 against 1164 images/s; in an instance of its own, so that
+    // the other launches keep their registers, and behind the first chunk's loads: 1260 against 1268.)
     const bool col = n < g.n_out;
     const float mu = col ? g.bnb.mean[n] : 0.f, is = col ? g.bnb.istd[n] : 0.f;
     // the lane's first row; its other rows lie dr = 8*(v/4) + v%4 rows further on, a distance
