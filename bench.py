@@ -73,8 +73,9 @@ def main():
     faulthandler.enable()
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by data parallelism, see DESIGN.md); "
-              "--gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path would shard by data parallelism: one plan, pool "
+              "and set of streams per GPU, one all-reduce of the weight gradients per iteration); --gpus must be 1",
+              file=sys.stderr)
         sys.exit(2)
     import numpy as np  # noqa: F401
     import torch
