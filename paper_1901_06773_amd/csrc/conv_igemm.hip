@@ -378,7 +378,9 @@ __global__ __launch_bounds__(256 * KS) void igemm_kernel(ConvGeom g, int M, int 
     // added in the same order as ever.  The next chunk's global loads are issued after the held-back MFMAs, so
     // that nothing stands between the barrier and queued matrix work.  (Measured against "all eight reads
     // first, then sixteen MFMAs", 256->256 3x3 at 14 x 14, minibatch 41: 82.6 -> 79.8 us with the interleaved
-    // reads, 79.4 with the held-back group, 78.6 with the loads behind it; two held-back groups: 79.7.)
+    // reads, 79.4 with the held-back group, 78.6 with the loads behind it; two held-back groups: 79.7; the four loads
+    // spread over the four groups instead of issued together: 82.3.  With no loads at all after the second chunk
+    // the same launch takes 71.3 us: the global -> LDS traffic costs a tenth of the kernel.)
     float4 pa = make_float4(0.f, 0.f, 0.f, 0.f), pb = pa;
     auto mm = [&](const float4& a, const float4& b, int half) {
       if constexpr (ES == 4) {
