@@ -378,6 +378,22 @@ int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const float* gam
                   const float* mean, const float* istd, void* dx, float* dgamma, float* dbeta,
                   void* g_out, int rows, int c, void* workspace, int dtype, void* stream);
 
+/* The parameter-free layers of the evaluated networks (Sec. 6.1: residual networks, VGG-16), which the
+ * unfolded iteration of Sec. 3.1 runs like any other step; the paper does not define them, the
+ * definitions are the textbook ones.  Max-pool over r x r windows (padding never wins, the first maximum
+ * in row-major window order takes the gradient; c a multiple of 4); mean over the hw positions of an
+ * image; softmax cross-entropy: loss_rows[i] = logsumexp(z_i) - z_i[label_i] (NaN for a label outside
+ * [0, classes)), *loss = their mean, dz = (softmax(z) - onehot) / n; loss_rows and dz may each be NULL
+ * (then loss, too, is not written).  labels, loss_rows (n floats) and loss (1 float) are device memory. */
+int acc_op_maxpool_fwd(const void* x, void* y, int n, int h, int wd, int c, int r, int stride, int pad,
+                       int dtype, void* stream);
+int acc_op_maxpool_bwd(const void* x, const void* dy, void* dx, int n, int h, int wd, int c, int r,
+                       int stride, int pad, int accumulate, int dtype, void* stream);
+int acc_op_gap_fwd(const void* x, void* y, int n, int hw, int c, int dtype, void* stream);
+int acc_op_gap_bwd(const void* dy, void* dx, int n, int hw, int c, int accumulate, int dtype, void* stream);
+int acc_op_softmax_ce(const void* z, const int32_t* labels, float* loss_rows, float* loss, void* dz, int n,
+                      int classes, int dtype, void* stream);
+
 
 /* ---- for callers that cannot allocate --------------------------------------------- */
 /* acc_op_bn_fwd() without the workspace argument, for code that may not call hipMalloc or

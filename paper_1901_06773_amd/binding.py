@@ -156,6 +156,11 @@ _PROTOS = {
     "acc_op_bn_fwd": (_I, [_VP] * 7 + [_I, _I, _I, _F, _VP, _I, _VP]),
     "acc_op_bn_bwd": (_I, [_VP] * 10 + [_I, _I, _VP, _I, _VP]),
     "acc_op_bn_fwd_noalloc": (_I, [_VP] * 7 + [_I, _I, _I, _F, _I, _VP]),
+    "acc_op_maxpool_fwd": (_I, [_VP, _VP] + [_I] * 8 + [_VP]),
+    "acc_op_maxpool_bwd": (_I, [_VP, _VP, _VP] + [_I] * 9 + [_VP]),
+    "acc_op_gap_fwd": (_I, [_VP, _VP, _I, _I, _I, _I, _VP]),
+    "acc_op_gap_bwd": (_I, [_VP, _VP, _I, _I, _I, _I, _I, _VP]),
+    "acc_op_softmax_ce": (_I, [_VP] * 5 + [_I, _I, _I, _VP]),
 }
 for _name, (_res, _args) in _PROTOS.items():
     _fn = getattr(_lib, _name)
@@ -531,3 +536,50 @@ def op_bn_bwd(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, ws):
                             _dtype_of(x), _stream_ptr(torch))
     if rc != ACC_OK:
         raise AccError(rc, "acc_op_bn_bwd")
+
+
+def op_maxpool_fwd(x, y, r, stride, pad):
+    """x [n, h, w, c] -> y [n, ho, wo, c] (torch device tensors, NHWC)."""
+    import torch
+    n, h, w, c = x.shape
+    rc = _lib.acc_op_maxpool_fwd(x.data_ptr(), y.data_ptr(), n, h, w, c, r, stride, pad, _dtype_of(x), _stream_ptr(torch))
+    if rc != ACC_OK:
+        raise AccError(rc, "acc_op_maxpool_fwd")
+
+
+def op_maxpool_bwd(x, dy, dx, r, stride, pad, accumulate=False):
+    import torch
+    n, h, w, c = x.shape
+    rc = _lib.acc_op_maxpool_bwd(x.data_ptr(), dy.data_ptr(), dx.data_ptr(), n, h, w, c, r, stride, pad,
+                                 1 if accumulate else 0, _dtype_of(x), _stream_ptr(torch))
+    if rc != ACC_OK:
+        raise AccError(rc, "acc_op_maxpool_bwd")
+
+
+def op_gap_fwd(x, y):
+    """x [n, h, w, c] -> y [n, c]: the mean over the positions of an image."""
+    import torch
+    n, h, w, c = x.shape
+    rc = _lib.acc_op_gap_fwd(x.data_ptr(), y.data_ptr(), n, h * w, c, _dtype_of(x), _stream_ptr(torch))
+    if rc != ACC_OK:
+        raise AccError(rc, "acc_op_gap_fwd")
+
+
+def op_gap_bwd(dy, dx, accumulate=False):
+    import torch
+    n, h, w, c = dx.shape
+    rc = _lib.acc_op_gap_bwd(dy.data_ptr(), dx.data_ptr(), n, h * w, c, 1 if accumulate else 0, _dtype_of(dx),
+                             _stream_ptr(torch))
+    if rc != ACC_OK:
+        raise AccError(rc, "acc_op_gap_bwd")
+
+
+def op_softmax_ce(z, labels, loss_rows, loss, dz):
+    """z [n, classes], labels int32 [n] (device); loss_rows [n] / loss [1] fp32 and dz like z, each optional."""
+    import torch
+    n, classes = z.shape
+    rc = _lib.acc_op_softmax_ce(z.data_ptr(), labels.data_ptr(), loss_rows.data_ptr() if loss_rows is not None else None,
+                                loss.data_ptr() if loss is not None else None, dz.data_ptr() if dz is not None else None,
+                                n, classes, _dtype_of(z), _stream_ptr(torch))
+    if rc != ACC_OK:
+        raise AccError(rc, "acc_op_softmax_ce")

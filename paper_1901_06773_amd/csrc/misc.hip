@@ -380,15 +380,17 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(const T* __restrict
   float se = 0.f;
   for (int j = threadIdx.x; j < classes; j += THREADS) se += expf(Elem<T>::load(zi + j) - mx);
   se = block_sum(se, sh);
-  const float lse = mx + logf(se);
+  // everything relative to the row maximum: z - mx is exact for the logits near the maximum (the only ones
+  // that matter), so neither the loss nor a probability close to one loses digits to the size of the logits
+  const float lg = logf(se);
   const int lab = labels[i];
   // a label outside [0, classes) reads nothing: the row's loss is NaN and its gradient has no one-hot term
   const bool lab_ok = (unsigned)lab < (unsigned)classes;
-  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lab_ok ? lse - Elem<T>::load(zi + lab) : NAN;
+  if (loss_rows && threadIdx.x == 0) loss_rows[i] = lab_ok ? lg - (Elem<T>::load(zi + lab) - mx) : NAN;
   if (dz) {
     const float inv_n = 1.f / (float)n;
     for (int j = threadIdx.x; j < classes; j += THREADS)
-      Elem<T>::store(dz + (size_t)i * classes + j, (expf(Elem<T>::load(zi + j) - lse) - (j == lab ? 1.f : 0.f)) * inv_n);
+      Elem<T>::store(dz + (size_t)i * classes + j, (expf((Elem<T>::load(zi + j) - mx) - lg) - (j == lab ? 1.f : 0.f)) * inv_n);
   }
 }
 

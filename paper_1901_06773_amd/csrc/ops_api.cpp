@@ -137,3 +137,35 @@ extern "C" int acc_op_bn_bwd(const void* x, const void* dy, const void* y, const
   return status(bn_backward(x, dy, y, gamma, mean, istd, dx, dgamma, dbeta, g_out, rows, c, workspace, dtype,
                             (hipStream_t)stream));
 }
+
+extern "C" int acc_op_maxpool_fwd(const void* x, void* y, int n, int h, int wd, int c, int r, int stride, int pad,
+                                  int dtype, void* stream) {
+  if (!x || !y || !dtype_ok(dtype) || !al16({x, y})) return ACC_EINVAL;
+  return status(maxpool_forward(x, y, n, h, wd, c, r, r, stride, pad, dtype, (hipStream_t)stream));
+}
+
+extern "C" int acc_op_maxpool_bwd(const void* x, const void* dy, void* dx, int n, int h, int wd, int c, int r,
+                                  int stride, int pad, int accumulate, int dtype, void* stream) {
+  if (!x || !dy || !dx || !dtype_ok(dtype) || !al16({x, dy, dx})) return ACC_EINVAL;
+  return status(maxpool_backward(x, dy, dx, n, h, wd, c, r, r, stride, pad, accumulate, dtype, (hipStream_t)stream));
+}
+
+extern "C" int acc_op_gap_fwd(const void* x, void* y, int n, int hw, int c, int dtype, void* stream) {
+  if (!x || !y || !dtype_ok(dtype)) return ACC_EINVAL;
+  return status(gap_forward(x, y, n, hw, c, dtype, (hipStream_t)stream));
+}
+
+extern "C" int acc_op_gap_bwd(const void* dy, void* dx, int n, int hw, int c, int accumulate, int dtype, void* stream) {
+  if (!dy || !dx || !dtype_ok(dtype)) return ACC_EINVAL;
+  return status(gap_backward(dy, dx, n, hw, c, accumulate, dtype, (hipStream_t)stream));
+}
+
+extern "C" int acc_op_softmax_ce(const void* z, const int32_t* labels, float* loss_rows, float* loss, void* dz, int n,
+                                 int classes, int dtype, void* stream) {
+  if (!z || !labels || !dtype_ok(dtype) || n <= 0 || classes <= 0 || (!loss_rows && !dz) || (loss_rows && !loss))
+    return ACC_EINVAL;
+  hipError_t e = hipSuccess;
+  if (loss_rows) e = softmax_ce_forward(z, labels, loss_rows, loss, n, classes, dtype, (hipStream_t)stream);
+  if (e == hipSuccess && dz) e = softmax_ce_backward(z, labels, dz, n, classes, dtype, (hipStream_t)stream);
+  return status(e);
+}

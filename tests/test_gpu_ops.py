@@ -136,6 +136,85 @@ def test_conv_wgrad(case):
     close(oihw(dw.cpu().numpy()), ref, f"conv_wgrad {case}")
 
 
+POOL_CASES = [  # n, c, h, w, r, stride, pad
+    (2, 64, 16, 16, 3, 2, 1),
+    (3, 12, 15, 13, 3, 2, 1),       # odd sizes: ragged last windows, channels not a multiple of 32
+    (2, 8, 8, 8, 2, 2, 0),          # VGG's pool: windows do not overlap
+    (2, 16, 9, 9, 3, 1, 1),         # stride 1: every position in up to nine windows
+    (41, 64, 112, 112, 3, 2, 1),    # the stem's pool at the benchmark minibatch
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+def test_maxpool_fwd_bwd(case):
+    """Forward: the same maxima, bit for bit.  Backward: the gradient goes to the first maximum of every
+    window in row-major order (the oracle's rule); a position that wins several windows adds their
+    gradients, in an order of its own, hence a tolerance.  The input is rounded to multiples of 1/4 so
+    that windows do hold equal values and the tie rule is exercised."""
+    n, c, h, w, r, stride, pad = case
+    x = np.round(rnd(11, n, c, h, w) * 4) / np.float32(4)
+    y_ref, arg = O.maxpool_fwd(x, r, stride, pad)
+    dy = rnd(12, *y_ref.shape)
+    dx_ref = O.maxpool_bwd(dy, arg, x.shape)
+    b = B()
+    xd = dev(nhwc(x))
+    y = torch.full((n, y_ref.shape[2], y_ref.shape[3], c), float("nan"), device="cuda")
+    b.op_maxpool_fwd(xd, y, r, stride, pad)
+    dx = torch.full((n, h, w, c), float("nan"), device="cuda")
+    b.op_maxpool_bwd(xd, dev(nhwc(dy)), dx, r, stride, pad)
+    base = rnd(13, n, c, h, w)
+    dxa = dev(nhwc(base))
+    b.op_maxpool_bwd(xd, dev(nhwc(dy)), dxa, r, stride, pad, accumulate=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(nchw(y.cpu().numpy()), y_ref), f"maxpool_fwd {case}"
+    close(nchw(dx.cpu().numpy()), dx_ref, f"maxpool_bwd {case}", 1e-6)
+    close(nchw(dxa.cpu().numpy()), dx_ref.astype(np.float64) + base, f"maxpool_bwd accumulate {case}", 1e-6)
+
+
+@pytest.mark.parametrize("case", [(41, 2048, 7, 7), (3, 20, 5, 3), (2, 64, 1, 1)])
+def test_gap_fwd_bwd(case):
+    n, c, h, w = case
+    x = rnd(14, n, c, h, w)
+    y_ref = O.gap_fwd(x)
+    dy = rnd(15, n, c)
+    dx_ref = O.gap_bwd(dy, x.shape)
+    b = B()
+    y = torch.full((n, c), float("nan"), device="cuda")
+    b.op_gap_fwd(dev(nhwc(x)), y)
+    dx = torch.full((n, h, w, c), float("nan"), device="cuda")
+    b.op_gap_bwd(dev(dy), dx)
+    torch.cuda.synchronize()
+    close(y.cpu().numpy(), y_ref, f"gap_fwd {case}")
+    close(nchw(dx.cpu().numpy()), dx_ref, f"gap_bwd {case}")
+
+
+@pytest.mark.parametrize("case", [(41, 1000), (3, 10), (1, 7), (300, 1000)])
+def test_softmax_ce(case):
+    """Loss and gradient against the oracle; logits scaled so that exp() of the unshifted values would
+    overflow in fp32 (the maximum is subtracted first); zero logits give ln(classes)."""
+    # (the gradient is held to 1e-4 per tensor like every other operation)
+    n, classes = case
+    z = rnd(16, n, classes) * np.float32(40.0)
+    lab = S.labels_uniform(17, n, classes)
+    loss_ref, dz_ref = O.softmax_ce(z, lab)
+    b = B()
+    zd, ld = dev(z), dev(lab)
+    rows = torch.full((n,), float("nan"), device="cuda")
+    loss = torch.full((1,), float("nan"), device="cuda")
+    dz = torch.full((n, classes), float("nan"), device="cuda")
+    b.op_softmax_ce(zd, ld, rows, loss, dz)
+    zeros = torch.zeros((n, classes), device="cuda")
+    loss0 = torch.full((1,), float("nan"), device="cuda")
+    b.op_softmax_ce(zeros, ld, rows.clone(), loss0, None)
+    torch.cuda.synchronize()
+    # (the kernel works relative to the row maximum, so the loss keeps its digits even where it is the small
+    # difference of two large logits: the (1, 7) case, loss 1.7e-3 beside logits of 70)
+    close(loss.cpu().numpy(), np.array([loss_ref], np.float32), f"softmax_ce loss {case}", 1e-5)
+    close(dz.cpu().numpy(), dz_ref, f"softmax_ce dz {case}")
+    assert abs(float(loss0.item()) - np.log(classes)) <= 1e-6 * np.log(classes)
+    assert abs(float(dz.sum().item())) < 1e-5          # every row of the gradient sums to zero
+
+
 BN_CASES = [  # n, c, h, w
     (2, 16, 16, 16),
     (3, 64, 7, 9),
