@@ -54,6 +54,41 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(b.EXPORTED_SYMBOLS), declared ^ set(b.EXPORTED_SYMBOLS)
 
 
+def test_single_operations_refuse_bad_arguments_before_any_launch():
+    """Every acc_op_* call checks its arguments on the host and returns ACC_EINVAL without launching anything:
+    null and misaligned pointers, an unknown storage type, shapes the kernels do not take, sizes beyond
+    their 32-bit index ranges.  (No GPU is needed for a call that must not reach one; the pointers are
+    made-up addresses that nothing dereferences.)"""
+    b = B()
+    L = b.lib()
+    P, Q, R = 0x10000, 0x20000, 0x30000          # 16-byte aligned, never dereferenced
+    E = b.ACC_EINVAL
+    conv = lambda x=P, w=Q, y=R, n=2, h=8, wd=8, cin=32, cout=32, r=3, s=3, st=1, pad=1, dt=b.F32: \
+        L.acc_op_conv_fwd(x, w, y, n, h, wd, cin, cout, r, s, st, pad, dt, None)
+    assert conv(x=None) == E and conv(w=None) == E and conv(y=None) == E
+    assert conv(x=P + 8) == E                    # 16 bytes at a time
+    assert conv(dt=7) == E
+    assert conv(s=1) == E                        # square filters only
+    assert conv(pad=3) == E and conv(st=0) == E and conv(n=0) == E and conv(h=1, wd=1, pad=0) == E
+    assert conv(n=65536, h=256, wd=256) == E     # 2^32 output positions: beyond the kernels' row index
+    assert L.acc_op_conv_dgrad(P, Q, R, 2, 8, 8, 32, 32, 3, 3, 1, 1, 0, None, 0, b.F32, None) == E   # needs its workspace
+    assert L.acc_op_conv_wgrad(P, Q, R + 4, 2, 8, 8, 32, 32, 3, 3, 1, 1, None, 0, b.F32, None) == E
+    bn = lambda x=P, rows=64, c=32, ws=R, dt=b.F32: L.acc_op_bn_fwd(x, Q, Q, None, P, Q, Q, rows, c, 1, 1e-5, ws, dt, None)
+    assert bn(x=None) == E and bn(ws=None) == E and bn(rows=0) == E and bn(c=30) == E and bn(dt=-1) == E
+    assert L.acc_op_bn_bwd(P, Q, None, Q, Q, Q, P, Q, Q, None, 64, 6, R, b.F32, None) == E
+    assert L.acc_op_bn_fwd_noalloc(P, Q, Q, None, P, Q, Q, 64, 2048 + 4, 1, 1e-5, b.F32, None) == E
+    assert b"ACC_NOALLOC_BN_MAX_C" in L.acc_last_error(None)
+    pool = lambda x=P, c=8, r=3, st=2, pad=1, dt=b.F32: L.acc_op_maxpool_fwd(x, Q, 2, 8, 8, c, r, st, pad, dt, None)
+    assert pool(x=None) == E and pool(c=6) == E and pool(pad=3) == E and pool(st=0) == E and pool(dt=9) == E
+    assert L.acc_op_maxpool_bwd(P, None, R, 2, 8, 8, 8, 3, 2, 1, 0, b.F32, None) == E
+    assert L.acc_op_gap_fwd(P, None, 2, 49, 64, b.F32, None) == E and L.acc_op_gap_fwd(P, Q, 2, 0, 64, b.F32, None) == E
+    assert L.acc_op_gap_bwd(None, Q, 2, 49, 64, 0, b.F32, None) == E
+    assert L.acc_op_softmax_ce(P, Q, None, None, None, 4, 10, b.F32, None) == E       # nothing asked for
+    assert L.acc_op_softmax_ce(P, Q, R, None, None, 4, 10, b.F32, None) == E          # rows without the mean
+    assert L.acc_op_softmax_ce(P, None, R, R, None, 4, 10, b.F32, None) == E
+    assert L.acc_op_softmax_ce(P, Q, R, R, None, 0, 10, b.F32, None) == E
+
+
 def test_execution_without_resources_fails_loudly():
     b = B()
     net = S.bottleneck_unit()
