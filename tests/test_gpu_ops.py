@@ -69,6 +69,10 @@ CONV_CASES = [  # n, h, w, cin, cout, r, stride, pad
     (2, 23, 23, 8, 16, 7, 2, 3),       # stem-like filter
     (8, 57, 55, 64, 256, 1, 1, 0),     # 1x1 expansion: 392 row tiles (ragged M) x 4, two chunks each
     (8, 57, 55, 256, 64, 1, 1, 0),     # 1x1 reduction: eight chunks; its data gradient is the expansion
+    (16, 32, 32, 256, 64, 1, 1, 0),    # exactly 256 tiles of eight chunks: the last launch shape of the two-group kernel
+    (1, 128, 129, 256, 64, 1, 1, 0),   # 258 tiles: the first one beyond it
+    (2, 8, 8, 224, 64, 1, 1, 0),       # seven chunks: too short for two groups
+    (2, 9, 7, 288, 40, 1, 1, 0),       # nine chunks in two groups (5 + 4), ragged rows and columns
 ]
 
 
@@ -241,6 +245,29 @@ def test_bn_full_size(case, variant):
     small ones, whose finishing pass runs inside the apply launch (256 slabs: two batches of
     partial loads per workgroup; 2048 channels: 64 column slices)."""
     bn_case(case, variant)
+
+
+def _bn_sweep():
+    """Seeded shapes around the boundaries of the batch-norm launch shapes: rows (n*h*w) below and above one
+    trip of 128 rows per workgroup, around 32-row and 512-row multiples (the number of partial sums, where the
+    finishing pass moves into the apply launch and where it does not), channel counts that fill a 32-channel
+    slice partly, exactly, and several times."""
+    rows = [1, 2, 31, 33, 127, 129, 500, 2047, 2049, 8191, 8193, 16383, 16385, 20001]
+    chans = [4, 8, 28, 32, 36, 60, 64, 100, 256, 260]
+    u = S.splitmix64(31, 0, 2 * len(rows))
+    out = []
+    for i, r in enumerate(rows):
+        c = chans[int(u[2 * i] % len(chans))]
+        h = [1, 3, 7][int(u[2 * i + 1] % 3)]
+        if r % h:
+            h = 1
+        out.append((r // h, c, h, 1, ["plain", "relu", "add_relu"][i % 3]))
+    return out
+
+
+@pytest.mark.parametrize("n,c,h,w,variant", _bn_sweep())
+def test_bn_shape_sweep(n, c, h, w, variant):
+    bn_case((n, c, h, w), variant)
 
 
 def bn_case(case, variant):
